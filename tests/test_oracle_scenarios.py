@@ -1,0 +1,216 @@
+"""Scripted scenarios, one rule each, on stacked walls.  Expected values follow from the rule text."""
+import numpy as np
+
+from oracle import mjo
+from tests.scenario import (A_CHI_H, A_CHI_L, A_CHI_M, A_KAN, A_PASS, A_PON, A_RIICHI, A_RON, A_TSUMO, A_KYUUSHU,
+                            A_MINKAN, J1, J2, J3, act, bits, build_wall, kind)
+from tests.invariants import check_env
+
+TENPAI = "234m 34p 456p 22s 678s"          # waits 2p / 5p; pinfu + tanyao
+TENPAI2 = "234m 34p 678p 33s 678s"         # the same waits from different tiles
+
+
+def engine(flags=mjo.RULES_NORED, mode=mjo.MODE_SINGLE, **kw):
+    return mjo.Oracle(1, seed=0, flags=flags, mode=mode, **kw)
+
+
+def test_tenhou():
+    o = engine()
+    o.deal_from_wall(0, build_wall([TENPAI, J1, J2, J3], draws="5p", dora="1z"))
+    e = o.export()[0]
+    assert bits(e["mask"][0]).count(A_TSUMO) == 1 and A_RIICHI in bits(e["mask"][0])
+    e = act(o, 0, {0: A_TSUMO})
+    assert e["end_type"] == 1 and e["winners"] == 1 and e["yakuman_units"][0] == 1 and e["yaku"][0] == 1 << 42
+    assert e["delta"].tolist() == [48000, -16000, -16000, -16000] and e["terminated"] == 1
+    assert e["final_rank"].tolist() == [0, 1, 2, 3] and e["gain"][0] == 48000
+
+
+def test_double_ron_honba_sticks_and_rotation():
+    o = engine(mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, TENPAI2, J3], draws="1m", dora="1z"))
+    e = o.export()
+    e["honba"], e["kyotaku"] = 2, 1
+    e["score"][0] = [25000, 25000, 25000, 24000]
+    o.import_(e)
+    e = act(o, 0, {0: kind("5p")})
+    assert e["phase"] == 1 and e["actor_mask"] == 0b0110
+    assert bits(e["mask"][1]) == [A_RON, A_CHI_M, A_CHI_H, A_PASS]       # next seat may also chi with 4p6p / 3p4p
+    assert bits(e["mask"][2]) == [A_RON, A_PASS]
+    e = act(o, 0, {1: A_RON, 2: A_RON})
+    assert e["end_type"] == 2 and e["winners"] == 0b0110 and e["loser"] == 0
+    assert e["han"].tolist() == [0, 2, 2, 0] and e["fu"].tolist() == [0, 30, 30, 0]
+    # 2000 + 2 honba * 300 each; the stick goes to seat 1, the first after the loser
+    assert e["delta"].tolist() == [-5200, 3600, 2600, 0] and e["gain"].tolist() == [0, 3600, 2600, 0]
+    assert e["kyoku"] == 1 and e["honba"] == 0 and e["kyotaku"] == 0 and e["kyoku_serial"] == 1
+    assert e["cur"] == 1 and e["phase"] == 0 and e["terminated"] == 0       # next kyoku dealt in the same step
+    check_env(e, mjo.RULES_NORED)
+
+
+def test_pon_beats_chi_and_kuikae():
+    o = engine()
+    hands = [J1, "4567m258p369s567z", "44m 369p147s456z 11p", J3]
+    o.deal_from_wall(0, build_wall(hands, draws="1m"))
+    e = act(o, 0, {0: kind("4m")})
+    assert e["actor_mask"] == 0b0110
+    assert bits(e["mask"][1]) == [A_CHI_L, A_PASS] and bits(e["mask"][2]) == [A_PON, A_PASS]
+    e = act(o, 0, {1: A_CHI_L, 2: A_PON})
+    assert e["cur"] == 2 and e["phase"] == 0 and e["n_meld"].tolist() == [0, 0, 1, 0]
+    m = int(e["meld"][2][0])
+    assert m & 7 == 2 and (m >> 3) & 63 == kind("4m") and (m >> 9) & 3 == 2       # pon, taken from the seat across
+    assert e["river"][0][0] == kind("4m") | 0x80 and e["drawn"] == 255
+    legal = bits(e["mask"][2])
+    assert kind("4m") not in legal and A_TSUMO not in legal and all(a < 34 for a in legal)
+    assert (e["first_turn"] == 0).all()
+    # now the chi alone: forbidden are the called kind and the kind three above it
+    o.deal_from_wall(0, build_wall([J1, hands[1], J2, J3], draws="1m"))
+    e = act(o, 0, {0: kind("4m")})
+    assert e["actor_mask"] == 0b0010
+    e = act(o, 0, {1: A_CHI_L})
+    m = int(e["meld"][1][0])
+    assert m & 7 == 1 and (m >> 3) & 63 == kind("4m") and (m >> 9) & 3 == 3 and (m >> 11) & 3 == 0
+    legal = bits(e["mask"][1])
+    assert kind("4m") not in legal and kind("7m") not in legal and kind("2p") in legal
+    assert e["kuikae"].tolist() == [kind("4m"), kind("7m")]
+    e = act(o, 0, {1: kind("2p")})
+    assert e["kuikae"].tolist() == [255, 255] and e["cur"] == 2
+
+
+def test_furiten_permanent_and_temporary():
+    # own discard among the waits: no ron
+    o = engine()
+    o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, J2, J3], draws="1m"))
+    e = o.export()
+    e["discarded_kinds"][0][1] = 1 << kind("2p")
+    o.import_(e)
+    e = act(o, 0, {0: kind("5p")})
+    assert A_RON not in bits(e["mask"][1]) and e["furiten_temp"][1] == 1
+    # passing a ron: furiten until the own next discard
+    o = engine()
+    hands = ["5p " + J1[1:], TENPAI, "2p 58m369p147s4567z", J3]
+    o.deal_from_wall(0, build_wall(hands, draws="1m 9m 9m 9s 1s"))
+    e = act(o, 0, {0: kind("5p")})
+    assert A_RON in bits(e["mask"][1])
+    e = act(o, 0, {1: A_PASS})
+    assert e["furiten_temp"][1] == 1 and e["cur"] == 1
+    e = act(o, 0, {1: kind("9m")})
+    assert e["furiten_temp"][1] == 0
+    e = act(o, 0, {2: kind("9m")})                       # seat 2 cuts its draw; nobody can call it
+    e = act(o, 0, {3: kind("9s")})
+    e = act(o, 0, {0: kind("2p")})
+    assert A_RON in bits(e["mask"][1])                     # the temporary furiten is over
+
+
+def test_temporary_furiten_blocks_same_go_around():
+    o = engine()
+    hands = ["5p " + J1[1:], J3, "2p 58m369p147s4567z", TENPAI]
+    # seat 3 waits on 2p/5p; seat 0 cuts 5p (seat 3 passes), then seat 2 cuts 2p in the same go-around
+    o.deal_from_wall(0, build_wall(hands, draws="1m 9m 9m"))
+    e = act(o, 0, {0: kind("5p")})
+    assert e["actor_mask"] == 0b1000
+    e = act(o, 0, {3: A_PASS})
+    assert e["furiten_temp"][3] == 1
+    e = act(o, 0, {1: kind("9m")})
+    e = act(o, 0, {2: kind("2p")})
+    assert bits(e["mask"][3]) == [A_CHI_L, A_PASS]               # the shape fits, but no ron in the same go-around
+
+
+def test_riichi_ippatsu_tsumo_ura():
+    o = engine()
+    o.deal_from_wall(0, build_wall([TENPAI, J1, J2, J3], draws="6p 5z 6z 7z 5p", dora="1z", ura="1s"))
+    e = o.export()[0]
+    assert A_RIICHI in bits(e["mask"][0])
+    e = act(o, 0, {0: A_RIICHI})
+    assert e["riichi_pending"] == 2 and e["cur"] == 0
+    assert bits(e["mask"][0]) == [kind("3p"), kind("4p"), kind("6p")]
+    e = act(o, 0, {0: kind("6p")})
+    assert e["riichi"][0] == 2 and e["ippatsu"][0] == 1 and e["score"][0] == 24000 and e["kyotaku"] == 1
+    assert e["riichi_idx"][0] == 0 and e["riichi_pending"] == 0 and e["delta"][0] == -1000
+    e = act(o, 0, {1: kind("5z")})
+    e = act(o, 0, {2: kind("6z")})
+    e = act(o, 0, {3: kind("7z")})
+    assert bits(e["mask"][0]) == [kind("5p"), A_TSUMO]
+    e = act(o, 0, {0: A_TSUMO})
+    want = (1 << 1) | (1 << 2) | (1 << 3) | (1 << 4) | (1 << 5)        # double riichi, ippatsu, tsumo, pinfu, tanyao
+    assert e["yaku"][0] == want and e["han"][0] == 8 and e["fu"][0] == 20 and e["r_ura"][0] == 2
+    assert e["delta"].tolist() == [25000, -8000, -8000, -8000] and e["score"][0] == 49000
+
+
+def test_riichi_discard_ronned_keeps_the_stick():
+    o = engine()
+    o.deal_from_wall(0, build_wall(["234m 34p 456p 22s 67s 5p", TENPAI2, J2, J3], draws="8s", dora="1z"))
+    # seat 0: tenpai after cutting 5p (waits 2p/5p itself would be furiten, irrelevant); seat 1 wins on it
+    e = act(o, 0, {0: A_RIICHI})
+    assert kind("5p") in bits(e["mask"][0])
+    e = act(o, 0, {0: kind("5p")})
+    assert e["phase"] == 1 and e["riichi"][0] == 0 and e["score"][0] == 25000
+    e = act(o, 0, {1: A_RON})
+    assert e["kyotaku"] == 0 and e["delta"].tolist() == [-2000, 2000, 0, 0] and e["riichi"][0] == 0
+
+
+def test_kakan_robbed():
+    o = engine()
+    hands = ["55p 147m 28p 369s 123z", "5p 258m 39p 147s 1247z", "234m 46p 456s 22s 678s", J3]
+    o2 = engine()
+    o2.deal_from_wall(0, build_wall(hands, draws="4z 9m 7z 6z 5z 5p", dora="1z"))
+    act(o2, 0, {0: kind("4z")}); act(o2, 0, {1: kind("5p")}); act(o2, 0, {0: A_PON, 2: A_PASS})
+    act(o2, 0, {0: kind("1m")}); act(o2, 0, {1: kind("7z")}); act(o2, 0, {2: kind("6z")})
+    e = act(o2, 0, {3: kind("5z")})
+    assert e["cur"] == 0 and e["drawn"] == kind("5p") and A_KAN + kind("5p") in bits(e["mask"][0])
+    e = act(o2, 0, {0: A_KAN + kind("5p")})
+    assert e["phase"] == 2 and e["actor_mask"] == 0b0100 and bits(e["mask"][2]) == [A_RON, A_PASS]
+    assert int(e["meld"][0][0]) & 7 == 5 and e["kakan_tile"] == kind("5p") and e["n_kan"] == 0
+    e = act(o2, 0, {2: A_RON})
+    assert e["end_type"] == 2 and e["loser"] == 0 and e["n_kan"] == 0 and e["n_dora"] == 1
+    assert e["yaku"][2] == (1 << 13) | (1 << 5) and e["han"][2] == 2 and e["fu"][2] == 40     # chankan + tanyao, closed wait
+    assert e["delta"].tolist() == [-2600, 0, 2600, 0]
+
+
+def test_ankan_rinshan_and_new_dora():
+    o = engine()
+    hands = ["111m 34p 456p 22s 678s", "47m258p369s1234z9m", J2, J3]
+    o.deal_from_wall(0, build_wall(hands, draws="1m", rinshan="5p", dora="1z 1s"))
+    e = o.export()[0]
+    assert A_KAN + kind("1m") in bits(e["mask"][0])
+    e = act(o, 0, {0: A_KAN + kind("1m")})
+    assert e["n_kan"] == 1 and e["n_dora"] == 2 and e["rinshan"] == 1 and e["live_left"] == 68 and e["kan_by"][0] == 1
+    assert int(e["meld"][0][0]) & 7 == 4 and (e["first_turn"] == 0).all()
+    assert A_TSUMO in bits(e["mask"][0])
+    e = act(o, 0, {0: A_TSUMO})
+    # tsumo 1 + rinshan 1 + dora 2 (second indicator 1s -> 2s pair); fu 20 + 2 + 32 (concealed terminal kan) = 54 -> 60
+    # 60 fu 4 han is over the 2000 cap: mangan, the dealer takes 4000 from each
+    assert e["yaku"][0] == (1 << 3) | (1 << 12) and e["han"][0] == 4 and e["fu"][0] == 60 and e["r_dora"][0] == 2
+    assert e["delta"].tolist() == [12000, -4000, -4000, -4000]
+
+
+def test_abortive_draws():
+    flags = mjo.RULES_NORED | mjo.F_ABORT
+    o = engine(flags=flags, mode=mjo.MODE_HALF)
+    h = lambda base: "1z " + base
+    o.deal_from_wall(0, build_wall([h("47m258p369s234z1m"), h("58m369p147s567z2m"), h("69m147p258s235z3m"),
+                                    h("19m19p19s4567z23s")], draws="9m 9p 9s 8m"))
+    e = None
+    for s in range(4):
+        e = act(o, 0, {s: kind("1z")})
+    assert e["end_type"] == 5 and e["honba"] == 1 and e["kyoku"] == 0 and e["kyoku_serial"] == 1 and (e["delta"] == 0).all()
+    # nine different terminals and honors on the first draw
+    o.deal_from_wall(0, build_wall(["19m19p19s123z 2345m", J1, J2, J3], draws="4z"))
+    e = o.export()[0]
+    assert A_KYUUSHU in bits(e["mask"][0])
+    e = act(o, 0, {0: A_KYUUSHU})
+    assert e["end_type"] == 4 and e["honba"] == 2 and e["kyoku"] == 0
+    # without the flag the option does not exist
+    o = engine()
+    o.deal_from_wall(0, build_wall(["19m19p19s123z 2345m", J1, J2, J3], draws="4z"))
+    assert A_KYUUSHU not in bits(o.export()[0]["mask"][0])
+
+
+def test_bust_ends_the_game():
+    o = engine(mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, J2, J3], draws="1m", dora="1z"))
+    e = o.export()
+    e["score"][0] = [1500, 48500, 25000, 25000]
+    o.import_(e)
+    act(o, 0, {0: kind("5p")})
+    e = act(o, 0, {1: A_RON})
+    assert e["score"].tolist() == [-500, 50500, 25000, 25000] and e["terminated"] == 1 and e["kyoku"] == 0
+    assert e["final_rank"].tolist() == [3, 0, 1, 2]
