@@ -1,0 +1,600 @@
+// Per-environment logic of the batched Riichi Mahjong step, written for one
+// GPU lane per environment (gfx950).  Every function is MJ_HD so that the same
+// source also compiles for the host, where the test-only host build runs it
+// under a debugger or sanitizer; the product only ever runs it inside the HIP
+// kernels of mj_lib.hip.
+//
+// What is computed follows the paper's environment (section 3.1: State, init,
+// step; section 3.2: rules, modes, action ids, legal_action_mask, illegal
+// action => termination; section 4.1: random policy).  How it is computed is
+// this library's own design:
+//   - hands are four words per seat of 3-bit packed counts (three suits, honors);
+//   - win detection looks each suit word up in a two-level table of all valid
+//     suit patterns (prefix -> shared row -> suffix bitmap, in LDS), honors by
+//     bit arithmetic;
+//   - scoring turns decomposition records into bit masks (triplet kinds, packed
+//     run multiplicities) so every yaku and the fu are mask / popcount tests;
+//   - waits of every seat are cached as 34-bit masks and refreshed only when
+//     that seat's concealed hand changes.
+#pragma once
+#include <stdint.h>
+
+#ifndef MJ_HD
+#define MJ_HD __host__ __device__ __forceinline__
+#endif
+#ifndef MJ_HD_NOINLINE
+#define MJ_HD_NOINLINE __host__ __device__ __attribute__((noinline))
+#endif
+
+namespace mj {
+
+// ---------------------------------------------------------------- constants
+enum { F_RED = 1, F_ABORT = 2, F_KUITAN = 4 };
+enum { PH_TURN = 0, PH_RESPOND = 1, PH_RESPOND_KAKAN = 2, PH_TERMINAL = 3 };
+enum { A_DISCARD = 0, A_DISCARD_RED = 34, A_KAN = 37, A_RIICHI = 71, A_TSUMO = 72, A_KYUUSHU = 73, A_RON = 74,
+       A_PON = 75, A_PON_RED = 76, A_MINKAN = 77, A_CHI_L = 78, A_CHI_L_RED = 81, A_PASS = 84, N_ACTIONS = 85 };
+enum { MT_CHI = 1, MT_PON = 2, MT_MINKAN = 3, MT_ANKAN = 4, MT_KAKAN = 5 };
+
+constexpr uint64_t K_TERMINALS = 0x4060301ull;                       // kinds 0,8,9,17,18,26
+constexpr uint64_t K_HONORS = 0x7Full << 27;
+constexpr uint64_t K_YAOCHU = K_TERMINALS | K_HONORS;
+constexpr uint64_t K_WINDS = 0xFull << 27;
+constexpr uint64_t K_DRAGONS = 0x7ull << 31;
+constexpr uint64_t K_ALL = (1ull << 34) - 1;
+constexpr uint32_t O111 = 0111111111u;                               // bit 0 of each of nine 3-bit fields
+
+struct Rules {
+  uint32_t flags, env_id_base;
+  int32_t start_score;
+  float illegal_penalty;
+  uint32_t mode;
+  uint32_t seed;
+};
+
+// the per-suit pattern table: probe part (LDS) and record part (global memory)
+struct Lut {
+  const uint8_t *rowid;      // [3125] row of a prefix
+  const uint32_t *bitmap;    // [rows][20] valid suffixes of a row
+  const uint16_t *base;      // [3125] keys before this prefix
+  const uint16_t *rowrank;   // [rows][20] set bits before each word
+  const uint32_t *keyinfo;   // [keys] first record | count << 16
+  const uint32_t *recs;
+};
+
+// One environment's view of the structure-of-arrays state: element i of a
+// field lives at ptr[i * n].  (n = B and ptr = base + b for state in HBM.)
+struct Env {
+  int64_t n;
+  uint64_t *dk, *waits, *mask, *yaku, *meld, *resw;   // [4] [4] [8] [4] [4] [4]
+  int32_t *score, *delta, *gain;                      // [4] each
+  uint32_t *episode, *serial, *hand, *seatw, *glob;   // [1] [1] [16] [4] [7]
+  uint8_t *wall, *river;                              // [136] [128]
+};
+
+// control bytes kept in registers during a step (7 words in HBM)
+struct Glob {
+  uint8_t kyoku, honba, kyotaku, terminated;
+  uint8_t draw_ptr, n_kan, live_left, n_dora;
+  uint8_t drawn, phase, cur, actor_mask;
+  uint8_t riichi_pending, rinshan, last_discard, last_discarder;
+  uint8_t kakan_tile, kuikae0, kuikae1, first_wind;
+  uint8_t same_wind_cnt, illegal_seat, end_type, winners;
+  uint8_t loser, tenpai_mask, pad0, pad1;
+};
+union GlobU { Glob g; uint32_t w[7]; };
+
+// per-seat control word
+//  0-2 hand_red | 3-5 n_meld | 6-11 n_river | 12-19 riichi_idx | 20-21 riichi | 22 ippatsu | 23 first_turn
+//  24 furiten_temp | 25 furiten_riichi | 26-28 kan_by | 29-30 final_rank
+enum { SW_RED = 0, SW_NMELD = 3, SW_NRIVER = 6, SW_RIDX = 12, SW_RIICHI = 20, SW_IPPATSU = 22, SW_FIRST = 23,
+       SW_FTEMP = 24, SW_FRIICHI = 25, SW_KANBY = 26, SW_RANK = 29 };
+MJ_HD uint32_t sw_get(uint32_t w, int pos, int bits) { return (w >> pos) & ((1u << bits) - 1); }
+MJ_HD uint32_t sw_set(uint32_t w, int pos, int bits, uint32_t v) { return (w & ~(((1u << bits) - 1) << pos)) | (v << pos); }
+
+// ------------------------------------------------------------------ helpers
+MJ_HD int popc32(uint32_t x) { return __builtin_popcount(x); }
+MJ_HD int popc64(uint64_t x) { return __builtin_popcountll(x); }
+MJ_HD int ctz64(uint64_t x) { return __builtin_ctzll(x); }
+MJ_HD uint32_t mulhi(uint32_t a, uint32_t b) { return (uint32_t)(((uint64_t)a * b) >> 32); }
+MJ_HD int suit_of(int k) { return k >= 27 ? 3 : k >= 18 ? 2 : k >= 9 ? 1 : 0; }
+MJ_HD int rank_of(int k, int su) { return k - 9 * su; }
+MJ_HD bool is_five(int k) { return k == 4 || k == 13 || k == 22; }
+MJ_HD int cnt3(uint32_t w, int r) { return (int)((w >> (3 * r)) & 7u); }
+MJ_HD uint64_t kbit(int k) { return 1ull << k; }
+MJ_HD int code_kind(int c) { return c & 63; }
+MJ_HD int code_red(int c) { return (c >> 6) & 1; }
+
+MJ_HD int m_type(uint32_t m) { return (int)(m & 7); }
+MJ_HD int m_kind(uint32_t m) { return (int)((m >> 3) & 63); }
+MJ_HD uint32_t m_make(int type, int kind, int from_rel, int pos, int has_red, int called_red)
+{
+  return (uint32_t)(type | kind << 3 | from_rel << 9 | pos << 11 | has_red << 13 | called_red << 14);
+}
+MJ_HD uint32_t meld_at(uint64_t mw, int j) { return (uint32_t)(mw >> (16 * j)) & 0xFFFFu; }
+
+// Philox4x32-10 (Salmon et al., SC'11)
+MJ_HD void philox(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1, uint32_t out[4])
+{
+#pragma unroll
+  for (int i = 0; i < 10; i++) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1; c3 = (uint32_t)p0; c0 = n0; c2 = n2;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// ------------------------------------------------------------ suit patterns
+MJ_HD uint32_t prefix5(uint32_t w) { return cnt3(w, 0) + 5 * cnt3(w, 1) + 25 * cnt3(w, 2) + 125 * cnt3(w, 3) + 625 * cnt3(w, 4); }
+MJ_HD uint32_t suffix5(uint32_t w) { return cnt3(w, 5) + 5 * cnt3(w, 6) + 25 * cnt3(w, 7) + 125 * cnt3(w, 8); }
+// is the suit word (counts 0..4) a valid pattern?  Two dependent LDS reads.
+MJ_HD bool lut_valid(const Lut &L, uint32_t w)
+{
+  uint32_t s = suffix5(w);
+  uint32_t row = L.rowid[prefix5(w)];
+  return (L.bitmap[row * 20 + (s >> 5)] >> (s & 31)) & 1u;
+}
+// records of a suit word: count (0 = not valid) and the index of the first one
+MJ_HD int lut_records(const Lut &L, uint32_t w, uint32_t *first)
+{
+  uint32_t p = prefix5(w), s = suffix5(w);
+  uint32_t row = L.rowid[p];
+  uint32_t word = L.bitmap[row * 20 + (s >> 5)];
+  *first = 0;
+  if (!((word >> (s & 31)) & 1u)) return 0;
+  uint32_t key = (uint32_t)L.base[p] + L.rowrank[row * 20 + (s >> 5)] + (uint32_t)popc32(word & ((1u << (s & 31)) - 1u));
+  uint32_t info = L.keyinfo[key];
+  *first = info & 0xFFFFu;
+  return (int)(info >> 16);
+}
+
+MJ_HD int tiles_in(uint32_t w)      // sum of the nine 3-bit fields
+{
+  uint32_t a = (w & 0007007007u) + ((w >> 3) & 0007007007u) + ((w >> 6) & 0007007007u);   // three 9-bit sums
+  return (int)((a & 0x1FF) + ((a >> 9) & 0x1FF) + ((a >> 18) & 0x1FF));
+}
+// honors: valid when every count is 0 or 3, or exactly one is 2
+MJ_HD bool honors_valid(uint32_t w)
+{
+  uint32_t b0 = w & O111, b1 = (w >> 1) & O111, b2 = (w >> 2) & O111;
+  uint32_t one = b0 & ~b1 & ~b2, two = b1 & ~b0 & ~b2, four = b2;
+  return one == 0 && four == 0 && popc32(two) <= 1;
+}
+MJ_HD uint32_t fields_eq(uint32_t w, int v)   // bit 3r set where field r == v
+{
+  uint32_t b0 = w & O111, b1 = (w >> 1) & O111, b2 = (w >> 2) & O111;
+  uint32_t m0 = (v & 1) ? b0 : ~b0, m1 = (v & 2) ? b1 : ~b1, m2 = (v & 4) ? b2 : ~b2;
+  return m0 & m1 & m2 & O111;
+}
+MJ_HD uint32_t fields_nonzero(uint32_t w) { return (w | (w >> 1) | (w >> 2)) & O111; }
+// compress the bits at positions 0,3,6,... of nine fields into 9 consecutive bits
+MJ_HD uint32_t squeeze9(uint32_t m)
+{
+  uint32_t r = 0;
+#pragma unroll
+  for (int i = 0; i < 9; i++) r |= ((m >> (3 * i)) & 1u) << i;
+  return r;
+}
+
+// kinds (34-bit mask) of which the seat owns four, concealed and melds together
+MJ_HD int meld_count(uint32_t m, int k)
+{
+  int t = m_type(m), b = m_kind(m);
+  if (t == MT_CHI) return (k >= b && k <= b + 2) ? 1 : 0;
+  if (t == MT_PON) return k == b ? 3 : 0;
+  if (t >= MT_MINKAN) return k == b ? 4 : 0;
+  return 0;
+}
+MJ_HD int hand_count(const uint32_t h[4], int k) { int su = suit_of(k); return cnt3(h[su], rank_of(k, su)); }
+
+// Waits of a (13 - 3*n_meld)-tile hand: kinds whose addition completes it and
+// of which the seat owns fewer than four.
+MJ_HD_NOINLINE uint64_t waits_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
+{
+  uint32_t h[4] = {h0, h1, h2, h3};
+  uint64_t w = 0;
+  int n[4], r1 = 0, r2 = 0;
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    n[s] = tiles_in(h[s]);
+    int r = n[s] % 3;
+    r1 += r == 1; r2 += r == 2;
+  }
+  // standard form: one suit takes the tile, the others must already be valid
+  if ((r1 == 1 && r2 == 0) || (r1 == 0 && r2 == 2)) {
+    bool ok[4];
+#pragma unroll
+    for (int s = 0; s < 3; s++) ok[s] = (n[s] % 3 == 1) ? false : lut_valid(L, h[s]);
+    ok[3] = (n[3] % 3 == 1) ? false : honors_valid(h[3]);
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+      if (n[s] % 3 == 0) continue;                 // the tile goes to a suit with remainder 1 or 2
+      bool others = true;
+#pragma unroll
+      for (int o = 0; o < 4; o++) if (o != s) others = others && ok[o];
+      if (!others) continue;
+      if (s < 3) {
+        for (int r = 0; r < 9; r++) {
+          if (cnt3(h[s], r) >= 4) continue;
+          if (lut_valid(L, h[s] + (1u << (3 * r)))) w |= kbit(9 * s + r);
+        }
+      } else {
+        for (int r = 0; r < 7; r++) {
+          int c = cnt3(h[3], r);
+          if (c == 0 || c >= 3) continue;          // 0 -> 1 and 3 -> 4 never help
+          if (honors_valid(h[3] + (1u << (3 * r)))) w |= kbit(27 + r);
+        }
+      }
+    }
+  }
+  if (n_meld == 0) {
+    // seven pairs: six pairs and a single; thirteen orphans: twelve or thirteen different ones
+    uint32_t pairs = 0, singles = 0, other = 0;
+    uint64_t singles_k = 0, present = 0;
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+      uint32_t e1 = fields_eq(h[s], 1), e2 = fields_eq(h[s], 2), nz = fields_nonzero(h[s]);
+      pairs += popc32(e2); singles += popc32(e1); other += popc32(nz & ~e1 & ~e2);
+      singles_k |= (uint64_t)squeeze9(e1) << (9 * s);
+      present |= (uint64_t)squeeze9(nz) << (9 * s);
+    }
+    if (pairs == 6 && singles == 1 && other == 0) w |= singles_k;
+    if ((present & ~K_YAOCHU) == 0 && other == 0) {
+      int kinds = popc64(present);
+      if (kinds == 13 && pairs == 0) w |= K_YAOCHU;
+      else if (kinds == 12 && pairs == 1) w |= K_YAOCHU & ~present;
+    }
+  }
+  // drop kinds the seat already owns four of
+  uint64_t rest = w;
+  while (rest) {
+    int k = ctz64(rest);
+    rest &= rest - 1;
+    int own = hand_count(h, k);
+    for (int j = 0; j < n_meld; j++) own += meld_count(meld_at(meldw, j), k);
+    if (own >= 4) w &= ~kbit(k);
+  }
+  return w;
+}
+
+// --------------------------------------------------------------- evaluation
+struct HandIn {
+  uint32_t h[4];        // concealed, winning tile included
+  uint64_t meldw;
+  int n_meld, win, flags, riichi, seat_wind, round_wind, n_ind, n_aka, kuitan;
+  uint8_t ind[5], ura[5];
+};
+struct HandOut {
+  uint64_t yaku;
+  int32_t points;
+  int han, fu, units, shape_ok, yaku_ok, n_dora, n_ura, n_aka;
+};
+
+MJ_HD int32_t up100(int32_t x) { return (x + 99) / 100 * 100; }
+MJ_HD int32_t base_points(int han, int fu, int units)
+{
+  if (units > 0) return 8000 * units;
+  if (han >= 13) return 8000;
+  if (han >= 11) return 6000;
+  if (han >= 8) return 4000;
+  if (han >= 6) return 3000;
+  if (han >= 5) return 2000;
+  int32_t b = (int32_t)fu << (han + 2);
+  return b > 2000 ? 2000 : b;
+}
+MJ_HD int32_t total_points(int32_t base, bool dealer, bool tsumo)
+{
+  if (!tsumo) return up100(base * (dealer ? 6 : 4));
+  if (dealer) return 3 * up100(base * 2);
+  return up100(base * 2) + 2 * up100(base);
+}
+MJ_HD int dora_of(int k)
+{
+  if (k < 27) { int su = k / 9, r = k - 9 * su; return 9 * su + (r == 8 ? 0 : r + 1); }
+  if (k < 31) return k == 30 ? 27 : k + 1;
+  return k == 33 ? 31 : k + 1;
+}
+
+// yaku bit numbers
+enum { Y_RIICHI = 0, Y_DRIICHI, Y_IPPATSU, Y_TSUMO, Y_PINFU, Y_TANYAO, Y_IIPEIKOU, Y_HAKU, Y_HATSU, Y_CHUN, Y_SEATW,
+       Y_ROUNDW, Y_RINSHAN, Y_CHANKAN, Y_HAITEI, Y_HOUTEI, Y_CHIITOI, Y_SANSHOKU, Y_ITTSU, Y_CHANTA, Y_TOITOI,
+       Y_SANANKOU, Y_DOUKOU, Y_SANKANTSU, Y_HONROUTOU, Y_SHOUSANGEN, Y_HONITSU, Y_JUNCHAN, Y_RYANPEIKOU, Y_CHINITSU,
+       Y_KOKUSHI = 32, Y_SUUANKOU, Y_DAISANGEN, Y_SHOUSUUSHII, Y_DAISUUSHII, Y_TSUUIISOU, Y_CHINROUTOU, Y_RYUUIISOU,
+       Y_CHUUREN, Y_SUUKANTSU, Y_TENHOU, Y_CHIIHOU };
+#define YB(x) (1ull << (x))
+// han value classes, closed / open
+constexpr uint64_t HC1 = YB(Y_RIICHI) | YB(Y_IPPATSU) | YB(Y_TSUMO) | YB(Y_PINFU) | YB(Y_TANYAO) | YB(Y_IIPEIKOU) |
+                         YB(Y_HAKU) | YB(Y_HATSU) | YB(Y_CHUN) | YB(Y_SEATW) | YB(Y_ROUNDW) | YB(Y_RINSHAN) |
+                         YB(Y_CHANKAN) | YB(Y_HAITEI) | YB(Y_HOUTEI);
+constexpr uint64_t HC2 = YB(Y_DRIICHI) | YB(Y_CHIITOI) | YB(Y_SANSHOKU) | YB(Y_ITTSU) | YB(Y_CHANTA) | YB(Y_TOITOI) |
+                         YB(Y_SANANKOU) | YB(Y_DOUKOU) | YB(Y_SANKANTSU) | YB(Y_HONROUTOU) | YB(Y_SHOUSANGEN);
+constexpr uint64_t HC3 = YB(Y_HONITSU) | YB(Y_JUNCHAN) | YB(Y_RYANPEIKOU);
+constexpr uint64_t HC6 = YB(Y_CHINITSU);
+constexpr uint64_t HO1 = YB(Y_TANYAO) | YB(Y_HAKU) | YB(Y_HATSU) | YB(Y_CHUN) | YB(Y_SEATW) | YB(Y_ROUNDW) |
+                         YB(Y_RINSHAN) | YB(Y_CHANKAN) | YB(Y_HAITEI) | YB(Y_HOUTEI) | YB(Y_SANSHOKU) | YB(Y_ITTSU) |
+                         YB(Y_CHANTA);
+constexpr uint64_t HO2 = YB(Y_TOITOI) | YB(Y_SANANKOU) | YB(Y_DOUKOU) | YB(Y_SANKANTSU) | YB(Y_HONROUTOU) |
+                         YB(Y_SHOUSANGEN) | YB(Y_HONITSU) | YB(Y_JUNCHAN);
+constexpr uint64_t HO5 = YB(Y_CHINITSU);
+
+struct EvalCtx {
+  bool menzen, tsumo, dealer;
+  int riichi, flags, n_meld, n_dora, n_ura, n_aka, seat_k, round_k, win;
+  uint64_t situ, first_ym, colour_y, colour_ym;
+  bool found;
+  HandOut best;
+};
+
+MJ_HD void offer(EvalCtx &c, uint64_t y, uint64_t ym, int fu)
+{
+  HandOut r;
+  ym |= c.first_ym;
+  if (ym) {
+    r.units = popc64(ym >> 32); r.yaku = ym; r.han = 13 * r.units; r.fu = 0;
+    r.points = total_points(8000 * r.units, c.dealer, c.tsumo);
+  } else {
+    y |= c.situ;
+    int han = c.menzen ? popc64(y & HC1) + 2 * popc64(y & HC2) + 3 * popc64(y & HC3) + 6 * popc64(y & HC6)
+                       : popc64(y & HO1) + 2 * popc64(y & HO2) + 5 * popc64(y & HO5);
+    if (han == 0) return;
+    han += c.n_dora + c.n_ura + c.n_aka;
+    r.units = 0; r.yaku = y; r.han = han; r.fu = fu;
+    r.points = total_points(base_points(han, fu, 0), c.dealer, c.tsumo);
+  }
+  bool better;
+  if (!c.found) better = true;
+  else if (r.points != c.best.points) better = r.points > c.best.points;
+  else if (r.han != c.best.han) better = r.han > c.best.han;
+  else if (r.fu != c.best.fu) better = r.fu > c.best.fu;
+  else better = r.yaku > c.best.yaku;
+  if (better) {
+    c.best.yaku = r.yaku; c.best.points = r.points; c.best.han = r.han; c.best.fu = r.fu; c.best.units = r.units;
+    c.found = true;
+  }
+}
+
+// one decomposition as masks
+struct Decomp {
+  uint64_t trip_c, trip_o, kan_c, kan_o;   // kinds
+  uint32_t crun[3], orun[3];               // packed multiplicities of run starts, concealed / called
+  int pair;
+};
+
+MJ_HD void add_record(Decomp &d, uint32_t rec, int su)
+{
+  int p = (int)(rec & 15);
+  if (p) d.pair = 9 * su + p - 1;
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    uint32_t s = (rec >> (4 + 5 * j)) & 31u;
+    if (s == 31u) continue;
+    int r = (int)(s & 15);
+    if (s & 16) d.trip_c |= kbit(9 * su + r);
+    else d.crun[su] += 1u << (3 * r);
+  }
+}
+
+// value of one decomposition under one way of waiting
+MJ_HD void eval_placed(EvalCtx &c, const Decomp &d, uint64_t trip_c, uint64_t trip_o, int wait_fu, bool two_sided)
+{
+  uint64_t y = c.colour_y, ym = c.colour_ym;
+  uint32_t run[3] = {d.crun[0] + d.orun[0], d.crun[1] + d.orun[1], d.crun[2] + d.orun[2]};
+  int n_run = tiles_in(run[0]) + tiles_in(run[1]) + tiles_in(run[2]);
+  uint64_t trips = trip_c | trip_o | d.kan_c | d.kan_o;
+  uint64_t concealed = trip_c | d.kan_c, kans = d.kan_c | d.kan_o;
+  uint64_t pairb = kbit(d.pair);
+  int n_conc = popc64(concealed), n_kan = popc64(kans);
+
+  y |= (trips >> 31 & 7) << Y_HAKU;
+  if (trips & kbit(c.seat_k)) y |= YB(Y_SEATW);
+  if (trips & kbit(c.round_k)) y |= YB(Y_ROUNDW);
+  int pair_fu = 0;
+  if (pairb & K_DRAGONS) pair_fu += 2;
+  if (d.pair == c.seat_k) pair_fu += 2;
+  if (d.pair == c.round_k) pair_fu += 2;
+  bool pinfu = c.menzen && n_run == 4 && pair_fu == 0 && two_sided;
+  if (pinfu) y |= YB(Y_PINFU);
+  if (c.menzen) {
+    int doubles = 0;
+#pragma unroll
+    for (int s = 0; s < 3; s++) {
+      uint32_t x = (d.crun[s] >> 1) & 0333333333u;
+      doubles += popc32(x & O111) + 2 * popc32(x & (O111 << 1));
+    }
+    if (doubles >= 2) y |= YB(Y_RYANPEIKOU);
+    else if (doubles == 1) y |= YB(Y_IIPEIKOU);
+  }
+  uint32_t rm0 = fields_nonzero(run[0]), rm1 = fields_nonzero(run[1]), rm2 = fields_nonzero(run[2]);
+  if (rm0 & rm1 & rm2) y |= YB(Y_SANSHOKU);
+  const uint32_t ITTSU = 1u | 1u << 9 | 1u << 18;
+  if ((rm0 & ITTSU) == ITTSU || (rm1 & ITTSU) == ITTSU || (rm2 & ITTSU) == ITTSU) y |= YB(Y_ITTSU);
+  const uint32_t ENDS = 1u | 1u << 18;          // runs 123 and 789
+  bool every_yao = ((rm0 | rm1 | rm2) & ~ENDS) == 0 && (trips & ~K_YAOCHU) == 0 && (pairb & K_YAOCHU) != 0;
+  if (every_yao && n_run >= 1) y |= ((trips | pairb) & K_HONORS) ? YB(Y_CHANTA) : YB(Y_JUNCHAN);
+  if (n_run == 0) y |= YB(Y_TOITOI);
+  if (n_conc == 3) y |= YB(Y_SANANKOU);
+  uint32_t t0 = (uint32_t)(trips & 0x1FF), t1 = (uint32_t)(trips >> 9 & 0x1FF), t2 = (uint32_t)(trips >> 18 & 0x1FF);
+  if (t0 & t1 & t2) y |= YB(Y_DOUKOU);
+  if (n_kan == 3) y |= YB(Y_SANKANTSU);
+  int n_dragon = popc64(trips & K_DRAGONS), n_wind = popc64(trips & K_WINDS);
+  if (n_dragon == 2 && (pairb & K_DRAGONS)) y |= YB(Y_SHOUSANGEN);
+
+  if (n_conc == 4) ym |= YB(Y_SUUANKOU);
+  if (n_dragon == 3) ym |= YB(Y_DAISANGEN);
+  if (n_wind == 3 && (pairb & K_WINDS)) ym |= YB(Y_SHOUSUUSHII);
+  if (n_wind == 4) ym |= YB(Y_DAISUUSHII);
+  if (n_kan == 4) ym |= YB(Y_SUUKANTSU);
+
+  int fu;
+  if (pinfu) fu = c.tsumo ? 20 : 30;
+  else {
+    fu = 20 + ((c.menzen && !c.tsumo) ? 10 : 0) + (c.tsumo ? 2 : 0) + pair_fu + wait_fu;
+    fu += 2 * popc64(trip_o & ~K_YAOCHU) + 4 * popc64(trip_o & K_YAOCHU) + 4 * popc64(trip_c & ~K_YAOCHU) +
+          8 * popc64(trip_c & K_YAOCHU) + 8 * popc64(d.kan_o & ~K_YAOCHU) + 16 * popc64(d.kan_o & K_YAOCHU) +
+          16 * popc64(d.kan_c & ~K_YAOCHU) + 32 * popc64(d.kan_c & K_YAOCHU);
+    if (!c.menzen && fu == 20) fu = 30;
+    fu = (fu + 9) / 10 * 10;
+  }
+  offer(c, y, ym, fu);
+}
+
+// all ways the winning tile can sit in this decomposition
+MJ_HD void eval_decomp(EvalCtx &c, const Decomp &d)
+{
+  int w = c.win;
+  if (d.pair == w) eval_placed(c, d, d.trip_c, d.trip_o, 2, false);
+  if (d.trip_c & kbit(w)) {
+    if (c.tsumo) eval_placed(c, d, d.trip_c, d.trip_o, 0, false);
+    else eval_placed(c, d, d.trip_c & ~kbit(w), d.trip_o | kbit(w), 0, false);
+  }
+  if (w < 27) {
+    int su = suit_of(w), r = rank_of(w, su);
+    uint32_t cr = d.crun[su];
+    bool mid = r >= 1 && r <= 7 && cnt3(cr, r - 1) > 0;                 // run r-1, r, r+1
+    bool low = r <= 6 && cnt3(cr, r) > 0;                               // run r, r+1, r+2
+    bool high = r >= 2 && cnt3(cr, r - 2) > 0;                          // run r-2, r-1, r
+    bool edge = (low && r == 6) || (high && r == 2);
+    bool two = (low && r != 6) || (high && r != 2);
+    if (mid || edge) eval_placed(c, d, d.trip_c, d.trip_o, 2, false);
+    if (two) eval_placed(c, d, d.trip_c, d.trip_o, 0, true);
+  }
+}
+
+MJ_HD_NOINLINE void eval_hand(const Lut &L, const HandIn &q, HandOut &out)
+{
+  out.yaku = 0; out.points = 0; out.han = out.fu = out.units = out.shape_ok = out.yaku_ok = 0;
+  out.n_dora = out.n_ura = out.n_aka = 0;
+  int n_meld = q.n_meld, w = q.win;
+  if (n_meld > 4 || w >= 34 || hand_count(q.h, w) == 0) return;
+  int total = tiles_in(q.h[0]) + tiles_in(q.h[1]) + tiles_in(q.h[2]) + tiles_in(q.h[3]);
+  if (total != 14 - 3 * n_meld) return;
+  // counts above four make no valid pattern
+  uint32_t over = 0;
+#pragma unroll
+  for (int s = 0; s < 4; s++) over |= ((q.h[s] >> 2) & O111) & ((q.h[s] | (q.h[s] >> 1)) & O111);
+  if (over) return;
+
+  // per-suit probes
+  int nd[3]; uint32_t idx[3];
+  int n_pair_suits = 0; bool std_ok = true;
+#pragma unroll
+  for (int s = 0; s < 3; s++) {
+    nd[s] = lut_records(L, q.h[s], &idx[s]);
+    if (nd[s] == 0) std_ok = false;
+    if (tiles_in(q.h[s]) % 3 == 2) n_pair_suits++;
+  }
+  if (!honors_valid(q.h[3])) std_ok = false;
+  uint32_t hon_pair = fields_eq(q.h[3], 2), hon_trip = fields_eq(q.h[3], 3);
+  if (hon_pair) n_pair_suits++;
+  if (n_pair_suits != 1) std_ok = false;
+
+  // special forms
+  uint32_t pairs = 0, other = 0; uint64_t present = 0;
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    uint32_t e2 = fields_eq(q.h[s], 2), nz = fields_nonzero(q.h[s]);
+    pairs += popc32(e2); other += popc32(nz & ~e2 & ~fields_eq(q.h[s], 1));
+    present |= (uint64_t)squeeze9(nz) << (9 * s);
+  }
+  bool chiitoi = n_meld == 0 && pairs == 7 && popc64(present) == 7;
+  bool kokushi = n_meld == 0 && (present & ~K_YAOCHU) == 0 && popc64(present) == 13 && pairs == 1 && other == 0;
+  if (!std_ok && !chiitoi && !kokushi) return;
+  out.shape_ok = 1;
+
+  // context shared by every interpretation
+  EvalCtx c;
+  c.found = false;
+  c.best.yaku = 0; c.best.points = 0; c.best.han = c.best.fu = c.best.units = 0;
+  c.n_meld = n_meld; c.win = w; c.flags = q.flags;
+  c.tsumo = q.flags & 1; c.dealer = q.seat_wind == 0;
+  c.seat_k = 27 + q.seat_wind; c.round_k = 27 + q.round_wind;
+  Decomp base;
+  base.trip_c = base.trip_o = base.kan_c = base.kan_o = 0;
+  base.crun[0] = base.crun[1] = base.crun[2] = 0;
+  base.orun[0] = base.orun[1] = base.orun[2] = 0;
+  base.pair = 63;
+  uint32_t all[4] = {q.h[0], q.h[1], q.h[2], q.h[3]};
+  c.menzen = true;
+  for (int j = 0; j < n_meld; j++) {
+    uint32_t m = meld_at(q.meldw, j);
+    int t = m_type(m), k = m_kind(m), su = suit_of(k), r = rank_of(k, su);
+    if (t != MT_ANKAN) c.menzen = false;
+    if (t == MT_CHI) { base.orun[su] += 1u << (3 * r); all[su] += 0111u << (3 * r); }
+    else if (t == MT_PON) { base.trip_o |= kbit(k); all[su] += 3u << (3 * r); }
+    else if (t == MT_ANKAN) { base.kan_c |= kbit(k); all[su] += 4u << (3 * r); }
+    else { base.kan_o |= kbit(k); all[su] += 4u << (3 * r); }
+  }
+  c.riichi = c.menzen ? q.riichi : 0;
+  c.n_dora = c.n_ura = 0;
+  for (int i = 0; i < q.n_ind && i < 5; i++) {
+    c.n_dora += hand_count(all, dora_of(q.ind[i]));
+    if (c.riichi) c.n_ura += hand_count(all, dora_of(q.ura[i]));
+  }
+  c.n_aka = q.n_aka;
+  int f = q.flags;
+  uint64_t situ = 0;
+  if (c.riichi == 1) situ |= YB(Y_RIICHI);
+  if (c.riichi == 2) situ |= YB(Y_DRIICHI);
+  if (c.riichi && (f & 2)) situ |= YB(Y_IPPATSU);
+  if (c.tsumo && c.menzen) situ |= YB(Y_TSUMO);
+  if (c.tsumo && (f & 4)) situ |= YB(Y_RINSHAN);
+  if (!c.tsumo && (f & 8)) situ |= YB(Y_CHANKAN);
+  if (c.tsumo && (f & 16) && !(f & 4)) situ |= YB(Y_HAITEI);
+  if (!c.tsumo && (f & 32) && !(f & 8)) situ |= YB(Y_HOUTEI);
+  c.situ = situ;
+  c.first_ym = ((f & 64) && c.tsumo && n_meld == 0 && !(f & 4)) ? YB(c.dealer ? Y_TENHOU : Y_CHIIHOU) : 0;
+
+  // yaku of the tile multiset alone
+  {
+    const uint32_t TERM = 7u | 7u << 24;
+    bool s0 = all[0] != 0, s1 = all[1] != 0, s2 = all[2] != 0, hon = all[3] != 0;
+    int n_suits = (int)s0 + (int)s1 + (int)s2;
+    uint32_t suited = all[0] | all[1] | all[2];
+    bool no_term = (suited & TERM) == 0, only_term = (suited & ~TERM) == 0;
+    uint64_t y = 0, ym = 0;
+    if (no_term && !hon && (c.menzen || q.kuitan)) y |= YB(Y_TANYAO);
+    if (n_suits == 1 && hon) y |= YB(Y_HONITSU);
+    if (n_suits == 1 && !hon) y |= YB(Y_CHINITSU);
+    if (only_term && hon && n_suits >= 1) y |= YB(Y_HONROUTOU);
+    if (n_suits == 0) ym |= YB(Y_TSUUIISOU);
+    if (only_term && !hon) ym |= YB(Y_CHINROUTOU);
+    const uint32_t GREEN_S = 7u << 3 | 7u << 6 | 7u << 9 | 7u << 15 | 7u << 21;   // 2 3 4 6 8 of souzu
+    if (all[0] == 0 && all[1] == 0 && (all[2] & ~GREEN_S) == 0 && (all[3] & ~(7u << 15)) == 0) ym |= YB(Y_RYUUIISOU);
+    c.colour_y = y; c.colour_ym = ym;
+  }
+
+  if (std_ok) {
+    // nine gates: closed, one suit, at least 3 1 1 1 1 1 1 1 3
+    uint64_t gates = 0;
+    if (n_meld == 0 && (c.colour_y & YB(Y_CHINITSU))) {
+      uint32_t x = all[0] | all[1] | all[2];        // only one of them is non-zero
+      bool each = fields_nonzero(x) == O111;
+      if (each && cnt3(x, 0) >= 3 && cnt3(x, 8) >= 3) gates = YB(Y_CHUUREN);
+    }
+    c.colour_ym |= gates;
+    if (hon_pair) base.pair = 27 + (ctz64(hon_pair) / 3);
+    uint32_t ht = hon_trip;
+    while (ht) { int b = ctz64(ht); ht &= ht - 1; base.trip_c |= kbit(27 + b / 3); }
+    for (int i0 = 0; i0 < nd[0]; i0++)
+      for (int i1 = 0; i1 < nd[1]; i1++)
+        for (int i2 = 0; i2 < nd[2]; i2++) {
+          Decomp d = base;
+          add_record(d, L.recs[idx[0] + i0], 0);
+          add_record(d, L.recs[idx[1] + i1], 1);
+          add_record(d, L.recs[idx[2] + i2], 2);
+          eval_decomp(c, d);
+        }
+    c.colour_ym &= ~gates;
+  }
+  if (chiitoi) offer(c, c.colour_y | YB(Y_CHIITOI), c.colour_ym, 25);
+  if (kokushi) offer(c, 0, YB(Y_KOKUSHI), 0);
+
+  if (c.found) {
+    out.yaku = c.best.yaku; out.points = c.best.points; out.han = c.best.han; out.fu = c.best.fu;
+    out.units = c.best.units; out.yaku_ok = 1;
+    out.n_dora = c.n_dora; out.n_ura = c.n_ura; out.n_aka = c.n_aka;
+  }
+}
+
+}  // namespace mj

@@ -1,0 +1,719 @@
+// The phase machine of one environment (deal, draw, discard, calls, kans,
+// wins, draws, kyoku and game transitions, legal masks) on the packed state of
+// mj_core.hpp.  One GPU lane runs one environment; see mj_core.hpp for the
+// host-compilation note.  Rules: paper section 3.2 (standard four-player
+// East-South Riichi, red / no-red variants, single / east / half modes,
+// illegal action => termination); the concrete readings (action numbering,
+// simultaneous responses, wall geography, tie-breaks) are this library's and
+// are listed in the design document.
+#pragma once
+#include "mj_core.hpp"
+
+namespace mj {
+
+struct Ctx {
+  Env e;
+  Lut L;
+  Rules R;
+  Glob g;
+  uint32_t env_id;
+};
+
+// ------------------------------------------------------------- field access
+MJ_HD uint32_t &HW(Ctx &c, int s, int su) { return c.e.hand[(int64_t)(s * 4 + su) * c.e.n]; }
+MJ_HD uint32_t &SW(Ctx &c, int s) { return c.e.seatw[(int64_t)s * c.e.n]; }
+MJ_HD uint64_t &MELDW(Ctx &c, int s) { return c.e.meld[(int64_t)s * c.e.n]; }
+MJ_HD uint64_t &WAITS(Ctx &c, int s) { return c.e.waits[(int64_t)s * c.e.n]; }
+MJ_HD uint64_t &DK(Ctx &c, int s) { return c.e.dk[(int64_t)s * c.e.n]; }
+MJ_HD uint64_t &MASK(Ctx &c, int s, int w) { return c.e.mask[(int64_t)(s * 2 + w) * c.e.n]; }
+MJ_HD int32_t &SCORE(Ctx &c, int s) { return c.e.score[(int64_t)s * c.e.n]; }
+MJ_HD int32_t &DELTA(Ctx &c, int s) { return c.e.delta[(int64_t)s * c.e.n]; }
+MJ_HD uint8_t &WALL(Ctx &c, int i) { return c.e.wall[(int64_t)i * c.e.n]; }
+MJ_HD uint8_t &RIVER(Ctx &c, int s, int i) { return c.e.river[(int64_t)(s * 32 + i) * c.e.n]; }
+
+MJ_HD int swf(Ctx &c, int s, int pos, int bits) { return (int)sw_get(SW(c, s), pos, bits); }
+MJ_HD void swf_set(Ctx &c, int s, int pos, int bits, int v) { SW(c, s) = sw_set(SW(c, s), pos, bits, (uint32_t)v); }
+
+MJ_HD int count_of(Ctx &c, int s, int k) { int su = suit_of(k); return cnt3(HW(c, s, su), rank_of(k, su)); }
+MJ_HD void hand_add(Ctx &c, int s, int k, int d)
+{
+  int su = suit_of(k);
+  HW(c, s, su) += (uint32_t)d << (3 * rank_of(k, su));     // d may be negative: two's complement on the field
+}
+MJ_HD bool has_red(Ctx &c, int s, int k) { return is_five(k) && ((SW(c, s) >> (k / 9)) & 1u); }
+MJ_HD int nonred_of(Ctx &c, int s, int k) { return count_of(c, s, k) - (has_red(c, s, k) ? 1 : 0); }
+MJ_HD int concealed_total(Ctx &c, int s)
+{
+  return tiles_in(HW(c, s, 0)) + tiles_in(HW(c, s, 1)) + tiles_in(HW(c, s, 2)) + tiles_in(HW(c, s, 3));
+}
+MJ_HD int dealer_of(const Ctx &c) { return c.g.kyoku & 3; }
+MJ_HD bool is_red_id(const Ctx &c, int id) { return (c.R.flags & F_RED) && (id == 16 || id == 52 || id == 88); }
+
+MJ_HD void refresh_waits(Ctx &c, int s)
+{
+  WAITS(c, s) = waits_of(c.L, HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3), MELDW(c, s), swf(c, s, SW_NMELD, 3));
+}
+MJ_HD int take_tile(Ctx &c, int s, int id)
+{
+  int k = id >> 2, red = is_red_id(c, id) ? 1 : 0;
+  hand_add(c, s, k, 1);
+  if (red) SW(c, s) |= 1u << (k / 9);
+  return k | red << 6;
+}
+MJ_HD bool menzen_of(Ctx &c, int s)
+{
+  uint64_t mw = MELDW(c, s);
+  int n = swf(c, s, SW_NMELD, 3);
+  for (int j = 0; j < n; j++) if (m_type(meld_at(mw, j)) != MT_ANKAN) return false;
+  return true;
+}
+MJ_HD void clear_masks(Ctx &c)
+{
+#pragma unroll
+  for (int i = 0; i < 8; i++) c.e.mask[(int64_t)i * c.e.n] = 0;
+  c.g.actor_mask = 0;
+}
+MJ_HD void clear_first_and_ippatsu(Ctx &c)
+{
+#pragma unroll
+  for (int s = 0; s < 4; s++) SW(c, s) &= ~((1u << SW_IPPATSU) | (1u << SW_FIRST));
+}
+
+// value of seat s winning on kind w now
+MJ_HD void eval_seat(Ctx &c, int s, int w, bool tsumo, bool chankan, HandOut &out)
+{
+  HandIn q;
+#pragma unroll
+  for (int su = 0; su < 4; su++) q.h[su] = HW(c, s, su);
+  if (!tsumo) { int su = suit_of(w); q.h[su] += 1u << (3 * rank_of(w, su)); }
+  uint32_t sw = SW(c, s);
+  q.meldw = MELDW(c, s);
+  q.n_meld = (int)sw_get(sw, SW_NMELD, 3);
+  q.win = w;
+  int f = 0;
+  if (tsumo) f |= 1;
+  if (sw >> SW_IPPATSU & 1) f |= 2;
+  if (tsumo && c.g.rinshan) f |= 4;
+  if (chankan) f |= 8;
+  if (tsumo && c.g.live_left == 0 && !c.g.rinshan) f |= 16;
+  if (!tsumo && !chankan && c.g.live_left == 0) f |= 32;
+  if (tsumo && (sw >> SW_FIRST & 1)) f |= 64;
+  q.flags = f;
+  q.riichi = (int)sw_get(sw, SW_RIICHI, 2);
+  q.seat_wind = (s - dealer_of(c)) & 3;
+  q.round_wind = c.g.kyoku >> 2;
+  q.n_ind = c.g.n_dora;
+#pragma unroll
+  for (int i = 0; i < 5; i++) { q.ind[i] = WALL(c, 126 + i) >> 2; q.ura[i] = WALL(c, 131 + i) >> 2; }
+  int aka = popc32(sw & 7u);
+  for (int j = 0; j < q.n_meld; j++) aka += (int)(meld_at(q.meldw, j) >> 13 & 1u);
+  if (!tsumo && !chankan && code_red(c.g.last_discard) && code_kind(c.g.last_discard) == w) aka++;
+  if (chankan && code_red(c.g.kakan_tile)) aka++;
+  q.n_aka = aka;
+  q.kuitan = (c.R.flags & F_KUITAN) ? 1 : 0;
+  eval_hand(c.L, q, out);
+}
+
+MJ_HD bool furiten(Ctx &c, int s)
+{
+  uint32_t sw = SW(c, s);
+  return (sw >> SW_FTEMP & 1) || (sw >> SW_FRIICHI & 1) || (WAITS(c, s) & DK(c, s)) != 0;
+}
+MJ_HD void mark_furiten(Ctx &c, int s)
+{
+  SW(c, s) |= sw_get(SW(c, s), SW_RIICHI, 2) ? (1u << SW_FRIICHI) : (1u << SW_FTEMP);
+}
+
+// kinds whose discard leaves the 14-tile hand of seat s tenpai
+MJ_HD uint64_t tenpai_discards(Ctx &c, int s)
+{
+  uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
+  uint64_t mw = MELDW(c, s);
+  int n_meld = swf(c, s, SW_NMELD, 3);
+  uint64_t out = 0;
+  for (int su = 0; su < 4; su++) {
+    int nr = su == 3 ? 7 : 9;
+    for (int r = 0; r < nr; r++) {
+      if (cnt3(h[su], r) == 0) continue;
+      uint32_t g[4] = {h[0], h[1], h[2], h[3]};
+      g[su] -= 1u << (3 * r);
+      if (waits_of(c.L, g[0], g[1], g[2], g[3], mw, n_meld)) out |= kbit((su == 3 ? 27 : 9 * su) + r);
+    }
+  }
+  return out;
+}
+
+MJ_HD void set_action(uint64_t m[2], int a) { m[a >> 6] |= 1ull << (a & 63); }
+
+// discards available from the hand of seat s, restricted to the kinds in `allowed`
+MJ_HD void discard_bits(Ctx &c, int s, uint64_t allowed, uint64_t m[2])
+{
+  uint32_t sw = SW(c, s);
+  for (int su = 0; su < 4; su++) {
+    uint32_t hw = HW(c, s, su);
+    int nr = su == 3 ? 7 : 9, basek = su == 3 ? 27 : 9 * su;
+    for (int r = 0; r < nr; r++) {
+      int n = cnt3(hw, r), k = basek + r;
+      if (n == 0 || !(allowed >> k & 1)) continue;
+      bool red = su < 3 && r == 4 && (sw >> su & 1u);
+      if (n - (red ? 1 : 0) > 0) set_action(m, A_DISCARD + k);
+      if (red) set_action(m, A_DISCARD_RED + su);
+    }
+  }
+}
+
+// legal actions of the seat to move
+MJ_HD void turn_mask(Ctx &c)
+{
+  int s = c.g.cur;
+  uint64_t m[2] = {0, 0};
+  clear_masks(c);
+  c.g.phase = PH_TURN;
+  c.g.actor_mask = (uint8_t)(1 << s);
+  int drawn_k = c.g.drawn == 255 ? -1 : code_kind(c.g.drawn);
+  uint32_t sw = SW(c, s);
+  int riichi = (int)sw_get(sw, SW_RIICHI, 2);
+
+  if (c.g.riichi_pending) {
+    discard_bits(c, s, tenpai_discards(c, s), m);
+  } else {
+    bool can_tsumo = false;
+    if (drawn_k >= 0 && (WAITS(c, s) >> drawn_k & 1)) {
+      HandOut r;
+      eval_seat(c, s, drawn_k, true, false, r);
+      can_tsumo = r.yaku_ok;
+    }
+    if (can_tsumo) set_action(m, A_TSUMO);
+    bool kan_ok = drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
+    if (riichi) {
+      if (code_red(c.g.drawn)) set_action(m, A_DISCARD_RED + drawn_k / 9);
+      else set_action(m, A_DISCARD + drawn_k);
+      if (kan_ok && count_of(c, s, drawn_k) == 4) {
+        // a concealed kan is allowed in riichi only when it leaves the waits as they were
+        int su = suit_of(drawn_k), n_meld = (int)sw_get(sw, SW_NMELD, 3);
+        uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
+        h[su] -= 4u << (3 * rank_of(drawn_k, su));
+        uint64_t mw = MELDW(c, s) | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
+        if (waits_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld + 1) == WAITS(c, s)) set_action(m, A_KAN + drawn_k);
+      }
+    } else {
+      uint64_t allowed = K_ALL;
+      if (c.g.kuikae0 != 255) allowed &= ~kbit(c.g.kuikae0);
+      if (c.g.kuikae1 != 255) allowed &= ~kbit(c.g.kuikae1);
+      discard_bits(c, s, allowed, m);
+      int n_meld = (int)sw_get(sw, SW_NMELD, 3);
+      uint64_t mw = MELDW(c, s);
+      if (kan_ok) {
+        for (int su = 0; su < 4; su++) {
+          uint32_t four = fields_eq(HW(c, s, su), 4);
+          while (four) { int b = ctz64(four); four &= four - 1; set_action(m, A_KAN + (su == 3 ? 27 : 9 * su) + b / 3); }
+        }
+        for (int j = 0; j < n_meld; j++) {
+          uint32_t ml = meld_at(mw, j);
+          if (m_type(ml) == MT_PON && count_of(c, s, m_kind(ml)) >= 1) set_action(m, A_KAN + m_kind(ml));
+        }
+      }
+      if (drawn_k >= 0 && menzen_of(c, s) && SCORE(c, s) >= 1000 && c.g.live_left >= 4) {
+        if (tenpai_discards(c, s)) set_action(m, A_RIICHI);
+      }
+      if ((c.R.flags & F_ABORT) && (sw >> SW_FIRST & 1) && drawn_k >= 0) {
+        uint64_t present = 0;
+        for (int su = 0; su < 4; su++) present |= (uint64_t)squeeze9(fields_nonzero(HW(c, s, su))) << (9 * su);
+        if (popc64(present & K_YAOCHU) >= 9) set_action(m, A_KYUUSHU);
+      }
+    }
+  }
+  MASK(c, s, 0) = m[0];
+  MASK(c, s, 1) = m[1];
+}
+
+MJ_HD void draw_live(Ctx &c, int s)
+{
+  c.g.cur = (uint8_t)s;
+  int id = WALL(c, c.g.draw_ptr);
+  c.g.draw_ptr++;
+  c.g.live_left--;
+  c.g.rinshan = 0;
+  c.g.drawn = (uint8_t)take_tile(c, s, id);
+}
+
+// Fisher-Yates over the 136 tile ids: key (seed, env_id), counter (kyoku_serial, j, 0, 0)
+MJ_HD void shuffle_wall(Ctx &c)
+{
+  uint32_t serial = c.e.serial[0];
+  for (int i = 0; i < 136; i++) WALL(c, i) = (uint8_t)i;
+  for (int j = 0; j < 34; j++) {
+    uint32_t r[4];
+    philox(serial, (uint32_t)j, 0, 0, c.R.seed, c.env_id, r);
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      int i = 4 * j + t;
+      if (i >= 135) break;
+      int k = i + (int)mulhi(r[t], (uint32_t)(136 - i));
+      uint8_t a = WALL(c, i), b = WALL(c, k);
+      WALL(c, i) = b; WALL(c, k) = a;
+    }
+  }
+}
+
+MJ_HD void deal(Ctx &c, bool reshuffle)
+{
+  if (reshuffle) shuffle_wall(c);
+#pragma unroll
+  for (int i = 0; i < 16; i++) c.e.hand[(int64_t)i * c.e.n] = 0;
+  for (int s = 0; s < 4; s++) {
+    // everything per seat back to the start of a kyoku, the final rank of the game kept
+    uint32_t keep = SW(c, s) & (3u << SW_RANK);
+    SW(c, s) = keep | (255u << SW_RIDX) | (1u << SW_FIRST);
+    MELDW(c, s) = 0;
+    DK(c, s) = 0;
+  }
+  c.g.draw_ptr = 52; c.g.n_kan = 0; c.g.live_left = 70; c.g.n_dora = 1;
+  c.g.drawn = 255; c.g.riichi_pending = 0; c.g.rinshan = 0;
+  c.g.last_discard = 255; c.g.last_discarder = 255; c.g.kakan_tile = 255;
+  c.g.kuikae0 = c.g.kuikae1 = 255;
+  c.g.first_wind = 255; c.g.same_wind_cnt = 0;
+  int dealer = dealer_of(c);
+  for (int j = 0; j < 4; j++) {
+    int s = (dealer + j) & 3;
+    for (int t = 0; t < 13; t++) take_tile(c, s, WALL(c, 13 * j + t));
+  }
+  for (int s = 0; s < 4; s++) refresh_waits(c, s);
+  draw_live(c, dealer);
+  turn_mask(c);
+}
+
+MJ_HD void new_game(Ctx &c)
+{
+  for (int s = 0; s < 4; s++) {
+    SCORE(c, s) = c.R.start_score;
+    SW(c, s) = 0;                                        // final rank 0
+  }
+  c.g.kyoku = 0; c.g.honba = 0; c.g.kyotaku = 0; c.g.terminated = 0;
+  deal(c, true);
+}
+
+MJ_HD void clear_result(Ctx &c)
+{
+  c.g.end_type = 0; c.g.winners = 0; c.g.loser = 255; c.g.tenpai_mask = 0;
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    c.e.resw[(int64_t)s * c.e.n] = 0;
+    c.e.yaku[(int64_t)s * c.e.n] = 0;
+    c.e.gain[(int64_t)s * c.e.n] = 0;
+  }
+}
+MJ_HD void credit(Ctx &c, int s, int32_t x) { SCORE(c, s) += x; DELTA(c, s) += x; }
+
+MJ_HD void finish_kyoku(Ctx &c, bool renchan, bool honba_up)
+{
+  int last = c.R.mode == 0 ? 0 : c.R.mode == 1 ? 3 : 7;
+  bool over = c.R.mode == 0;
+  for (int s = 0; s < 4; s++) if (SCORE(c, s) < 0) over = true;
+  if (!renchan && c.g.kyoku == last) over = true;
+  if (honba_up) { if (c.g.honba < 255) c.g.honba++; } else c.g.honba = 0;
+  if (!renchan && !over) c.g.kyoku++;
+  if (over) {
+    int32_t sc[4] = {SCORE(c, 0), SCORE(c, 1), SCORE(c, 2), SCORE(c, 3)};
+    int top = 0;
+    for (int s = 1; s < 4; s++) if (sc[s] > sc[top]) top = s;
+    int32_t sticks = 1000 * (int32_t)c.g.kyotaku;
+    credit(c, top, sticks);
+    sc[top] += sticks;
+    c.g.kyotaku = 0;
+    for (int s = 0; s < 4; s++) {
+      int r = 0;
+      for (int o = 0; o < 4; o++) r += (sc[o] > sc[s] || (sc[o] == sc[s] && o < s)) ? 1 : 0;
+      swf_set(c, s, SW_RANK, 2, r);
+    }
+    c.g.terminated = 1; c.g.phase = PH_TERMINAL;
+    clear_masks(c);
+    return;
+  }
+  c.e.serial[0]++;
+  deal(c, true);
+}
+
+MJ_HD void win(Ctx &c, int winners, bool tsumo, int loser, int w, bool chankan)
+{
+  int dealer = dealer_of(c);
+  clear_result(c);
+  c.g.end_type = tsumo ? 1 : 2;
+  c.g.winners = (uint8_t)winners;
+  c.g.loser = tsumo ? 255 : (uint8_t)loser;
+  // the sticks go to the only winner, or to the first winner after the loser
+  int stick_seat = 0;
+  if (tsumo) stick_seat = ctz64((uint64_t)winners);
+  else for (int d = 3; d >= 1; d--) if (winners >> ((loser + d) & 3) & 1) stick_seat = (loser + d) & 3;
+  int32_t honba = c.g.honba;
+  for (int s = 0; s < 4; s++) {
+    if (!(winners >> s & 1)) continue;
+    HandOut r;
+    eval_seat(c, s, w, tsumo, chankan, r);
+    c.e.yaku[(int64_t)s * c.e.n] = r.yaku;
+    c.e.resw[(int64_t)s * c.e.n] = (uint64_t)(uint8_t)r.han | (uint64_t)(uint8_t)r.fu << 8 | (uint64_t)r.units << 16 |
+                                   (uint64_t)r.n_dora << 24 | (uint64_t)r.n_ura << 32 | (uint64_t)r.n_aka << 40;
+    int32_t base = base_points(r.han, r.fu, r.units), got = 0;
+    if (tsumo) {
+      for (int o = 0; o < 4; o++) {
+        if (o == s) continue;
+        int32_t x = ((s == dealer || o == dealer) ? up100(base * 2) : up100(base)) + 100 * honba;
+        credit(c, o, -x);
+        got += x;
+      }
+    } else {
+      got = up100(base * (s == dealer ? 6 : 4)) + 300 * honba;
+      credit(c, loser, -got);
+    }
+    if (s == stick_seat) { got += 1000 * (int32_t)c.g.kyotaku; c.g.kyotaku = 0; }
+    credit(c, s, got);
+    c.e.gain[(int64_t)s * c.e.n] = got;
+  }
+  bool renchan = winners >> dealer & 1;
+  finish_kyoku(c, renchan, renchan);
+}
+
+MJ_HD void exhaustive_draw(Ctx &c)
+{
+  clear_result(c);
+  c.g.end_type = 3;
+  int T = 0;
+  for (int s = 0; s < 4; s++) if (WAITS(c, s) != 0 || swf(c, s, SW_RIICHI, 2)) T |= 1 << s;
+  c.g.tenpai_mask = (uint8_t)T;
+  int n = popc32((uint32_t)T);
+  if (n >= 1 && n <= 3) {
+    int32_t get = 3000 / n, give = 3000 / (4 - n);
+    for (int s = 0; s < 4; s++) credit(c, s, (T >> s & 1) ? get : -give);
+  }
+  finish_kyoku(c, T >> dealer_of(c) & 1, true);
+}
+MJ_HD void abortive_draw(Ctx &c, int type)
+{
+  clear_result(c);
+  c.g.end_type = (uint8_t)type;
+  finish_kyoku(c, true, true);
+}
+
+MJ_HD void advance(Ctx &c)
+{
+  if (c.g.live_left == 0) { exhaustive_draw(c); return; }
+  draw_live(c, (c.g.last_discarder + 1) & 3);
+  turn_mask(c);
+}
+
+MJ_HD void finish_kan(Ctx &c)
+{
+  int s = c.g.cur;
+  swf_set(c, s, SW_KANBY, 3, swf(c, s, SW_KANBY, 3) + 1);
+  c.g.n_dora++;
+  int id = WALL(c, 122 + c.g.n_kan);
+  c.g.n_kan++;
+  c.g.live_left--;
+  clear_first_and_ippatsu(c);
+  c.g.drawn = (uint8_t)take_tile(c, s, id);
+  c.g.rinshan = 1;
+  c.g.kakan_tile = 255;
+  turn_mask(c);
+}
+
+// returns true when the kyoku ended here
+MJ_HD bool settle_discard(Ctx &c)
+{
+  int d = c.g.last_discarder;
+  if (c.g.riichi_pending) {
+    credit(c, d, -1000);
+    c.g.kyotaku++;
+    uint32_t sw = SW(c, d);
+    sw = sw_set(sw, SW_RIICHI, 2, c.g.riichi_pending);
+    sw |= 1u << SW_IPPATSU;
+    sw = sw_set(sw, SW_RIDX, 8, sw_get(sw, SW_NRIVER, 6) - 1);
+    SW(c, d) = sw;
+    c.g.riichi_pending = 0;
+  }
+  if (c.R.flags & F_ABORT) {
+    if (c.g.same_wind_cnt == 4) { abortive_draw(c, 5); return true; }
+    bool all_riichi = true, one_seat = false;
+    for (int s = 0; s < 4; s++) {
+      uint32_t sw = SW(c, s);
+      if (!sw_get(sw, SW_RIICHI, 2)) all_riichi = false;
+      if (sw_get(sw, SW_KANBY, 3) == 4) one_seat = true;
+    }
+    if (all_riichi) { abortive_draw(c, 6); return true; }
+    if (c.g.n_kan == 4 && !one_seat) { abortive_draw(c, 7); return true; }
+  }
+  return false;
+}
+
+// what seat o may do about the tile just discarded by d
+MJ_HD void response_options(Ctx &c, int o, int d, int code, uint64_t m[2])
+{
+  int k = code_kind(code);
+  m[0] = m[1] = 0;
+  uint32_t sw = SW(c, o);
+  if (WAITS(c, o) >> k & 1) {
+    bool ok = false;
+    if (!furiten(c, o)) {
+      HandOut r;
+      eval_seat(c, o, k, false, false, r);
+      ok = r.yaku_ok;
+    }
+    if (ok) set_action(m, A_RON);
+    else mark_furiten(c, o);
+  }
+  if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0) {
+    int su = suit_of(k), r = rank_of(k, su);
+    uint32_t hw = HW(c, o, su);
+    int have = cnt3(hw, r);
+    int total = concealed_total(c, o);
+    bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
+    int nonred = have - (red_held ? 1 : 0);
+    if (total - have > 0) {
+      if (nonred >= 2) set_action(m, A_PON);
+      if (red_held && nonred >= 1) set_action(m, A_PON_RED);
+    }
+    if (have >= 3 && c.g.n_kan < 4) set_action(m, A_MINKAN);
+    if (o == ((d + 1) & 3) && su < 3) {
+      bool red_in_suit = sw >> su & 1u;
+#pragma unroll
+      for (int pos = 0; pos < 3; pos++) {
+        int lo = r - pos;
+        if (lo < 0 || lo > 6) continue;
+        int ra = pos == 0 ? lo + 1 : lo, rb = pos == 2 ? lo + 1 : lo + 2;       // the two ranks taken from the hand
+        int ca = cnt3(hw, ra), cb = cnt3(hw, rb);
+        if (ca == 0 || cb == 0) continue;
+        int extra = 0;
+        if (pos == 0 && r + 3 <= 8) extra = cnt3(hw, r + 3);
+        if (pos == 2 && r - 3 >= 0) extra = cnt3(hw, r - 3);
+        if (total - 2 - have - extra <= 0) continue;
+        bool five_used = ra == 4 || rb == 4;
+        int na = ca - ((ra == 4 && red_in_suit) ? 1 : 0), nb = cb - ((rb == 4 && red_in_suit) ? 1 : 0);
+        if (na >= 1 && nb >= 1) set_action(m, A_CHI_L + pos);
+        if (five_used && red_in_suit) set_action(m, A_CHI_L_RED + pos);
+      }
+    }
+  }
+  if (m[0] | m[1]) set_action(m, A_PASS);
+}
+
+MJ_HD void discard(Ctx &c, int s, int k, int red)
+{
+  hand_add(c, s, k, -1);
+  uint32_t sw = SW(c, s);
+  if (red) sw &= ~(1u << (k / 9));
+  int nr = (int)sw_get(sw, SW_NRIVER, 6);
+  RIVER(c, s, nr) = (uint8_t)(k | red << 6);
+  sw = sw_set(sw, SW_NRIVER, 6, nr + 1);
+  DK(c, s) |= kbit(k);
+  sw &= ~(1u << SW_FTEMP);
+  if (sw_get(sw, SW_RIICHI, 2)) sw &= ~(1u << SW_IPPATSU);
+  if ((sw >> SW_FIRST & 1) && c.g.same_wind_cnt != 255) {
+    if (k >= 27 && k <= 30 && (c.g.same_wind_cnt == 0 || k == c.g.first_wind)) { c.g.first_wind = (uint8_t)k; c.g.same_wind_cnt++; }
+    else c.g.same_wind_cnt = 255;
+  }
+  sw &= ~(1u << SW_FIRST);
+  SW(c, s) = sw;
+  c.g.kuikae0 = c.g.kuikae1 = 255;
+  refresh_waits(c, s);
+  c.g.last_discard = (uint8_t)(k | red << 6);
+  c.g.last_discarder = (uint8_t)s;
+  c.g.drawn = 255;
+
+  int any = 0;
+  uint64_t m[4][2];
+#pragma unroll
+  for (int o = 0; o < 4; o++) {
+    m[o][0] = m[o][1] = 0;
+    if (o == s) continue;
+    response_options(c, o, s, c.g.last_discard, m[o]);
+    if (m[o][0] | m[o][1]) any |= 1 << o;
+  }
+  if (any) {
+    c.g.phase = PH_RESPOND;
+    c.g.actor_mask = (uint8_t)any;
+#pragma unroll
+    for (int o = 0; o < 4; o++) { MASK(c, o, 0) = m[o][0]; MASK(c, o, 1) = m[o][1]; }
+    return;
+  }
+  if (settle_discard(c)) return;
+  advance(c);
+}
+
+MJ_HD void remove_tiles(Ctx &c, int s, int k, int n_nonred, int take_red)
+{
+  hand_add(c, s, k, -(n_nonred + take_red));
+  if (take_red) SW(c, s) &= ~(1u << (k / 9));
+}
+MJ_HD void push_meld(Ctx &c, int s, uint32_t m)
+{
+  int j = swf(c, s, SW_NMELD, 3);
+  MELDW(c, s) |= (uint64_t)m << (16 * j);
+  swf_set(c, s, SW_NMELD, 3, j + 1);
+}
+
+MJ_HD void do_call(Ctx &c, int s, int a)
+{
+  int d = c.g.last_discarder, k = code_kind(c.g.last_discard), cred = code_red(c.g.last_discard);
+  int from_rel = (d - s) & 3;
+  RIVER(c, d, swf(c, d, SW_NRIVER, 6) - 1) |= 0x80;
+  clear_first_and_ippatsu(c);
+  c.g.cur = (uint8_t)s;
+  c.g.drawn = 255;
+  c.g.rinshan = 0;
+  if (a == A_PON || a == A_PON_RED) {
+    int tr = a == A_PON_RED;
+    remove_tiles(c, s, k, tr ? 1 : 2, tr);
+    push_meld(c, s, m_make(MT_PON, k, from_rel, 0, tr | cred, cred));
+    c.g.kuikae0 = (uint8_t)k; c.g.kuikae1 = 255;
+    turn_mask(c);
+  } else if (a == A_MINKAN) {
+    int tr = has_red(c, s, k) ? 1 : 0;
+    remove_tiles(c, s, k, tr ? 2 : 3, tr);
+    push_meld(c, s, m_make(MT_MINKAN, k, from_rel, 0, tr | cred, cred));
+    refresh_waits(c, s);
+    finish_kan(c);
+  } else {
+    int v = a - A_CHI_L, tr = v >= 3 ? 1 : 0, pos = v % 3, base = k - pos;
+    for (int t = 0; t < 3; t++) {
+      if (t == pos) continue;
+      int kk = base + t, r = (tr && is_five(kk)) ? 1 : 0;
+      remove_tiles(c, s, kk, r ? 0 : 1, r);
+    }
+    push_meld(c, s, m_make(MT_CHI, base, from_rel, pos, tr | cred, cred));
+    int rk = k % 9;
+    c.g.kuikae0 = (uint8_t)k;
+    c.g.kuikae1 = 255;
+    if (pos == 0 && rk + 3 <= 8) c.g.kuikae1 = (uint8_t)(k + 3);
+    if (pos == 2 && rk - 3 >= 0) c.g.kuikae1 = (uint8_t)(k - 3);
+    turn_mask(c);
+  }
+}
+
+MJ_HD void own_kan(Ctx &c, int k)
+{
+  int s = c.g.cur;
+  int tr = has_red(c, s, k) ? 1 : 0;
+  if (count_of(c, s, k) == 4) {
+    remove_tiles(c, s, k, tr ? 3 : 4, tr);
+    push_meld(c, s, m_make(MT_ANKAN, k, 0, 0, tr, 0));
+    c.g.drawn = 255;
+    refresh_waits(c, s);
+    finish_kan(c);
+    return;
+  }
+  remove_tiles(c, s, k, tr ? 0 : 1, tr);
+  uint64_t mw = MELDW(c, s);
+  int n_meld = swf(c, s, SW_NMELD, 3);
+  for (int j = 0; j < n_meld; j++) {
+    uint32_t ml = meld_at(mw, j);
+    if (m_type(ml) == MT_PON && m_kind(ml) == k) {
+      uint32_t nm = (ml & ~7u) | MT_KAKAN | (tr ? 1u << 13 : 0u);
+      mw = (mw & ~(0xFFFFull << (16 * j))) | (uint64_t)nm << (16 * j);
+    }
+  }
+  MELDW(c, s) = mw;
+  c.g.kakan_tile = (uint8_t)(k | tr << 6);
+  c.g.drawn = 255;
+  refresh_waits(c, s);
+  int any = 0;
+  uint64_t m[4][2];
+#pragma unroll
+  for (int o = 0; o < 4; o++) {
+    m[o][0] = m[o][1] = 0;
+    if (o == s || !(WAITS(c, o) >> k & 1)) continue;
+    bool ok = false;
+    if (!furiten(c, o)) {
+      HandOut r;
+      eval_seat(c, o, k, false, true, r);
+      ok = r.yaku_ok;
+    }
+    if (ok) { set_action(m[o], A_RON); set_action(m[o], A_PASS); any |= 1 << o; }
+    else mark_furiten(c, o);
+  }
+  if (any) {
+    c.g.phase = PH_RESPOND_KAKAN;
+    c.g.actor_mask = (uint8_t)any;
+#pragma unroll
+    for (int o = 0; o < 4; o++) { MASK(c, o, 0) = m[o][0]; MASK(c, o, 1) = m[o][1]; }
+    return;
+  }
+  finish_kan(c);
+}
+
+MJ_HD void mark_passed_ron(Ctx &c)
+{
+  for (int s = 0; s < 4; s++)
+    if ((c.g.actor_mask >> s & 1) && (MASK(c, s, 1) >> (A_RON - 64) & 1)) mark_furiten(c, s);
+}
+
+// one step of one environment; a[4] = the four seats' actions
+MJ_HD void step_env(Ctx &c, const int a[4])
+{
+#pragma unroll
+  for (int s = 0; s < 4; s++) DELTA(c, s) = 0;
+  c.g.illegal_seat = 255;
+  if (c.g.terminated) return;
+  for (int s = 0; s < 4; s++) {
+    if (!(c.g.actor_mask >> s & 1)) continue;
+    int x = a[s];
+    bool ok = x >= 0 && x < N_ACTIONS && (MASK(c, s, x >> 6) >> (x & 63) & 1);
+    if (!ok) {
+      c.g.illegal_seat = (uint8_t)s;
+      clear_result(c);
+      c.g.end_type = 9;
+      c.g.terminated = 1;
+      c.g.phase = PH_TERMINAL;
+      clear_masks(c);
+      return;
+    }
+  }
+  int actors = c.g.actor_mask;
+  if (c.g.phase == PH_TURN) {
+    int s = c.g.cur, act = a[s];
+    if (act < A_DISCARD_RED) discard(c, s, act, 0);
+    else if (act < A_KAN) discard(c, s, 4 + 9 * (act - A_DISCARD_RED), 1);
+    else if (act < A_RIICHI) own_kan(c, act - A_KAN);
+    else if (act == A_RIICHI) { c.g.riichi_pending = (SW(c, s) >> SW_FIRST & 1) ? 2 : 1; turn_mask(c); }
+    else if (act == A_TSUMO) win(c, 1 << s, true, -1, code_kind(c.g.drawn), false);
+    else abortive_draw(c, 4);
+  } else if (c.g.phase == PH_RESPOND) {
+    int d = c.g.last_discarder, ronners = 0;
+    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] == A_RON) ronners |= 1 << s;
+    if (popc32((uint32_t)ronners) == 3 && (c.R.flags & F_ABORT)) { clear_masks(c); abortive_draw(c, 8); return; }
+    if (ronners) { clear_masks(c); win(c, ronners, false, d, code_kind(c.g.last_discard), false); return; }
+    mark_passed_ron(c);
+    int caller = -1, call = 0;
+    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] >= A_PON && a[s] <= A_MINKAN) { caller = s; call = a[s]; }
+    if (caller < 0) {
+      int nx = (d + 1) & 3;
+      if ((actors >> nx & 1) && a[nx] >= A_CHI_L && a[nx] < A_PASS) { caller = nx; call = a[nx]; }
+    }
+    clear_masks(c);
+    if (settle_discard(c)) return;
+    if (caller >= 0) do_call(c, caller, call);
+    else advance(c);
+  } else if (c.g.phase == PH_RESPOND_KAKAN) {
+    int ronners = 0;
+    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] == A_RON) ronners |= 1 << s;
+    if (ronners) { clear_masks(c); win(c, ronners, false, c.g.cur, code_kind(c.g.kakan_tile), true); return; }
+    mark_passed_ron(c);
+    clear_masks(c);
+    finish_kan(c);
+  }
+}
+
+// uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)
+MJ_HD int sample_action(uint64_t m0, uint64_t m1, uint32_t seed, uint32_t env_id, uint64_t step, int seat)
+{
+  int n = popc64(m0) + popc64(m1);
+  if (n == 0) return -1;
+  uint32_t r[4];
+  philox((uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seat, 1, seed, env_id, r);
+  int pick = (int)mulhi(r[0], (uint32_t)n);
+  int n0 = popc64(m0);
+  uint64_t m = m0; int base = 0;
+  if (pick >= n0) { pick -= n0; m = m1; base = 64; }
+  for (int i = 0; i < pick; i++) m &= m - 1;
+  return base + ctz64(m);
+}
+
+}  // namespace mj

@@ -1,0 +1,553 @@
+// libmj: HIP kernels (gfx950) and the C ABI of include/mj.h.
+//
+// Kernels map one lane to one environment (64 consecutive environments per
+// wavefront, structure-of-arrays state, see mj_layout.hpp) except the
+// observation writer, which builds bit planes per environment and then streams
+// bytes with all lanes.  Every step kernel first stages the probe part of the
+// per-suit pattern table (row ids + suffix bitmaps, about 11 KB) into LDS.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "../../include/mj.h"
+#include "mj_canon.hpp"
+#include "mj_tables.hpp"
+
+using namespace mj;
+
+static_assert(sizeof(MjEnvCanon) == 744, "canonical record layout");
+static_assert(sizeof(MjHandQuery) == 64 && sizeof(MjHandResult) == 24, "hand records");
+static_assert(sizeof(Glob) == 28, "control bytes");
+
+namespace {
+
+constexpr int kBlock = 256;
+
+struct DevTables {
+  const uint8_t *probe;                  // global: rowid[kRowIdBytes] followed by bitmap[rows * 20]
+  const uint16_t *base, *rowrank;
+  const uint32_t *keyinfo, *recs;
+  int probe_bytes;                       // multiple of 16
+};
+constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
+
+// copy the probe tables into LDS and return a view on them
+__device__ __forceinline__ Lut stage_lut(const DevTables &T, uint16_t *lds)
+{
+  const uint4 *src = (const uint4 *)T.probe;
+  uint4 *dst = (uint4 *)lds;
+  for (int i = threadIdx.x; i < T.probe_bytes / 16; i += blockDim.x) dst[i] = src[i];
+  __syncthreads();
+  Lut L;
+  L.rowid = (const uint8_t *)lds;
+  L.bitmap = (const uint32_t *)((const uint8_t *)lds + kRowIdBytes);
+  L.base = T.base; L.rowrank = T.rowrank; L.keyinfo = T.keyinfo; L.recs = T.recs;
+  return L;
+}
+
+__device__ __forceinline__ void reset_env(Ctx &c, bool first)
+{
+  if (first) {
+    c.e.episode[0] = 0; c.e.serial[0] = 0;
+    __builtin_memset(&c.g, 0, sizeof c.g);
+    clear_result(c);
+#pragma unroll
+    for (int s = 0; s < 4; s++) DELTA(c, s) = 0;
+    c.g.illegal_seat = 255;
+  } else {
+    c.e.episode[0]++; c.e.serial[0]++;
+  }
+  new_game(c);
+}
+
+__global__ void __launch_bounds__(kBlock) k_init(void *state, int64_t B, Rules R, DevTables T)
+{
+  extern __shared__ uint16_t lds[];
+  Lut L = stage_lut(T, lds);
+  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  Ctx c;
+  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  reset_env(c, true);
+  store_glob(c.e, c.g);
+}
+
+__global__ void __launch_bounds__(kBlock) k_reset_done(void *state, int64_t B, Rules R, DevTables T)
+{
+  extern __shared__ uint16_t lds[];
+  Lut L = stage_lut(T, lds);
+  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  Ctx c;
+  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  load_glob(c.e, c.g);
+  if (!c.g.terminated) return;
+  reset_env(c, false);
+  store_glob(c.e, c.g);
+}
+
+__global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions)
+{
+  extern __shared__ uint16_t lds[];
+  Lut L = stage_lut(T, lds);
+  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  Ctx c;
+  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  load_glob(c.e, c.g);
+  uint32_t packed = ((const uint32_t *)actions)[b];
+  int a[4] = {(int8_t)(packed), (int8_t)(packed >> 8), (int8_t)(packed >> 16), (int8_t)(packed >> 24)};
+  step_env(c, a);
+  store_glob(c.e, c.g);
+}
+
+// n_steps of { sample, step, optional reset } without leaving the kernel: environments never interact
+__global__ void __launch_bounds__(kBlock) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
+                                                    int n_steps, int auto_reset)
+{
+  extern __shared__ uint16_t lds[];
+  Lut L = stage_lut(T, lds);
+  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  Ctx c;
+  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  load_glob(c.e, c.g);
+  for (int t = 0; t < n_steps; t++) {
+    int a[4];
+#pragma unroll
+    for (int s = 0; s < 4; s++) a[s] = sample_action(MASK(c, s, 0), MASK(c, s, 1), R.seed, c.env_id, step0 + t, s);
+    step_env(c, a);
+    if (auto_reset && c.g.terminated) reset_env(c, false);
+  }
+  store_glob(c.e, c.g);
+}
+
+// test / scripting aid: give env b the wall in `wall` and deal the current kyoku again from it
+__global__ void __launch_bounds__(kBlock) k_deal_from_wall(void *state, int64_t B, Rules R, DevTables T, int64_t b,
+                                                           const uint8_t *wall)
+{
+  extern __shared__ uint16_t lds[];
+  Lut L = stage_lut(T, lds);
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  Ctx c;
+  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  load_glob(c.e, c.g);
+  for (int i = 0; i < 136; i++) WALL(c, i) = wall[i];
+  deal(c, false);
+  store_glob(c.e, c.g);
+}
+
+__global__ void __launch_bounds__(kBlock) k_sample(void *state, int64_t B, Rules R, uint64_t step, int8_t *actions)
+{
+  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  Env e = make_env(state, B, b);
+  uint32_t packed = 0;
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    int a = sample_action(e.mask[(2 * s) * B], e.mask[(2 * s + 1) * B], R.seed, R.env_id_base + (uint32_t)b, step, s);
+    packed |= (uint32_t)(uint8_t)(int8_t)a << (8 * s);
+  }
+  ((uint32_t *)actions)[b] = packed;
+}
+
+__global__ void __launch_bounds__(kBlock) k_legal_mask(void *state, int64_t B, uint64_t *out)
+{
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;      // one thread per (b, word)
+  if (i >= 8 * B) return;
+  int64_t b = i >> 3;
+  int w = (int)(i & 7);
+  const uint64_t *mask = (const uint64_t *)state + 8 * B;
+  out[i] = mask[(int64_t)w * B + b];
+}
+
+__global__ void __launch_bounds__(kBlock) k_reward(void *state, int64_t B, float penalty, int32_t *delta, float *reward,
+                                                   uint8_t *terminated)
+{
+  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= B) return;
+  Env e = make_env(state, B, b);
+  Glob g;
+  load_glob(e, g);
+  int32_t d[4];
+#pragma unroll
+  for (int s = 0; s < 4; s++) d[s] = e.delta[s * B];
+  if (delta) ((int4 *)delta)[b] = make_int4(d[0], d[1], d[2], d[3]);
+  if (reward) {
+    float r[4];
+#pragma unroll
+    for (int s = 0; s < 4; s++) r[s] = g.illegal_seat == s ? penalty : (float)d[s] * 0.001f;
+    ((float4 *)reward)[b] = make_float4(r[0], r[1], r[2], r[3]);
+  }
+  if (terminated) terminated[b] = g.terminated;
+}
+
+__global__ void __launch_bounds__(kBlock) k_export(void *state, int64_t B, int64_t lo, int64_t n, MjEnvCanon *out)
+{
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  MjEnvCanon o;
+  export_env(make_env(state, B, lo + i), o);
+  out[i] = o;
+}
+__global__ void __launch_bounds__(kBlock) k_import(void *state, int64_t B, int64_t lo, int64_t n, const MjEnvCanon *in)
+{
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  MjEnvCanon o = in[i];
+  import_env(make_env(state, B, lo + i), o);
+}
+
+__global__ void __launch_bounds__(kBlock) k_eval_hands(DevTables T, int64_t n, const MjHandQuery *in, MjHandResult *out)
+{
+  extern __shared__ uint16_t lds[];
+  Lut L = stage_lut(T, lds);
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t *qw = (const uint32_t *)(in + i);
+  uint32_t w[16];
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    uint4 v = ((const uint4 *)qw)[j];
+    w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+  }
+  MjHandQuery q;
+  __builtin_memcpy(&q, w, 64);
+  HandIn hi;
+  for (int su = 0; su < 4; su++) {
+    uint32_t hw = 0;
+    int nr = su == 3 ? 7 : 9;
+    for (int r = 0; r < nr; r++) {
+      uint32_t cnt = q.hand[(su == 3 ? 27 : 9 * su) + r];
+      hw |= (cnt > 7 ? 7u : cnt) << (3 * r);
+    }
+    hi.h[su] = hw;
+  }
+  hi.meldw = (uint64_t)q.meld[0] | (uint64_t)q.meld[1] << 16 | (uint64_t)q.meld[2] << 32 | (uint64_t)q.meld[3] << 48;
+  hi.n_meld = q.n_meld; hi.win = q.win_kind; hi.flags = q.flags; hi.riichi = q.riichi;
+  hi.seat_wind = q.seat_wind; hi.round_wind = q.round_wind; hi.n_ind = q.n_ind; hi.n_aka = q.n_aka; hi.kuitan = q.kuitan;
+  for (int j = 0; j < 5; j++) { hi.ind[j] = q.ind[j]; hi.ura[j] = q.ura[j]; }
+  HandOut ho;
+  eval_hand(L, hi, ho);
+  MjHandResult r;
+  r.yaku = ho.yaku; r.points = ho.points; r.han = (uint8_t)ho.han; r.fu = (uint8_t)ho.fu;
+  r.yakuman_units = (uint8_t)ho.units; r.shape_ok = (uint8_t)ho.shape_ok; r.yaku_ok = (uint8_t)ho.yaku_ok;
+  r.n_dora = (uint8_t)ho.n_dora; r.n_ura = (uint8_t)ho.n_ura; r.n_aka = (uint8_t)ho.n_aka;
+  r.pad_[0] = r.pad_[1] = r.pad_[2] = r.pad_[3] = 0;
+  out[i] = r;
+}
+
+// Observation writer.  A block takes kObsEnvs environments at a time:
+//  1. 4 lanes per env build the per-seat masks, lane 0 of each quad also the env masks (LDS);
+//  2. one lane per (env, viewer) concatenates the 56 planes of 34 bits into a 1904-bit string (LDS);
+//  3. all lanes expand bits to bytes, 16 bytes per store, consecutive lanes on consecutive addresses.
+constexpr int kObsEnvs = 16;
+constexpr int kObsBits = 56 * 34;                 // 1904
+constexpr int kObsWords = 60;                     // u32 words per (env, viewer), 1920 bits
+
+__global__ void __launch_bounds__(kBlock) k_observe(void *state, int64_t B, uint32_t rule_flags, uint8_t *obs)
+{
+  __shared__ uint64_t S[kObsEnvs][4][OB_SEAT_WORDS];
+  __shared__ uint64_t G[kObsEnvs][OG_WORDS];
+  __shared__ uint64_t R[kObsEnvs][4];
+  __shared__ uint32_t own_red[kObsEnvs][4];
+  __shared__ uint32_t bits[kObsEnvs][4][kObsWords];
+  const int tid = threadIdx.x;
+  for (int64_t base = (int64_t)blockIdx.x * kObsEnvs; base < B; base += (int64_t)gridDim.x * kObsEnvs) {
+    int nenv = (int)((B - base) < kObsEnvs ? (B - base) : kObsEnvs);
+    if (tid < 4 * nenv) {
+      int el = tid >> 2, s = tid & 3;
+      Env e = make_env(state, B, base + el);
+      uint64_t m[OB_SEAT_WORDS];
+      R[el][s] = obs_seat_masks(e, s, m);
+#pragma unroll
+      for (int i = 0; i < OB_SEAT_WORDS; i++) S[el][s][i] = m[i];
+      own_red[el][s] = e.seatw[s * B] & 7u;
+    }
+    __syncthreads();
+    if (tid < nenv) {
+      Env e = make_env(state, B, base + tid);
+      Glob g;
+      load_glob(e, g);
+      uint64_t m[OG_WORDS];
+      obs_env_masks(e, g, rule_flags, R[tid][0] | R[tid][1] | R[tid][2] | R[tid][3], m);
+#pragma unroll
+      for (int i = 0; i < OG_WORDS; i++) G[tid][i] = m[i];
+    }
+    __syncthreads();
+    if (tid < 4 * nenv) {
+      int el = tid >> 2, me = tid & 3;
+      uint32_t *out = bits[el][me];
+      uint64_t acc = 0;
+      int fill = 0, wpos = 0;                 // fill stays even and <= 30 before each plane is added
+      for (int p = 0; p < 56; p++) {
+        uint64_t v = obs_plane(p, me, &S[el][0][0], own_red[el][me], G[el]) & K_ALL;
+        acc |= v << fill;
+        fill += 34;
+        while (fill >= 32) { out[wpos++] = (uint32_t)acc; acc >>= 32; fill -= 32; }
+      }
+      while (wpos < kObsWords) { out[wpos++] = (uint32_t)acc; acc = 0; }
+    }
+    __syncthreads();
+    // 7616 bytes per env = 476 stores of 16 bytes; 16 bytes = 16 bits of the string
+    const int per_env = 4 * kObsBits / 16;
+    uint4 *dst = (uint4 *)(obs + (size_t)base * 4 * kObsBits);
+    for (int i = tid; i < nenv * per_env; i += kBlock) {
+      int el = i / per_env, j = i - el * per_env;          // j-th 16-byte group of env el
+      int me = j / (kObsBits / 16), q = j - me * (kObsBits / 16);
+      uint32_t word = bits[el][me][q >> 1];
+      uint32_t v = (q & 1) ? word >> 16 : word & 0xFFFFu;
+      uint4 o;
+      o.x = ((v & 0xFu) * 0x00204081u) & 0x01010101u;
+      o.y = (((v >> 4) & 0xFu) * 0x00204081u) & 0x01010101u;
+      o.z = (((v >> 8) & 0xFu) * 0x00204081u) & 0x01010101u;
+      o.w = (((v >> 12) & 0xFu) * 0x00204081u) & 0x01010101u;
+      dst[i] = o;
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ host side
+struct MjHandle {
+  int64_t B;
+  Rules R;
+  MjRules rules;
+  uint64_t step;
+  void *d_state, *d_scratch;
+  DevTables T;
+  size_t lds_bytes;
+  hipEvent_t ev[2];
+  int ev_steps;
+  bool ev_valid;
+};
+
+namespace {
+
+const mjt::SuitTables &tables()
+{
+  static const mjt::SuitTables t = mjt::build();
+  return t;
+}
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+struct ScratchLayout { size_t probe, base, rowrank, keyinfo, recs, total, probe_bytes; };
+ScratchLayout scratch_layout()
+{
+  const mjt::SuitTables &t = tables();
+  ScratchLayout s;
+  s.probe = 0;
+  s.probe_bytes = t.rowid.size() + t.bitmap.size() * 4;
+  s.base = align256(s.probe_bytes);
+  s.rowrank = align256(s.base + t.base.size() * 2);
+  s.keyinfo = align256(s.rowrank + t.rowrank.size() * 2);
+  s.recs = align256(s.keyinfo + t.keyinfo.size() * 4);
+  s.total = align256(s.recs + t.recs.size() * 4);
+  return s;
+}
+size_t scratch_bytes_impl() { return scratch_layout().total; }
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
+inline int check(hipError_t e) { return e == hipSuccess ? MJ_OK : MJ_E_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *mj_strerror(int code)
+{
+  switch (code) {
+    case MJ_OK: return "ok";
+    case MJ_E_ARG: return "bad argument";
+    case MJ_E_HIP: return "HIP call or kernel launch failed";
+    case MJ_E_NOMEM: return "host allocation failed";
+    case MJ_E_UNSUPPORTED: return "device cannot run the kernels";
+    default: return "unknown error";
+  }
+}
+
+size_t mj_state_bytes(int64_t B, const MjRules *rules)
+{
+  if (B <= 0 || !rules) return 0;
+  return (size_t)B * (size_t)kBytesPerEnv;
+}
+size_t mj_scratch_bytes(int64_t B, const MjRules *rules)
+{
+  if (B <= 0 || !rules) return 0;
+  return scratch_bytes_impl();
+}
+
+int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t seed, const MjRules *rules, void *stream)
+{
+  if (!out || !d_state || !d_scratch || !rules || B <= 0 || (seed >> 32) || rules->mode > 2) return MJ_E_ARG;
+  if (((uintptr_t)d_state & 15) || ((uintptr_t)d_scratch & 15)) return MJ_E_ARG;
+  MjHandle *h = new (std::nothrow) MjHandle();
+  if (!h) return MJ_E_NOMEM;
+  h->B = B; h->rules = *rules; h->step = 0; h->d_state = d_state; h->d_scratch = d_scratch;
+  h->R.flags = rules->flags; h->R.env_id_base = rules->env_id_base; h->R.start_score = rules->start_score;
+  h->R.illegal_penalty = rules->illegal_penalty; h->R.mode = rules->mode; h->R.seed = (uint32_t)seed;
+  h->ev_valid = false; h->ev_steps = 0;
+  const mjt::SuitTables &t = tables();
+  const ScratchLayout sl = scratch_layout();
+  if (t.rowid.size() != (size_t)kRowIdBytes || (sl.probe_bytes & 15)) { delete h; return MJ_E_UNSUPPORTED; }
+  int dev = 0, lds_max = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) { delete h; return MJ_E_HIP; }
+  if ((size_t)lds_max < sl.probe_bytes) { delete h; return MJ_E_UNSUPPORTED; }
+  h->lds_bytes = sl.probe_bytes;
+  hipStream_t st = (hipStream_t)stream;
+  // table image in the caller's scratch buffer
+  std::vector<uint8_t> img(sl.total, 0);
+  std::memcpy(img.data() + sl.probe, t.rowid.data(), t.rowid.size());
+  std::memcpy(img.data() + sl.probe + t.rowid.size(), t.bitmap.data(), t.bitmap.size() * 4);
+  std::memcpy(img.data() + sl.base, t.base.data(), t.base.size() * 2);
+  std::memcpy(img.data() + sl.rowrank, t.rowrank.data(), t.rowrank.size() * 2);
+  std::memcpy(img.data() + sl.keyinfo, t.keyinfo.data(), t.keyinfo.size() * 4);
+  std::memcpy(img.data() + sl.recs, t.recs.data(), t.recs.size() * 4);
+  int rc = check(hipMemcpyAsync(d_scratch, img.data(), sl.total, hipMemcpyHostToDevice, st));
+  if (rc == MJ_OK) rc = check(hipStreamSynchronize(st));       // the host image goes away
+  char *sc = (char *)d_scratch;
+  h->T.probe = (const uint8_t *)(sc + sl.probe);
+  h->T.base = (const uint16_t *)(sc + sl.base);
+  h->T.rowrank = (const uint16_t *)(sc + sl.rowrank);
+  h->T.keyinfo = (const uint32_t *)(sc + sl.keyinfo);
+  h->T.recs = (const uint32_t *)(sc + sl.recs);
+  h->T.probe_bytes = (int)sl.probe_bytes;
+  if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[0]));
+  if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[1]));
+  if (rc != MJ_OK) { delete h; return rc; }
+  k_init<<<blocks_for(B), kBlock, h->lds_bytes, st>>>(d_state, B, h->R, h->T);
+  rc = check(hipGetLastError());
+  if (rc != MJ_OK) { delete h; return rc; }
+  *out = h;
+  return MJ_OK;
+}
+
+int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
+{
+  if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
+  k_step<<<blocks_for(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, d_actions);
+  h->step++;
+  return check(hipGetLastError());
+}
+
+int mj_legal_mask(const MjHandle *h, uint64_t *d_mask, void *stream)
+{
+  if (!h || !d_mask) return MJ_E_ARG;
+  k_legal_mask<<<blocks_for(8 * h->B), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, d_mask);
+  return check(hipGetLastError());
+}
+
+int mj_observe(const MjHandle *h, uint8_t *d_obs, void *stream)
+{
+  if (!h || !d_obs || ((uintptr_t)d_obs & 15)) return MJ_E_ARG;
+  int64_t groups = (h->B + kObsEnvs - 1) / kObsEnvs;
+  unsigned grid = (unsigned)(groups < 65536 ? groups : 65536);
+  k_observe<<<grid, kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, d_obs);
+  return check(hipGetLastError());
+}
+
+int mj_reward(const MjHandle *h, int32_t *d_delta, float *d_reward, uint8_t *d_terminated, void *stream)
+{
+  if (!h || ((uintptr_t)d_delta & 15) || ((uintptr_t)d_reward & 15)) return MJ_E_ARG;
+  k_reward<<<blocks_for(h->B), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.illegal_penalty, d_delta, d_reward,
+                                                                 d_terminated);
+  return check(hipGetLastError());
+}
+
+int mj_reset_done(MjHandle *h, void *stream)
+{
+  if (!h) return MJ_E_ARG;
+  k_reset_done<<<blocks_for(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T);
+  return check(hipGetLastError());
+}
+
+int mj_sample_random(const MjHandle *h, int8_t *d_actions, void *stream)
+{
+  if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
+  k_sample<<<blocks_for(h->B), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->step, d_actions);
+  return check(hipGetLastError());
+}
+
+int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, uint8_t *d_obs, void *stream)
+{
+  if (!h || n_steps < 0 || (write_obs && (!d_obs || ((uintptr_t)d_obs & 15)))) return MJ_E_ARG;
+  if (n_steps == 0) return MJ_OK;
+  hipStream_t st = (hipStream_t)stream;
+  int rc = check(hipEventRecord(h->ev[0], st));
+  if (rc != MJ_OK) return rc;
+  if (!write_obs) {
+    // environments never interact, so many steps run inside one launch; chunked to bound a launch's duration
+    for (int t = 0; t < n_steps && rc == MJ_OK; t += MJ_ROLLOUT_CHUNK) {
+      int n = n_steps - t < MJ_ROLLOUT_CHUNK ? n_steps - t : MJ_ROLLOUT_CHUNK;
+      k_rollout<<<blocks_for(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
+      rc = check(hipGetLastError());
+    }
+  } else {
+    for (int t = 0; t < n_steps && rc == MJ_OK; t++) {
+      k_rollout<<<blocks_for(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset);
+      rc = check(hipGetLastError());
+      if (rc == MJ_OK) rc = mj_observe(h, d_obs, stream);
+    }
+  }
+  if (rc != MJ_OK) return rc;
+  h->step += (uint64_t)n_steps;
+  rc = check(hipEventRecord(h->ev[1], st));
+  h->ev_valid = rc == MJ_OK;
+  h->ev_steps = n_steps;
+  return rc;
+}
+
+int mj_export(const MjHandle *h, int64_t env_lo, int64_t n, MjEnvCanon *d_out, void *stream)
+{
+  if (!h || !d_out || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
+  if (n == 0) return MJ_OK;
+  k_export<<<blocks_for(n), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_out);
+  return check(hipGetLastError());
+}
+int mj_import(MjHandle *h, int64_t env_lo, int64_t n, const MjEnvCanon *d_in, void *stream)
+{
+  if (!h || !d_in || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
+  if (n == 0) return MJ_OK;
+  k_import<<<blocks_for(n), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_in);
+  return check(hipGetLastError());
+}
+
+int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandResult *d_out, void *stream)
+{
+  if (!h || n < 0 || !d_in || !d_out || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 7)) return MJ_E_ARG;
+  if (n == 0) return MJ_OK;
+  k_eval_hands<<<blocks_for(n), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->T, n, d_in, d_out);
+  return check(hipGetLastError());
+}
+
+int mj_deal_from_wall(MjHandle *h, int64_t b, const uint8_t *d_wall, void *stream)
+{
+  if (!h || !d_wall || b < 0 || b >= h->B) return MJ_E_ARG;
+  k_deal_from_wall<<<1, kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, b, d_wall);
+  return check(hipGetLastError());
+}
+
+uint64_t mj_step_count(const MjHandle *h) { return h ? h->step : 0; }
+
+float mj_last_step_kernel_ms(MjHandle *h)
+{
+  if (!h || !h->ev_valid || h->ev_steps <= 0) return -1.0f;
+  if (hipEventSynchronize(h->ev[1]) != hipSuccess) return -1.0f;
+  float ms = 0;
+  if (hipEventElapsedTime(&ms, h->ev[0], h->ev[1]) != hipSuccess) return -1.0f;
+  return ms / (float)h->ev_steps;
+}
+
+int mj_destroy(MjHandle *h)
+{
+  if (!h) return MJ_E_ARG;
+  (void)hipEventDestroy(h->ev[0]);
+  (void)hipEventDestroy(h->ev[1]);
+  delete h;
+  return MJ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+"""The C-ABI library loads and exports every symbol that include/mj.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mj.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mj_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    for must in ("mj_init", "mj_step", "mj_legal_mask", "mj_observe", "mj_reward", "mj_reset_done",
+                 "mj_sample_random", "mj_step_random", "mj_export", "mj_import", "mj_eval_hands", "mj_destroy"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    so = os.path.join(ROOT, "paper_2605_20577_amd", "libmj.so")
+    if not os.path.exists(so):
+        from paper_2605_20577_amd import build
+        build.build()
+    lib = ctypes.CDLL(so)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    import paper_2605_20577_amd.binding as b
+    assert sorted(b.EXPORTS) == declared_functions()
+    lib.mj_strerror.restype = ctypes.c_char_p
+    assert lib.mj_strerror(-1) == b"bad argument"
+    r = b.MjRules(12, 0, 25000, -1.0, 2)
+    assert b.mj_state_bytes(65536, r) == 65536 * 652 and b.mj_state_bytes(0, r) == 0
+    assert 0 < b.mj_scratch_bytes(1, r) < 1 << 20
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch):
+    import paper_2605_20577_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_SO", os.path.join(ROOT, "no_such_dir", "libmj.so"))
+    with pytest.raises(RuntimeError):
+        b.lib()

@@ -1,0 +1,157 @@
+"""GPU tier: the HIP library through its C ABI against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import mjo
+from tests.engines import GpuEngine, diff_records
+from tests import handtext
+from workloads import hands
+
+pytestmark = pytest.mark.gpu
+
+
+def _trace(B, seed, flags, mode, steps, reset_every=1, check_every=1, env_id_base=0):
+    o = mjo.Oracle(B, seed, flags, mode, env_id_base=env_id_base)
+    g = GpuEngine(B, seed=seed, flags=flags, mode=mode, env_id_base=env_id_base)
+    for t in range(steps):
+        if t % check_every == 0:
+            d = diff_records(o.export(), g.export())
+            assert not d, (t, d[:4])
+            assert np.array_equal(o.legal_mask(), g.legal_mask())
+        a, a2 = o.sample_random(), g.sample_random()
+        assert np.array_equal(a, a2), t
+        o.step(a); g.step(a)
+        if t % check_every == 0:
+            for x, y in zip(o.reward(), g.reward()):
+                assert np.array_equal(x, y), t
+        if t % reset_every == 0:
+            o.reset_done(); g.reset_done()
+    d = diff_records(o.export(), g.export())
+    assert not d, d[:4]
+    return o, g
+
+
+def test_single_kyoku_full_trace():
+    """B=256, no-red, one kyoku per game, every state / mask / reward of the trace until all games are over"""
+    B = 256
+    o = mjo.Oracle(B, 0, mjo.RULES_NORED, mjo.MODE_SINGLE)
+    g = GpuEngine(B, seed=0, flags=mjo.RULES_NORED, mode=mjo.MODE_SINGLE)
+    ends = None
+    for t in range(400):
+        eo, eg = o.export(), g.export()
+        d = diff_records(eo, eg)
+        assert not d, (t, d[:4])
+        assert np.array_equal(o.legal_mask(), g.legal_mask())
+        if eo["terminated"].all():
+            ends = np.bincount(eo["end_type"], minlength=10)
+            break
+        a, a2 = o.sample_random(), g.sample_random()
+        assert np.array_equal(a, a2)
+        o.step(a); g.step(a)
+        for x, y in zip(o.reward(), g.reward()):
+            assert np.array_equal(x, y)
+    assert ends is not None and ends[3] > 100 and ends[1] + ends[2] > 0
+
+
+def test_hanchan_red_trace_with_reset_and_observation():
+    o, g = _trace(192, 5, mjo.RULES_RED, mjo.MODE_HALF, 1500, reset_every=2)
+    assert np.array_equal(o.observe(), g.observe())
+    assert o.export()["episode"].max() >= 1
+
+
+def test_east_mode_with_abortive_draws():
+    _trace(128, 9, mjo.RULES_NORED | mjo.F_ABORT, mjo.MODE_EAST, 700)
+
+
+@pytest.mark.parametrize("B", [1, 63, 257, 1000])
+def test_ragged_batch_sizes(B):
+    o, g = _trace(B, 2, mjo.RULES_RED, mjo.MODE_HALF, 150, check_every=10)
+    assert np.array_equal(o.observe(), g.observe())
+
+
+def test_fused_rollout_equals_unfused_and_oracle():
+    B = 1536
+    o = mjo.Oracle(B, 4, mjo.RULES_NORED, mjo.MODE_HALF)
+    g = GpuEngine(B, seed=4, flags=mjo.RULES_NORED, mode=mjo.MODE_HALF)
+    for n in (1, 37, 128, 300):                       # also crosses the per-launch chunk of the fused path
+        o.step_random(n); g.step_random(n)
+        d = diff_records(o.export(), g.export())
+        assert not d, (n, d[:4])
+    assert g.env.step_count == o.step_count == 466
+    # fused path with observations
+    import torch
+    obs = torch.zeros((B, 4, 56, 34), dtype=torch.uint8, device="cuda:0")
+    o.step_random(3); g.env.step_random(3, True, obs)
+    assert not diff_records(o.export(), g.export())
+    assert np.array_equal(o.observe(), obs.cpu().numpy())
+
+
+def test_full_size_sampled_envs():
+    """B=65,536 in the benchmark's launch shape; sampled environments recomputed one by one by the oracle"""
+    B, steps = 65536, 400
+    for flags in (mjo.RULES_NORED, mjo.RULES_RED):
+        g = GpuEngine(B, seed=0, flags=flags, mode=mjo.MODE_HALF)
+        g.step_random(steps)
+        rng = np.random.default_rng(1)
+        ids = sorted(set([0, 1, 63, 64, 255, 256, B - 1] + rng.integers(0, B, 25).tolist()))
+        for b in ids:
+            o = mjo.Oracle(1, 0, flags, mjo.MODE_HALF, env_id_base=b)
+            o.step_random(steps)
+            d = diff_records(o.export(), g.export(b, 1))
+            assert not d, (b, d[:4])
+        # properties over the whole batch
+        e = g.export()
+        assert (e["score"].sum(1) + 1000 * e["kyotaku"].astype(np.int64) == 100000).all()
+        assert (e["terminated"] == 0).all() and (e["actor_mask"] != 0).all()
+        assert (e["live_left"].astype(int) == 70 - (e["draw_ptr"].astype(int) - 52) - e["n_kan"]).all()
+        g.close()
+
+
+def test_import_export_roundtrip():
+    o = mjo.Oracle(64, 8, mjo.RULES_RED, mjo.MODE_HALF)
+    o.step_random(333)
+    g = GpuEngine(64, seed=8, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    g.import_(o.export())
+    assert not diff_records(o.export(), g.export())
+    # continue from the imported state: the step counters differ, so drive both with the oracle's actions
+    for _ in range(100):
+        a = o.sample_random()
+        o.step(a); g.step(a)
+        o.reset_done(); g.reset_done()
+    d = diff_records(o.export(), g.export())
+    assert not d, d[:4]
+
+
+def test_illegal_action():
+    o, g = mjo.Oracle(8, 1), GpuEngine(8, seed=1)
+    a = o.sample_random()
+    a[3, int(o.export()["cur"][3])] = 74          # RON on the own turn
+    a[5, :] = -1
+    o.step(a); g.step(a)
+    assert not diff_records(o.export(), g.export())
+    for x, y in zip(o.reward(), g.reward()):
+        assert np.array_equal(x, y)
+    assert g.reward()[1][3].min() == -1.0 and g.export()["end_type"][3] == 9
+
+
+def test_worked_hands_on_gpu():
+    g = GpuEngine(1)
+    cases = handtext.load(mjo.QUERY_DTYPE)
+    r = g.eval_hands(np.array([c[1] for c in cases]))
+    for (name, q, exp), got in zip(cases, r):
+        for k, v in exp.items():
+            assert int(got[k]) == v, (name, k, int(got[k]), v)
+
+
+def test_hand_microbatch_full_size():
+    """2^20 hands on the GPU; all of them against the oracle"""
+    g = GpuEngine(1)
+    q = hands.generate(1 << 20, mjo.QUERY_DTYPE, seed=0)
+    rg = g.eval_hands(q)
+    ro = mjo.eval_hands(q)
+    bad = np.flatnonzero((ro.view(np.uint8).reshape(-1, 24) != rg.view(np.uint8).reshape(-1, 24)).any(1))
+    assert bad.size == 0, (bad[:5], ro[bad[:2]], rg[bad[:2]])
+    assert ro["yaku_ok"].sum() > 250000 and (ro["yakuman_units"] > 0).sum() > 1000
+    # edge cases: empty batch, ragged tail
+    assert g.eval_hands(q[:0]).size == 0
+    assert g.eval_hands(q[:257]).tobytes() == ro[:257].tobytes()

@@ -1,7 +1,12 @@
-"""Scripted scenarios, one rule each, on stacked walls.  Expected values follow from the rule text."""
+"""Scripted scenarios, one rule each, on stacked walls.  Expected values follow from the rule text.
+
+Every scenario runs on the oracle, on the host build of the kernels' code, and (marked gpu) on the HIP library.
+"""
 import numpy as np
+import pytest
 
 from oracle import mjo
+from tests.engines import make_engine
 from tests.scenario import (A_CHI_H, A_CHI_L, A_CHI_M, A_KAN, A_PASS, A_PON, A_RIICHI, A_RON, A_TSUMO, A_KYUUSHU,
                             A_MINKAN, J1, J2, J3, act, bits, build_wall, kind)
 from tests.invariants import check_env
@@ -10,11 +15,14 @@ TENPAI = "234m 34p 456p 22s 678s"          # waits 2p / 5p; pinfu + tanyao
 TENPAI2 = "234m 34p 678p 33s 678s"         # the same waits from different tiles
 
 
-def engine(flags=mjo.RULES_NORED, mode=mjo.MODE_SINGLE, **kw):
-    return mjo.Oracle(1, seed=0, flags=flags, mode=mode, **kw)
+@pytest.fixture(params=["oracle", "hostsim", pytest.param("gpu", marks=pytest.mark.gpu)])
+def engine(request):
+    def make(flags=mjo.RULES_NORED, mode=mjo.MODE_SINGLE, **kw):
+        return make_engine(request.param, 1, seed=0, flags=flags, mode=mode, **kw)
+    return make
 
 
-def test_tenhou():
+def test_tenhou(engine):
     o = engine()
     o.deal_from_wall(0, build_wall([TENPAI, J1, J2, J3], draws="5p", dora="1z"))
     e = o.export()[0]
@@ -25,7 +33,7 @@ def test_tenhou():
     assert e["final_rank"].tolist() == [0, 1, 2, 3] and e["gain"][0] == 48000
 
 
-def test_double_ron_honba_sticks_and_rotation():
+def test_double_ron_honba_sticks_and_rotation(engine):
     o = engine(mode=mjo.MODE_HALF)
     o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, TENPAI2, J3], draws="1m", dora="1z"))
     e = o.export()
@@ -46,7 +54,7 @@ def test_double_ron_honba_sticks_and_rotation():
     check_env(e, mjo.RULES_NORED)
 
 
-def test_pon_beats_chi_and_kuikae():
+def test_pon_beats_chi_and_kuikae(engine):
     o = engine()
     hands = [J1, "4567m258p369s567z", "44m 369p147s456z 11p", J3]
     o.deal_from_wall(0, build_wall(hands, draws="1m"))
@@ -75,7 +83,7 @@ def test_pon_beats_chi_and_kuikae():
     assert e["kuikae"].tolist() == [255, 255] and e["cur"] == 2
 
 
-def test_furiten_permanent_and_temporary():
+def test_furiten_permanent_and_temporary(engine):
     # own discard among the waits: no ron
     o = engine()
     o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, J2, J3], draws="1m"))
@@ -100,7 +108,7 @@ def test_furiten_permanent_and_temporary():
     assert A_RON in bits(e["mask"][1])                     # the temporary furiten is over
 
 
-def test_temporary_furiten_blocks_same_go_around():
+def test_temporary_furiten_blocks_same_go_around(engine):
     o = engine()
     hands = ["5p " + J1[1:], J3, "2p 58m369p147s4567z", TENPAI]
     # seat 3 waits on 2p/5p; seat 0 cuts 5p (seat 3 passes), then seat 2 cuts 2p in the same go-around
@@ -114,7 +122,7 @@ def test_temporary_furiten_blocks_same_go_around():
     assert bits(e["mask"][3]) == [A_CHI_L, A_PASS]               # the shape fits, but no ron in the same go-around
 
 
-def test_riichi_ippatsu_tsumo_ura():
+def test_riichi_ippatsu_tsumo_ura(engine):
     o = engine()
     o.deal_from_wall(0, build_wall([TENPAI, J1, J2, J3], draws="6p 5z 6z 7z 5p", dora="1z", ura="1s"))
     e = o.export()[0]
@@ -135,7 +143,7 @@ def test_riichi_ippatsu_tsumo_ura():
     assert e["delta"].tolist() == [25000, -8000, -8000, -8000] and e["score"][0] == 49000
 
 
-def test_riichi_discard_ronned_keeps_the_stick():
+def test_riichi_discard_ronned_keeps_the_stick(engine):
     o = engine()
     o.deal_from_wall(0, build_wall(["234m 34p 456p 22s 67s 5p", TENPAI2, J2, J3], draws="8s", dora="1z"))
     # seat 0: tenpai after cutting 5p (waits 2p/5p itself would be furiten, irrelevant); seat 1 wins on it
@@ -147,7 +155,7 @@ def test_riichi_discard_ronned_keeps_the_stick():
     assert e["kyotaku"] == 0 and e["delta"].tolist() == [-2000, 2000, 0, 0] and e["riichi"][0] == 0
 
 
-def test_kakan_robbed():
+def test_kakan_robbed(engine):
     o = engine()
     hands = ["55p 147m 28p 369s 123z", "5p 258m 39p 147s 1247z", "234m 46p 456s 22s 678s", J3]
     o2 = engine()
@@ -165,7 +173,7 @@ def test_kakan_robbed():
     assert e["delta"].tolist() == [-2600, 0, 2600, 0]
 
 
-def test_ankan_rinshan_and_new_dora():
+def test_ankan_rinshan_and_new_dora(engine):
     o = engine()
     hands = ["111m 34p 456p 22s 678s", "47m258p369s1234z9m", J2, J3]
     o.deal_from_wall(0, build_wall(hands, draws="1m", rinshan="5p", dora="1z 1s"))
@@ -182,7 +190,7 @@ def test_ankan_rinshan_and_new_dora():
     assert e["delta"].tolist() == [12000, -4000, -4000, -4000]
 
 
-def test_abortive_draws():
+def test_abortive_draws(engine):
     flags = mjo.RULES_NORED | mjo.F_ABORT
     o = engine(flags=flags, mode=mjo.MODE_HALF)
     h = lambda base: "1z " + base
@@ -204,7 +212,7 @@ def test_abortive_draws():
     assert A_KYUUSHU not in bits(o.export()[0]["mask"][0])
 
 
-def test_bust_ends_the_game():
+def test_bust_ends_the_game(engine):
     o = engine(mode=mjo.MODE_HALF)
     o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, J2, J3], draws="1m", dora="1z"))
     e = o.export()
