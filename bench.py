@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--batch", type=int, default=65536)
     ap.add_argument("--no-extras", action="store_true", help="skip the red-rule and observation side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB three times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (environments are independent; see DESIGN.md for sharding); "
@@ -70,6 +72,14 @@ def main():
     import paper_2605_20577_amd as mj
     assert torch.cuda.is_available(), "needs an MI355X"
     B, K, W = args.batch, args.steps, args.warmup
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}))
+        return
 
     env = mj.MahjongEnv(B, seed=0, flags=mj.RULES_NORED, mode=mj.MODE_HALF)
     dt, step_ms = timed_rollout(env, torch, W, K)

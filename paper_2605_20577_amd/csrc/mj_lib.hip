@@ -502,23 +502,26 @@ int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, 
 
 int mj_export(const MjHandle *h, int64_t env_lo, int64_t n, MjEnvCanon *d_out, void *stream)
 {
-  if (!h || !d_out || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
+  if (!h || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
   if (n == 0) return MJ_OK;
+  if (!d_out) return MJ_E_ARG;
   k_export<<<blocks_for(n), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_out);
   return check(hipGetLastError());
 }
 int mj_import(MjHandle *h, int64_t env_lo, int64_t n, const MjEnvCanon *d_in, void *stream)
 {
-  if (!h || !d_in || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
+  if (!h || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
   if (n == 0) return MJ_OK;
+  if (!d_in) return MJ_E_ARG;
   k_import<<<blocks_for(n), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_in);
   return check(hipGetLastError());
 }
 
 int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandResult *d_out, void *stream)
 {
-  if (!h || n < 0 || !d_in || !d_out || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 7)) return MJ_E_ARG;
-  if (n == 0) return MJ_OK;
+  if (!h || n < 0) return MJ_E_ARG;
+  if (n == 0) return MJ_OK;                               // an empty batch needs no buffers
+  if (!d_in || !d_out || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 7)) return MJ_E_ARG;
   k_eval_hands<<<blocks_for(n), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->T, n, d_in, d_out);
   return check(hipGetLastError());
 }
