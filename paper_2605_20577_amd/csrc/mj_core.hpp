@@ -22,6 +22,9 @@
 #ifndef MJ_HD
 #define MJ_HD __host__ __device__ __forceinline__
 #endif
+#ifndef MJ_STAT
+#define MJ_STAT(x) ((void)0)
+#endif
 #ifndef MJ_HD_NOINLINE
 #define MJ_HD_NOINLINE __host__ __device__ __attribute__((noinline))
 #endif
@@ -61,14 +64,18 @@ struct Lut {
   const uint32_t *recs;
 };
 
-// One environment's view of the structure-of-arrays state: element i of a
-// field lives at ptr[i * n].  (n = B and ptr = base + b for state in HBM.)
+// One environment's view of the structure-of-arrays state.  "Hot" fields (touched by every step) live at
+// ptr[i * hs]; the step kernels keep them in LDS (hs = block size, ptr = LDS base + thread) and every other
+// user reads them in HBM (hs = n).  "Cold" fields always live in HBM at ptr[i * n] (n = B, ptr = base + b).
 struct Env {
-  int64_t n;
-  uint64_t *dk, *waits, *mask, *yaku, *meld, *resw;   // [4] [4] [8] [4] [4] [4]
-  int32_t *score, *delta, *gain;                      // [4] each
-  uint32_t *episode, *serial, *hand, *seatw, *glob;   // [1] [1] [16] [4] [7]
-  uint8_t *wall, *river;                              // [136] [128]
+  int64_t n, hs;
+  uint64_t *dk, *waits, *mask, *meld;                 // hot  [4] [4] [8] [4]
+  int32_t *score, *delta;                             // hot  [4] [4]
+  uint32_t *episode, *serial, *hand, *seatw;          // hot  [1] [1] [16] [4]
+  uint64_t *yaku, *resw;                              // cold [4] [4]
+  int32_t *gain;                                      // cold [4]
+  uint32_t *glob;                                     // cold [7] (held in registers during a step)
+  uint8_t *wall, *river;                              // cold [136] [128]
 };
 
 // control bytes kept in registers during a step (7 words in HBM)
@@ -131,6 +138,7 @@ MJ_HD uint32_t suffix5(uint32_t w) { return cnt3(w, 5) + 5 * cnt3(w, 6) + 25 * c
 // is the suit word (counts 0..4) a valid pattern?  Two dependent LDS reads.
 MJ_HD bool lut_valid(const Lut &L, uint32_t w)
 {
+  MJ_STAT(n_lut);
   uint32_t s = suffix5(w);
   uint32_t row = L.rowid[prefix5(w)];
   return (L.bitmap[row * 20 + (s >> 5)] >> (s & 31)) & 1u;
@@ -188,74 +196,192 @@ MJ_HD int meld_count(uint32_t m, int k)
 }
 MJ_HD int hand_count(const uint32_t h[4], int k) { int su = suit_of(k); return cnt3(h[su], rank_of(k, su)); }
 
+MJ_HD bool suit_valid(const Lut &L, int su, uint32_t w) { return su == 3 ? honors_valid(w) : lut_valid(L, w); }
+// ranks r (bit r) with count < 4 whose addition makes the suit word valid
+MJ_HD uint32_t suit_addmask(const Lut &L, int su, uint32_t w)
+{
+  uint32_t m = 0;
+  if (su < 3) {
+#pragma unroll
+    for (int r = 0; r < 9; r++)
+      if (cnt3(w, r) < 4 && lut_valid(L, w + (1u << (3 * r)))) m |= 1u << r;
+  } else {
+    // honors: a single becomes the pair, a pair becomes a triplet; the other counts must already fit
+    uint32_t one = fields_eq(w, 1), two = fields_eq(w, 2), four = (w >> 2) & O111;
+    if (four) return 0;
+    int n1 = popc32(one), n2 = popc32(two);
+    uint32_t cand = 0;
+    if (n1 == 1 && n2 == 0) cand = one;                 // 1 -> 2: the pair
+    else if (n1 == 0 && n2 == 1) cand = two;            // 2 -> 3, no pair left here
+    else if (n1 == 0 && n2 == 2) cand = two;            // one of two pairs becomes a triplet
+    else if (n1 == 1 && n2 == 1) cand = 0;              // a single and a pair can not both be fixed
+    m = squeeze9(cand) & 0x7Fu;
+  }
+  return m;
+}
+// kinds of which the seat owns four or more once its melds are counted (concealed four-of-a-kind included)
+MJ_HD uint64_t own4_mask(const uint32_t h[4], uint64_t meldw, int n_meld)
+{
+  uint64_t full = 0;
+#pragma unroll
+  for (int su = 0; su < 4; su++) full |= (uint64_t)squeeze9((h[su] >> 2) & O111) << (9 * su);
+  for (int j = 0; j < n_meld; j++) {
+    uint32_t m = meld_at(meldw, j);
+    int t = m_type(m), b = m_kind(m), span = t == MT_CHI ? 3 : 1;
+    for (int d = 0; d < span; d++) {
+      int k = b + d, own = hand_count(h, k);
+      for (int i = 0; i < n_meld; i++) own += meld_count(meld_at(meldw, i), k);
+      if (own >= 4) full |= kbit(k);
+    }
+  }
+  return full;
+}
+struct SpecialCounts { int c1, c2, c3, c4, yao_tiles, total; };
+MJ_HD SpecialCounts special_counts(const uint32_t h[4])
+{
+  SpecialCounts c = {0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int su = 0; su < 4; su++) {
+    c.c1 += popc32(fields_eq(h[su], 1)); c.c2 += popc32(fields_eq(h[su], 2));
+    c.c3 += popc32(fields_eq(h[su], 3)); c.c4 += popc32(fields_eq(h[su], 4));
+    c.yao_tiles += su == 3 ? tiles_in(h[3]) : cnt3(h[su], 0) + cnt3(h[su], 8);
+  }
+  c.total = c.c1 + 2 * c.c2 + 3 * c.c3 + 4 * c.c4;
+  return c;
+}
+MJ_HD uint64_t kinds_where(const uint32_t h[4], int v)     // 34-bit mask of kinds whose count equals v
+{
+  uint64_t m = 0;
+#pragma unroll
+  for (int su = 0; su < 4; su++) m |= (uint64_t)squeeze9(fields_eq(h[su], v)) << (9 * su);
+  return m;
+}
+
 // Waits of a (13 - 3*n_meld)-tile hand: kinds whose addition completes it and
 // of which the seat owns fewer than four.
 MJ_HD_NOINLINE uint64_t waits_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
 {
+  MJ_STAT(n_waits);
   uint32_t h[4] = {h0, h1, h2, h3};
   uint64_t w = 0;
-  int n[4], r1 = 0, r2 = 0;
+  int rem[4], r1 = 0, r2 = 0;
 #pragma unroll
   for (int s = 0; s < 4; s++) {
-    n[s] = tiles_in(h[s]);
-    int r = n[s] % 3;
-    r1 += r == 1; r2 += r == 2;
+    rem[s] = tiles_in(h[s]) % 3;
+    r1 += rem[s] == 1; r2 += rem[s] == 2;
   }
-  // standard form: one suit takes the tile, the others must already be valid
+  // standard form: the suit that takes the tile has remainder 1 (it then holds the pair) or is one of two
+  // suits with remainder 2; every other suit must already be valid
   if ((r1 == 1 && r2 == 0) || (r1 == 0 && r2 == 2)) {
-    bool ok[4];
+    int bad = 0, bad_suit = -1;
 #pragma unroll
-    for (int s = 0; s < 3; s++) ok[s] = (n[s] % 3 == 1) ? false : lut_valid(L, h[s]);
-    ok[3] = (n[3] % 3 == 1) ? false : honors_valid(h[3]);
+    for (int s = 0; s < 4; s++)
+      if (rem[s] == 1 || !suit_valid(L, s, h[s])) { bad++; bad_suit = s; }
+    // with remainder pattern (1,0,0,0) the remainder-1 suit is the only "bad" one allowed;
+    // with (2,2,0,0) either no suit is bad (both candidates) or one of the two is (then it must take the tile)
 #pragma unroll
     for (int s = 0; s < 4; s++) {
-      if (n[s] % 3 == 0) continue;                 // the tile goes to a suit with remainder 1 or 2
-      bool others = true;
+      if (rem[s] == 0) continue;
+      if (bad > 1 || (bad == 1 && bad_suit != s)) continue;
+      w |= (uint64_t)suit_addmask(L, s, h[s]) << (9 * s);
+    }
+  }
+  if (n_meld == 0) {
+    SpecialCounts c = special_counts(h);
+    if (c.c2 == 6 && c.c1 == 1 && c.c3 == 0 && c.c4 == 0) w |= kinds_where(h, 1);      // seven pairs
+    if (c.yao_tiles == c.total && c.c3 == 0 && c.c4 == 0) {                            // thirteen orphans
+      if (c.c1 == 13) w |= K_YAOCHU;
+      else if (c.c1 == 11 && c.c2 == 1) w |= K_YAOCHU & ~(kinds_where(h, 1) | kinds_where(h, 2));
+    }
+  }
+  if (w) w &= ~own4_mask(h, meldw, n_meld);
+  return w;
+}
+
+// Kinds whose discard leaves the 14 - 3*n_meld tiles of a hand tenpai (non-empty waits_of).  Shares the
+// per-suit work between the candidate discards: only the suit that loses the tile is looked up again.
+MJ_HD_NOINLINE uint64_t tenpai_discards_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
+                                           int n_meld)
+{
+  MJ_STAT(n_tenpai);
+  uint32_t h[4] = {h0, h1, h2, h3};
+  int rem[4];
+  bool v[4];
+  int n_invalid = 0, t1 = 0, t2 = 0;
 #pragma unroll
-      for (int o = 0; o < 4; o++) if (o != s) others = others && ok[o];
-      if (!others) continue;
-      if (s < 3) {
-        for (int r = 0; r < 9; r++) {
-          if (cnt3(h[s], r) >= 4) continue;
-          if (lut_valid(L, h[s] + (1u << (3 * r)))) w |= kbit(9 * s + r);
+  for (int s = 0; s < 4; s++) {
+    rem[s] = tiles_in(h[s]) % 3;
+    t1 += rem[s] == 1; t2 += rem[s] == 2;
+    v[s] = suit_valid(L, s, h[s]);
+    n_invalid += v[s] ? 0 : 1;
+  }
+  uint64_t out = 0;
+  if (n_invalid <= 2) {
+    uint64_t full = own4_mask(h, meldw, n_meld);
+    // add[s]: ranks whose addition makes suit s valid and of which fewer than four are owned; computed on demand
+    uint32_t add[4] = {0, 0, 0, 0};
+    bool have[4] = {false, false, false, false};
+    for (int s1 = 0; s1 < 4; s1++) {
+      if (h[s1] == 0) continue;
+      // which suits may take the new tile when a tile leaves s1: the final remainders must be one 2 and three 0.
+      // A suit that loses a tile goes 0 -> 2, 1 -> 0, 2 -> 1; one that gains a tile goes 0 -> 1, 1 -> 2, 2 -> 0.
+      int feas = 0;
+      if (t1 == 0 && t2 == 1) feas |= 1 << s1;                                  // the tile comes back into s1
+      for (int s2 = 0; s2 < 4; s2++) {
+        if (s2 == s1) continue;
+        bool f = (rem[s1] == 0 && rem[s2] == 2 && t2 == 1 && t1 == 0) || (rem[s1] == 1 && rem[s2] == 1 && t1 == 2 && t2 == 0) ||
+                 (rem[s1] == 1 && rem[s2] == 2 && t1 == 1 && t2 == 2);
+        if (f) feas |= 1 << s2;
+      }
+      if (!feas) continue;
+      // the untouched suits must be valid as they are
+      int others_bad = 0, bad_other = -1;
+      for (int s = 0; s < 4; s++) if (s != s1 && !v[s]) { others_bad++; bad_other = s; }
+      if (others_bad > 1) continue;
+      int nr = s1 == 3 ? 7 : 9, basek = s1 == 3 ? 27 : 9 * s1;
+      for (int r = 0; r < nr; r++) {
+        if (cnt3(h[s1], r) == 0) continue;
+        uint32_t g = h[s1] - (1u << (3 * r));
+        bool ok = false;
+        // the new tile goes to another suit s2: g must be valid, and s2 is the only suit allowed to be invalid now
+        if (suit_valid(L, s1, g)) {
+          for (int s2 = 0; s2 < 4 && !ok; s2++) {
+            if (s2 == s1 || !(feas >> s2 & 1)) continue;
+            if (others_bad == 1 && bad_other != s2) continue;
+            if (!have[s2]) { add[s2] = suit_addmask(L, s2, h[s2]) & ~(uint32_t)(full >> (9 * s2) & 0x1FF); have[s2] = true; }
+            ok = add[s2] != 0;
+          }
         }
-      } else {
-        for (int r = 0; r < 7; r++) {
-          int c = cnt3(h[3], r);
-          if (c == 0 || c >= 3) continue;          // 0 -> 1 and 3 -> 4 never help
-          if (honors_valid(h[3] + (1u << (3 * r)))) w |= kbit(27 + r);
+        // the new tile goes back into s1
+        if (!ok && (feas >> s1 & 1) && others_bad == 0) {
+          uint32_t blocked = (uint32_t)(full >> (9 * s1) & 0x1FF) & ~(1u << r);     // the discarded kind is owned one less
+          ok = (suit_addmask(L, s1, g) & ~blocked) != 0;
         }
+        if (ok) out |= kbit(basek + r);
       }
     }
   }
   if (n_meld == 0) {
-    // seven pairs: six pairs and a single; thirteen orphans: twelve or thirteen different ones
-    uint32_t pairs = 0, singles = 0, other = 0;
-    uint64_t singles_k = 0, present = 0;
-#pragma unroll
-    for (int s = 0; s < 4; s++) {
-      uint32_t e1 = fields_eq(h[s], 1), e2 = fields_eq(h[s], 2), nz = fields_nonzero(h[s]);
-      pairs += popc32(e2); singles += popc32(e1); other += popc32(nz & ~e1 & ~e2);
-      singles_k |= (uint64_t)squeeze9(e1) << (9 * s);
-      present |= (uint64_t)squeeze9(nz) << (9 * s);
-    }
-    if (pairs == 6 && singles == 1 && other == 0) w |= singles_k;
-    if ((present & ~K_YAOCHU) == 0 && other == 0) {
-      int kinds = popc64(present);
-      if (kinds == 13 && pairs == 0) w |= K_YAOCHU;
-      else if (kinds == 12 && pairs == 1) w |= K_YAOCHU & ~present;
+    SpecialCounts c = special_counts(h);
+    bool chiitoi_near = c.c2 + c.c3 + c.c4 >= 5, kokushi_near = c.total - c.yao_tiles <= 1;
+    if (chiitoi_near || kokushi_near) {
+      for (int su = 0; su < 4; su++) {
+        int nr = su == 3 ? 7 : 9;
+        for (int r = 0; r < nr; r++) {
+          int n = cnt3(h[su], r);
+          if (n == 0) continue;
+          int c1 = c.c1, c2 = c.c2, c3 = c.c3, c4 = c.c4;
+          if (n == 1) c1--; else if (n == 2) { c2--; c1++; } else if (n == 3) { c3--; c2++; } else { c4--; c3++; }
+          bool yao = su == 3 || r == 0 || r == 8;
+          int nonyao = c.total - c.yao_tiles - (yao ? 0 : 1);
+          bool t = (c2 == 6 && c1 == 1 && c3 == 0 && c4 == 0) ||
+                   (nonyao == 0 && c3 == 0 && c4 == 0 && ((c1 == 13 && c2 == 0) || (c1 == 11 && c2 == 1)));
+          if (t) out |= kbit((su == 3 ? 27 : 9 * su) + r);
+        }
+      }
     }
   }
-  // drop kinds the seat already owns four of
-  uint64_t rest = w;
-  while (rest) {
-    int k = ctz64(rest);
-    rest &= rest - 1;
-    int own = hand_count(h, k);
-    for (int j = 0; j < n_meld; j++) own += meld_count(meld_at(meldw, j), k);
-    if (own >= 4) w &= ~kbit(k);
-  }
-  return w;
+  return out;
 }
 
 // --------------------------------------------------------------- evaluation
@@ -463,6 +589,7 @@ MJ_HD void eval_decomp(EvalCtx &c, const Decomp &d)
 
 MJ_HD_NOINLINE void eval_hand(const Lut &L, const HandIn &q, HandOut &out)
 {
+  MJ_STAT(n_eval);
   out.yaku = 0; out.points = 0; out.han = out.fu = out.units = out.shape_ok = out.yaku_ok = 0;
   out.n_dora = out.n_ura = out.n_aka = 0;
   int n_meld = q.n_meld, w = q.win;

@@ -17,17 +17,18 @@ struct Ctx {
   Rules R;
   Glob g;
   uint32_t env_id;
+  bool need_deal;      // set when a step ends in "deal the next kyoku": the caller shuffles and deals
 };
 
 // ------------------------------------------------------------- field access
-MJ_HD uint32_t &HW(Ctx &c, int s, int su) { return c.e.hand[(int64_t)(s * 4 + su) * c.e.n]; }
-MJ_HD uint32_t &SW(Ctx &c, int s) { return c.e.seatw[(int64_t)s * c.e.n]; }
-MJ_HD uint64_t &MELDW(Ctx &c, int s) { return c.e.meld[(int64_t)s * c.e.n]; }
-MJ_HD uint64_t &WAITS(Ctx &c, int s) { return c.e.waits[(int64_t)s * c.e.n]; }
-MJ_HD uint64_t &DK(Ctx &c, int s) { return c.e.dk[(int64_t)s * c.e.n]; }
-MJ_HD uint64_t &MASK(Ctx &c, int s, int w) { return c.e.mask[(int64_t)(s * 2 + w) * c.e.n]; }
-MJ_HD int32_t &SCORE(Ctx &c, int s) { return c.e.score[(int64_t)s * c.e.n]; }
-MJ_HD int32_t &DELTA(Ctx &c, int s) { return c.e.delta[(int64_t)s * c.e.n]; }
+MJ_HD uint32_t &HW(Ctx &c, int s, int su) { return c.e.hand[(int64_t)(s * 4 + su) * c.e.hs]; }
+MJ_HD uint32_t &SW(Ctx &c, int s) { return c.e.seatw[(int64_t)s * c.e.hs]; }
+MJ_HD uint64_t &MELDW(Ctx &c, int s) { return c.e.meld[(int64_t)s * c.e.hs]; }
+MJ_HD uint64_t &WAITS(Ctx &c, int s) { return c.e.waits[(int64_t)s * c.e.hs]; }
+MJ_HD uint64_t &DK(Ctx &c, int s) { return c.e.dk[(int64_t)s * c.e.hs]; }
+MJ_HD uint64_t &MASK(Ctx &c, int s, int w) { return c.e.mask[(int64_t)(s * 2 + w) * c.e.hs]; }
+MJ_HD int32_t &SCORE(Ctx &c, int s) { return c.e.score[(int64_t)s * c.e.hs]; }
+MJ_HD int32_t &DELTA(Ctx &c, int s) { return c.e.delta[(int64_t)s * c.e.hs]; }
 MJ_HD uint8_t &WALL(Ctx &c, int i) { return c.e.wall[(int64_t)i * c.e.n]; }
 MJ_HD uint8_t &RIVER(Ctx &c, int s, int i) { return c.e.river[(int64_t)(s * 32 + i) * c.e.n]; }
 
@@ -70,7 +71,7 @@ MJ_HD bool menzen_of(Ctx &c, int s)
 MJ_HD void clear_masks(Ctx &c)
 {
 #pragma unroll
-  for (int i = 0; i < 8; i++) c.e.mask[(int64_t)i * c.e.n] = 0;
+  for (int i = 0; i < 8; i++) c.e.mask[(int64_t)i * c.e.hs] = 0;
   c.g.actor_mask = 0;
 }
 MJ_HD void clear_first_and_ippatsu(Ctx &c)
@@ -127,20 +128,7 @@ MJ_HD void mark_furiten(Ctx &c, int s)
 // kinds whose discard leaves the 14-tile hand of seat s tenpai
 MJ_HD uint64_t tenpai_discards(Ctx &c, int s)
 {
-  uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
-  uint64_t mw = MELDW(c, s);
-  int n_meld = swf(c, s, SW_NMELD, 3);
-  uint64_t out = 0;
-  for (int su = 0; su < 4; su++) {
-    int nr = su == 3 ? 7 : 9;
-    for (int r = 0; r < nr; r++) {
-      if (cnt3(h[su], r) == 0) continue;
-      uint32_t g[4] = {h[0], h[1], h[2], h[3]};
-      g[su] -= 1u << (3 * r);
-      if (waits_of(c.L, g[0], g[1], g[2], g[3], mw, n_meld)) out |= kbit((su == 3 ? 27 : 9 * su) + r);
-    }
-  }
-  return out;
+  return tenpai_discards_of(c.L, HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3), MELDW(c, s), swf(c, s, SW_NMELD, 3));
 }
 
 MJ_HD void set_action(uint64_t m[2], int a) { m[a >> 6] |= 1ull << (a & 63); }
@@ -165,6 +153,7 @@ MJ_HD void discard_bits(Ctx &c, int s, uint64_t allowed, uint64_t m[2])
 // legal actions of the seat to move
 MJ_HD void turn_mask(Ctx &c)
 {
+  MJ_STAT(n_turn);
   int s = c.g.cur;
   uint64_t m[2] = {0, 0};
   clear_masks(c);
@@ -237,7 +226,8 @@ MJ_HD void draw_live(Ctx &c, int s)
   c.g.drawn = (uint8_t)take_tile(c, s, id);
 }
 
-// Fisher-Yates over the 136 tile ids: key (seed, env_id), counter (kyoku_serial, j, 0, 0)
+// Fisher-Yates over the 136 tile ids: key (seed, env_id), counter (kyoku_serial, j, 0, 0); position i swaps
+// with i + mulhi(r[i], 136 - i).  Plain per-environment form (the kernels do the same steps wave-cooperatively).
 MJ_HD void shuffle_wall(Ctx &c)
 {
   uint32_t serial = c.e.serial[0];
@@ -256,11 +246,13 @@ MJ_HD void shuffle_wall(Ctx &c)
   }
 }
 
-MJ_HD void deal(Ctx &c, bool reshuffle)
+// first half of a deal: per-kyoku state back to its start, 4 x 13 tiles and the dealer's first draw, read
+// from the wall copy at w[i * ws] (the same bytes as the environment's wall)
+MJ_HD void deal_tiles(Ctx &c, const uint8_t *w, int64_t ws)
 {
-  if (reshuffle) shuffle_wall(c);
+  MJ_STAT(n_deal);
 #pragma unroll
-  for (int i = 0; i < 16; i++) c.e.hand[(int64_t)i * c.e.n] = 0;
+  for (int i = 0; i < 16; i++) c.e.hand[(int64_t)i * c.e.hs] = 0;
   for (int s = 0; s < 4; s++) {
     // everything per seat back to the start of a kyoku, the final rank of the game kept
     uint32_t keep = SW(c, s) & (3u << SW_RANK);
@@ -268,19 +260,38 @@ MJ_HD void deal(Ctx &c, bool reshuffle)
     MELDW(c, s) = 0;
     DK(c, s) = 0;
   }
-  c.g.draw_ptr = 52; c.g.n_kan = 0; c.g.live_left = 70; c.g.n_dora = 1;
-  c.g.drawn = 255; c.g.riichi_pending = 0; c.g.rinshan = 0;
+  c.g.n_kan = 0; c.g.n_dora = 1;
+  c.g.riichi_pending = 0; c.g.rinshan = 0;
   c.g.last_discard = 255; c.g.last_discarder = 255; c.g.kakan_tile = 255;
   c.g.kuikae0 = c.g.kuikae1 = 255;
   c.g.first_wind = 255; c.g.same_wind_cnt = 0;
   int dealer = dealer_of(c);
   for (int j = 0; j < 4; j++) {
     int s = (dealer + j) & 3;
-    for (int t = 0; t < 13; t++) take_tile(c, s, WALL(c, 13 * j + t));
+    for (int t = 0; t < 13; t++) take_tile(c, s, w[(int64_t)(13 * j + t) * ws]);
   }
-  for (int s = 0; s < 4; s++) refresh_waits(c, s);
-  draw_live(c, dealer);
+  c.g.cur = (uint8_t)dealer;
+  c.g.draw_ptr = 53; c.g.live_left = 69;
+  c.g.drawn = (uint8_t)take_tile(c, dealer, w[52 * ws]);
+}
+// second half: the waits of the four 13-tile hands (the dealer's without the drawn tile) and the dealer's mask
+MJ_HD void deal_finish(Ctx &c)
+{
+  int dealer = dealer_of(c), dk = code_kind(c.g.drawn);
+  for (int s = 0; s < 4; s++) {
+    if (s == dealer) hand_add(c, s, dk, -1);
+    refresh_waits(c, s);
+    if (s == dealer) hand_add(c, s, dk, 1);
+  }
   turn_mask(c);
+}
+// whole deal from the environment's own wall in HBM
+MJ_HD void deal(Ctx &c, bool reshuffle)
+{
+  if (reshuffle) shuffle_wall(c);
+  deal_tiles(c, c.e.wall, c.e.n);
+  deal_finish(c);
+  c.need_deal = false;
 }
 
 MJ_HD void new_game(Ctx &c)
@@ -290,7 +301,7 @@ MJ_HD void new_game(Ctx &c)
     SW(c, s) = 0;                                        // final rank 0
   }
   c.g.kyoku = 0; c.g.honba = 0; c.g.kyotaku = 0; c.g.terminated = 0;
-  deal(c, true);
+  c.need_deal = true;
 }
 
 MJ_HD void clear_result(Ctx &c)
@@ -331,7 +342,7 @@ MJ_HD void finish_kyoku(Ctx &c, bool renchan, bool honba_up)
     return;
   }
   c.e.serial[0]++;
-  deal(c, true);
+  c.need_deal = true;
 }
 
 MJ_HD void win(Ctx &c, int winners, bool tsumo, int loser, int w, bool chankan)
@@ -645,9 +656,12 @@ MJ_HD void mark_passed_ron(Ctx &c)
     if ((c.g.actor_mask >> s & 1) && (MASK(c, s, 1) >> (A_RON - 64) & 1)) mark_furiten(c, s);
 }
 
-// one step of one environment; a[4] = the four seats' actions
-MJ_HD void step_env(Ctx &c, const int a[4])
+// One step of one environment; `acts` packs the four seats' actions as signed bytes (seat s in byte s).
+// When the step ends a kyoku and the game goes on, need_deal is set and the caller deals (shuffle, deal).
+MJ_HD void step_env(Ctx &c, uint32_t acts)
 {
+  const int a[4] = {(int8_t)(acts), (int8_t)(acts >> 8), (int8_t)(acts >> 16), (int8_t)(acts >> 24)};
+  c.need_deal = false;
 #pragma unroll
   for (int s = 0; s < 4; s++) DELTA(c, s) = 0;
   c.g.illegal_seat = 255;

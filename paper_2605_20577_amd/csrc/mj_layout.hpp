@@ -3,28 +3,45 @@
 // For B environments every field is an array over b, so the 64 lanes of a
 // wavefront (64 consecutive environments) touch consecutive addresses.
 // Sections, in this order, each array of length B:
-//   u64: discarded_kinds[4] waits[4] mask[8] yaku[4] meld[4] result[4]      (28 arrays)
-//   u32: score[4] delta[4] gain[4] episode serial hand[16] seatw[4] glob[7] (41 arrays)
-//   u8 : wall[136] river[128]                                               (264 arrays)
-// = 652 bytes per environment.
+//   u64 hot : discarded_kinds[4] waits[4] mask[8] meld[4]                   (20 arrays)
+//   u64 cold: yaku[4] result[4]                                             ( 8 arrays)
+//   u32 hot : score[4] delta[4] episode serial hand[16] seatw[4]            (30 arrays)
+//   u32 cold: gain[4] glob[7]                                               (11 arrays)
+//   u8  cold: wall[136] river[128]                                          (264 arrays)
+// = 652 bytes per environment, 280 of them hot.  The step kernels copy the
+// hot arrays of their block into LDS, run there, and copy them back.
 #pragma once
 #include "mj_core.hpp"
 
 namespace mj {
 
-constexpr int kU64Arrays = 28, kU32Arrays = 41, kU8Arrays = 264;
+constexpr int kHotU64 = 20, kColdU64 = 8, kHotU32 = 30, kColdU32 = 11, kU8Arrays = 264;
+constexpr int kU64Arrays = kHotU64 + kColdU64, kU32Arrays = kHotU32 + kColdU32;
 constexpr int64_t kBytesPerEnv = 8 * kU64Arrays + 4 * kU32Arrays + kU8Arrays;
+constexpr int kHotBytesPerEnv = 8 * kHotU64 + 4 * kHotU32;
 
+MJ_HD uint64_t *state_u64(void *state, int64_t B) { (void)B; return (uint64_t *)state; }
+MJ_HD uint32_t *state_u32(void *state, int64_t B) { return (uint32_t *)((uint64_t *)state + (int64_t)kU64Arrays * B); }
+MJ_HD uint8_t *state_u8(void *state, int64_t B) { return (uint8_t *)(state_u32(state, B) + (int64_t)kU32Arrays * B); }
+
+MJ_HD void set_hot(Env &e, uint64_t *q, uint32_t *w, int64_t hs)
+{
+  e.hs = hs;
+  e.dk = q; e.waits = q + 4 * hs; e.mask = q + 8 * hs; e.meld = q + 16 * hs;
+  e.score = (int32_t *)w; e.delta = (int32_t *)(w + 4 * hs); e.episode = w + 8 * hs; e.serial = w + 9 * hs;
+  e.hand = w + 10 * hs; e.seatw = w + 26 * hs;
+}
+// view of environment b with every field in HBM
 MJ_HD Env make_env(void *state, int64_t B, int64_t b)
 {
   Env e;
   e.n = B;
-  uint64_t *q = (uint64_t *)state + b;
-  e.dk = q; e.waits = q + 4 * B; e.mask = q + 8 * B; e.yaku = q + 16 * B; e.meld = q + 20 * B; e.resw = q + 24 * B;
-  uint32_t *w = (uint32_t *)((uint64_t *)state + (int64_t)kU64Arrays * B) + b;
-  e.score = (int32_t *)w; e.delta = (int32_t *)(w + 4 * B); e.gain = (int32_t *)(w + 8 * B);
-  e.episode = w + 12 * B; e.serial = w + 13 * B; e.hand = w + 14 * B; e.seatw = w + 30 * B; e.glob = w + 34 * B;
-  uint8_t *y = (uint8_t *)((uint32_t *)((uint64_t *)state + (int64_t)kU64Arrays * B) + (int64_t)kU32Arrays * B) + b;
+  uint64_t *q = state_u64(state, B) + b;
+  uint32_t *w = state_u32(state, B) + b;
+  uint8_t *y = state_u8(state, B) + b;
+  set_hot(e, q, w, B);
+  e.yaku = q + (int64_t)kHotU64 * B; e.resw = q + (int64_t)(kHotU64 + 4) * B;
+  e.gain = (int32_t *)(w + (int64_t)kHotU32 * B); e.glob = w + (int64_t)(kHotU32 + 4) * B;
   e.wall = y; e.river = y + 136 * B;
   return e;
 }

@@ -1,10 +1,15 @@
 // libmj: HIP kernels (gfx950) and the C ABI of include/mj.h.
 //
-// Kernels map one lane to one environment (64 consecutive environments per
-// wavefront, structure-of-arrays state, see mj_layout.hpp) except the
-// observation writer, which builds bit planes per environment and then streams
-// bytes with all lanes.  Every step kernel first stages the probe part of the
-// per-suit pattern table (row ids + suffix bitmaps, about 11 KB) into LDS.
+// Step kernels map one lane to one environment (64 consecutive environments
+// per wavefront, structure-of-arrays state, see mj_layout.hpp).  A block of
+// 128 lanes stages into LDS: the probe part of the per-suit pattern table
+// (11 KB), the hot state arrays of its 128 environments (35 KB) and a small
+// per-wave slot for dealing; it runs its steps there and writes the hot
+// arrays back.  The rare heavy step, the wall shuffle, is done by the whole
+// wavefront for one environment at a time (ballot over the lanes that need a
+// deal, 34 lanes run Philox, one lane applies the swaps in LDS).  The
+// observation writer builds bit planes per environment and then streams bytes
+// with all lanes.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstdlib>
@@ -23,7 +28,8 @@ static_assert(sizeof(Glob) == 28, "control bytes");
 
 namespace {
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 128;              // lanes per block of the step kernels
+constexpr int kAuxBlock = 256;           // lanes per block of the helper kernels
 
 struct DevTables {
   const uint8_t *probe;                  // global: rowid[kRowIdBytes] followed by bitmap[rows * 20]
@@ -32,19 +38,116 @@ struct DevTables {
   int probe_bytes;                       // multiple of 16
 };
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
+constexpr int kDealSlotBytes = 272;      // per wave: 136 wall bytes + 136 swap targets
 
-// copy the probe tables into LDS and return a view on them
-__device__ __forceinline__ Lut stage_lut(const DevTables &T, uint16_t *lds)
+// LDS of a step kernel: probe tables | hot u64 arrays | hot u32 arrays | one deal slot per wave
+__host__ __device__ inline size_t step_lds_bytes(int probe_bytes)
+{
+  return (size_t)probe_bytes + (size_t)kBlock * kHotBytesPerEnv + (size_t)(kBlock / 64) * kDealSlotBytes;
+}
+
+struct BlockMem {
+  Lut L;
+  uint64_t *hq;                          // [kHotU64][kBlock]
+  uint32_t *hw;                          // [kHotU32][kBlock]
+  uint8_t *slot;                         // this wave's deal slot
+};
+
+// carve up the block's LDS and copy the probe tables in (ends with a block barrier)
+__device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds)
 {
   const uint4 *src = (const uint4 *)T.probe;
   uint4 *dst = (uint4 *)lds;
   for (int i = threadIdx.x; i < T.probe_bytes / 16; i += blockDim.x) dst[i] = src[i];
+  BlockMem m;
+  m.L.rowid = lds;
+  m.L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
+  m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.keyinfo = T.keyinfo; m.L.recs = T.recs;
+  m.hq = (uint64_t *)(lds + T.probe_bytes);
+  m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)kBlock * 8 * kHotU64);
+  m.slot = lds + T.probe_bytes + (size_t)kBlock * kHotBytesPerEnv + (threadIdx.x >> 6) * kDealSlotBytes;
   __syncthreads();
-  Lut L;
-  L.rowid = (const uint8_t *)lds;
-  L.bitmap = (const uint32_t *)((const uint8_t *)lds + kRowIdBytes);
-  L.base = T.base; L.rowrank = T.rowrank; L.keyinfo = T.keyinfo; L.recs = T.recs;
-  return L;
+  return m;
+}
+// the per-lane environment view: hot fields in LDS, cold fields in HBM
+__device__ __forceinline__ Env block_env(const BlockMem &m, void *state, int64_t B, int64_t b)
+{
+  Env e = make_env(state, B, b);
+  set_hot(e, m.hq + threadIdx.x, m.hw + threadIdx.x, kBlock);
+  return e;
+}
+__device__ __forceinline__ void load_hot(const BlockMem &m, void *state, int64_t B, int64_t b)
+{
+  const uint64_t *gq = state_u64(state, B) + b;
+  const uint32_t *gw = state_u32(state, B) + b;
+#pragma unroll
+  for (int f = 0; f < kHotU64; f++) m.hq[f * kBlock + threadIdx.x] = gq[(int64_t)f * B];
+#pragma unroll
+  for (int f = 0; f < kHotU32; f++) m.hw[f * kBlock + threadIdx.x] = gw[(int64_t)f * B];
+}
+__device__ __forceinline__ void store_hot(const BlockMem &m, void *state, int64_t B, int64_t b)
+{
+  uint64_t *gq = state_u64(state, B) + b;
+  uint32_t *gw = state_u32(state, B) + b;
+#pragma unroll
+  for (int f = 0; f < kHotU64; f++) gq[(int64_t)f * B] = m.hq[f * kBlock + threadIdx.x];
+#pragma unroll
+  for (int f = 0; f < kHotU32; f++) gw[(int64_t)f * B] = m.hw[f * kBlock + threadIdx.x];
+}
+
+// lanes of one wavefront exchange data through LDS: order the accesses
+__device__ __forceinline__ void wave_sync()
+{
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// Deal for every lane of the wavefront that needs one.  All 64 lanes must call this together.
+// Per environment in turn: 34 lanes run Philox and turn the words into swap targets, the owner lane applies
+// the 135 swaps on the wall in LDS, all lanes copy the wall to HBM, the owner takes its tiles from LDS.
+// Afterwards the owners compute waits and masks side by side.
+__device__ __forceinline__ void deal_wave(Ctx &c, bool need, uint8_t *slot, void *state, int64_t B, int64_t b)
+{
+  const int lane = threadIdx.x & 63;
+  uint8_t *wl = slot, *kk = slot + 136;
+  unsigned long long pending = __ballot(need ? 1 : 0);
+  const uint32_t my_serial = need ? c.e.serial[0] : 0u;
+  const uint32_t b_lo = (uint32_t)b, b_hi = (uint32_t)((uint64_t)b >> 32);
+  while (pending) {
+    const int src = __builtin_ctzll(pending);
+    pending &= pending - 1;
+    const uint32_t serial = __shfl(my_serial, src), env_id = __shfl(c.env_id, src);
+    const int64_t bsrc = (int64_t)(((uint64_t)__shfl(b_hi, src) << 32) | __shfl(b_lo, src));
+    if (lane < 34) {
+      uint32_t r[4];
+      philox(serial, (uint32_t)lane, 0, 0, c.R.seed, env_id, r);
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        int i = 4 * lane + t;
+        if (i < 135) kk[i] = (uint8_t)(i + (int)mulhi(r[t], (uint32_t)(136 - i)));
+      }
+    }
+    wl[lane] = (uint8_t)lane;
+    wl[lane + 64] = (uint8_t)(lane + 64);
+    if (lane < 8) wl[lane + 128] = (uint8_t)(lane + 128);
+    wave_sync();
+    if (lane == src) {
+      for (int i = 0; i < 135; i++) {
+        int k = kk[i];
+        uint8_t x = wl[i], y = wl[k];
+        wl[i] = y; wl[k] = x;
+      }
+    }
+    wave_sync();
+    uint8_t *gw = state_u8(state, B) + bsrc;
+    gw[(int64_t)lane * B] = wl[lane];
+    gw[(int64_t)(lane + 64) * B] = wl[lane + 64];
+    if (lane < 8) gw[(int64_t)(lane + 128) * B] = wl[lane + 128];
+    if (lane == src) deal_tiles(c, wl, 1);
+    wave_sync();
+  }
+  if (need) { deal_finish(c); c.need_deal = false; }
 }
 
 __device__ __forceinline__ void reset_env(Ctx &c, bool first)
@@ -62,86 +165,100 @@ __device__ __forceinline__ void reset_env(Ctx &c, bool first)
   new_game(c);
 }
 
-__global__ void __launch_bounds__(kBlock) k_init(void *state, int64_t B, Rules R, DevTables T)
+// mode 0: first initialisation of every env; mode 1: restart of the terminated ones
+__global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Rules R, DevTables T, int mode)
 {
-  extern __shared__ uint16_t lds[];
-  Lut L = stage_lut(T, lds);
-  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (b >= B) return;
+  extern __shared__ __align__(16) uint8_t lds[];
+  BlockMem m = stage_block(T, lds);
+  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = b < B;
   Ctx c;
-  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  reset_env(c, true);
-  store_glob(c.e, c.g);
-}
-
-__global__ void __launch_bounds__(kBlock) k_reset_done(void *state, int64_t B, Rules R, DevTables T)
-{
-  extern __shared__ uint16_t lds[];
-  Lut L = stage_lut(T, lds);
-  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (b >= B) return;
-  Ctx c;
-  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  load_glob(c.e, c.g);
-  if (!c.g.terminated) return;
-  reset_env(c, false);
-  store_glob(c.e, c.g);
+  c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  c.need_deal = false;
+  bool touched = false;
+  if (active) {
+    if (mode == 0) { reset_env(c, true); touched = true; }
+    else {
+      load_hot(m, state, B, b);
+      load_glob(c.e, c.g);
+      if (c.g.terminated) { reset_env(c, false); touched = true; }
+    }
+  }
+  deal_wave(c, active && c.need_deal, m.slot, state, B, b);
+  if (touched) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
 __global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions)
 {
-  extern __shared__ uint16_t lds[];
-  Lut L = stage_lut(T, lds);
-  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (b >= B) return;
+  extern __shared__ __align__(16) uint8_t lds[];
+  BlockMem m = stage_block(T, lds);
+  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = b < B;
   Ctx c;
-  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  load_glob(c.e, c.g);
-  uint32_t packed = ((const uint32_t *)actions)[b];
-  int a[4] = {(int8_t)(packed), (int8_t)(packed >> 8), (int8_t)(packed >> 16), (int8_t)(packed >> 24)};
-  step_env(c, a);
-  store_glob(c.e, c.g);
+  c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  c.need_deal = false;
+  if (active) {
+    load_hot(m, state, B, b);
+    load_glob(c.e, c.g);
+    step_env(c, ((const uint32_t *)actions)[b]);
+  }
+  deal_wave(c, active && c.need_deal, m.slot, state, B, b);
+  if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
+}
+
+// the random policy for every acting seat of the lane's environment, packed as four signed bytes
+__device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step)
+{
+  uint32_t acts = 0xFFFFFFFFu, am = c.g.actor_mask;
+  while (am) {
+    int s = __builtin_ctz(am);
+    am &= am - 1;
+    int a = sample_action(MASK(c, s, 0), MASK(c, s, 1), c.R.seed, c.env_id, step, s);
+    acts = (acts & ~(0xFFu << (8 * s))) | ((uint32_t)(uint8_t)(int8_t)a << (8 * s));
+  }
+  return acts;
 }
 
 // n_steps of { sample, step, optional reset } without leaving the kernel: environments never interact
 __global__ void __launch_bounds__(kBlock) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
                                                     int n_steps, int auto_reset)
 {
-  extern __shared__ uint16_t lds[];
-  Lut L = stage_lut(T, lds);
-  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (b >= B) return;
+  extern __shared__ __align__(16) uint8_t lds[];
+  BlockMem m = stage_block(T, lds);
+  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const bool active = b < B;
   Ctx c;
-  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  load_glob(c.e, c.g);
+  c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  c.need_deal = false;
+  if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
   for (int t = 0; t < n_steps; t++) {
-    int a[4];
-#pragma unroll
-    for (int s = 0; s < 4; s++) a[s] = sample_action(MASK(c, s, 0), MASK(c, s, 1), R.seed, c.env_id, step0 + t, s);
-    step_env(c, a);
-    if (auto_reset && c.g.terminated) reset_env(c, false);
+    if (active) {
+      step_env(c, sample_actors(c, step0 + t));
+      if (auto_reset && c.g.terminated) reset_env(c, false);
+    }
+    deal_wave(c, active && c.need_deal, m.slot, state, B, b);
   }
-  store_glob(c.e, c.g);
+  if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
 // test / scripting aid: give env b the wall in `wall` and deal the current kyoku again from it
 __global__ void __launch_bounds__(kBlock) k_deal_from_wall(void *state, int64_t B, Rules R, DevTables T, int64_t b,
                                                            const uint8_t *wall)
 {
-  extern __shared__ uint16_t lds[];
-  Lut L = stage_lut(T, lds);
+  extern __shared__ __align__(16) uint8_t lds[];
+  BlockMem m = stage_block(T, lds);
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
   Ctx c;
-  c.e = make_env(state, B, b); c.L = L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  c.e = make_env(state, B, b); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   load_glob(c.e, c.g);
   for (int i = 0; i < 136; i++) WALL(c, i) = wall[i];
   deal(c, false);
   store_glob(c.e, c.g);
 }
 
-__global__ void __launch_bounds__(kBlock) k_sample(void *state, int64_t B, Rules R, uint64_t step, int8_t *actions)
+__global__ void __launch_bounds__(kAuxBlock) k_sample(void *state, int64_t B, Rules R, uint64_t step, int8_t *actions)
 {
-  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  int64_t b = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (b >= B) return;
   Env e = make_env(state, B, b);
   uint32_t packed = 0;
@@ -153,9 +270,9 @@ __global__ void __launch_bounds__(kBlock) k_sample(void *state, int64_t B, Rules
   ((uint32_t *)actions)[b] = packed;
 }
 
-__global__ void __launch_bounds__(kBlock) k_legal_mask(void *state, int64_t B, uint64_t *out)
+__global__ void __launch_bounds__(kAuxBlock) k_legal_mask(void *state, int64_t B, uint64_t *out)
 {
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;      // one thread per (b, word)
+  int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;      // one thread per (b, word)
   if (i >= 8 * B) return;
   int64_t b = i >> 3;
   int w = (int)(i & 7);
@@ -163,10 +280,10 @@ __global__ void __launch_bounds__(kBlock) k_legal_mask(void *state, int64_t B, u
   out[i] = mask[(int64_t)w * B + b];
 }
 
-__global__ void __launch_bounds__(kBlock) k_reward(void *state, int64_t B, float penalty, int32_t *delta, float *reward,
+__global__ void __launch_bounds__(kAuxBlock) k_reward(void *state, int64_t B, float penalty, int32_t *delta, float *reward,
                                                    uint8_t *terminated)
 {
-  int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  int64_t b = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (b >= B) return;
   Env e = make_env(state, B, b);
   Glob g;
@@ -184,27 +301,35 @@ __global__ void __launch_bounds__(kBlock) k_reward(void *state, int64_t B, float
   if (terminated) terminated[b] = g.terminated;
 }
 
-__global__ void __launch_bounds__(kBlock) k_export(void *state, int64_t B, int64_t lo, int64_t n, MjEnvCanon *out)
+__global__ void __launch_bounds__(kAuxBlock) k_export(void *state, int64_t B, int64_t lo, int64_t n, MjEnvCanon *out)
 {
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (i >= n) return;
   MjEnvCanon o;
   export_env(make_env(state, B, lo + i), o);
   out[i] = o;
 }
-__global__ void __launch_bounds__(kBlock) k_import(void *state, int64_t B, int64_t lo, int64_t n, const MjEnvCanon *in)
+__global__ void __launch_bounds__(kAuxBlock) k_import(void *state, int64_t B, int64_t lo, int64_t n, const MjEnvCanon *in)
 {
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (i >= n) return;
   MjEnvCanon o = in[i];
   import_env(make_env(state, B, lo + i), o);
 }
 
-__global__ void __launch_bounds__(kBlock) k_eval_hands(DevTables T, int64_t n, const MjHandQuery *in, MjHandResult *out)
+__global__ void __launch_bounds__(kAuxBlock) k_eval_hands(DevTables T, int64_t n, const MjHandQuery *in, MjHandResult *out)
 {
-  extern __shared__ uint16_t lds[];
-  Lut L = stage_lut(T, lds);
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  extern __shared__ __align__(16) uint8_t lds[];
+  {
+    const uint4 *src = (const uint4 *)T.probe;
+    uint4 *dst = (uint4 *)lds;
+    for (int j = threadIdx.x; j < T.probe_bytes / 16; j += blockDim.x) dst[j] = src[j];
+    __syncthreads();
+  }
+  Lut L;
+  L.rowid = lds; L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
+  L.base = T.base; L.rowrank = T.rowrank; L.keyinfo = T.keyinfo; L.recs = T.recs;
+  int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (i >= n) return;
   const uint32_t *qw = (const uint32_t *)(in + i);
   uint32_t w[16];
@@ -247,7 +372,7 @@ constexpr int kObsEnvs = 16;
 constexpr int kObsBits = 56 * 34;                 // 1904
 constexpr int kObsWords = 60;                     // u32 words per (env, viewer), 1920 bits
 
-__global__ void __launch_bounds__(kBlock) k_observe(void *state, int64_t B, uint32_t rule_flags, uint8_t *obs)
+__global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, uint32_t rule_flags, uint8_t *obs)
 {
   __shared__ uint64_t S[kObsEnvs][4][OB_SEAT_WORDS];
   __shared__ uint64_t G[kObsEnvs][OG_WORDS];
@@ -294,7 +419,7 @@ __global__ void __launch_bounds__(kBlock) k_observe(void *state, int64_t B, uint
     // 7616 bytes per env = 476 stores of 16 bytes; 16 bytes = 16 bits of the string
     const int per_env = 4 * kObsBits / 16;
     uint4 *dst = (uint4 *)(obs + (size_t)base * 4 * kObsBits);
-    for (int i = tid; i < nenv * per_env; i += kBlock) {
+    for (int i = tid; i < nenv * per_env; i += kAuxBlock) {
       int el = i / per_env, j = i - el * per_env;          // j-th 16-byte group of env el
       int me = j / (kObsBits / 16), q = j - me * (kObsBits / 16);
       uint32_t word = bits[el][me][q >> 1];
@@ -320,7 +445,7 @@ struct MjHandle {
   uint64_t step;
   void *d_state, *d_scratch;
   DevTables T;
-  size_t lds_bytes;
+  size_t lds_bytes, probe_bytes;
   hipEvent_t ev[2];
   int ev_steps;
   bool ev_valid;
@@ -349,7 +474,8 @@ ScratchLayout scratch_layout()
   return s;
 }
 size_t scratch_bytes_impl() { return scratch_layout().total; }
-inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kAuxBlock - 1) / kAuxBlock); }
+inline unsigned step_blocks(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 inline int check(hipError_t e) { return e == hipSuccess ? MJ_OK : MJ_E_HIP; }
 
 }  // namespace
@@ -395,8 +521,9 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   int dev = 0, lds_max = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) { delete h; return MJ_E_HIP; }
-  if ((size_t)lds_max < sl.probe_bytes) { delete h; return MJ_E_UNSUPPORTED; }
-  h->lds_bytes = sl.probe_bytes;
+  h->lds_bytes = step_lds_bytes((int)sl.probe_bytes);
+  h->probe_bytes = sl.probe_bytes;
+  if ((size_t)lds_max < h->lds_bytes) { delete h; return MJ_E_UNSUPPORTED; }
   hipStream_t st = (hipStream_t)stream;
   // table image in the caller's scratch buffer
   std::vector<uint8_t> img(sl.total, 0);
@@ -418,7 +545,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[0]));
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[1]));
   if (rc != MJ_OK) { delete h; return rc; }
-  k_init<<<blocks_for(B), kBlock, h->lds_bytes, st>>>(d_state, B, h->R, h->T);
+  k_new_games<<<step_blocks(B), kBlock, h->lds_bytes, st>>>(d_state, B, h->R, h->T, 0);
   rc = check(hipGetLastError());
   if (rc != MJ_OK) { delete h; return rc; }
   *out = h;
@@ -428,7 +555,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
 int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
 {
   if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
-  k_step<<<blocks_for(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, d_actions);
+  k_step<<<step_blocks(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, d_actions);
   h->step++;
   return check(hipGetLastError());
 }
@@ -436,7 +563,7 @@ int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
 int mj_legal_mask(const MjHandle *h, uint64_t *d_mask, void *stream)
 {
   if (!h || !d_mask) return MJ_E_ARG;
-  k_legal_mask<<<blocks_for(8 * h->B), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, d_mask);
+  k_legal_mask<<<blocks_for(8 * h->B), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, d_mask);
   return check(hipGetLastError());
 }
 
@@ -445,14 +572,14 @@ int mj_observe(const MjHandle *h, uint8_t *d_obs, void *stream)
   if (!h || !d_obs || ((uintptr_t)d_obs & 15)) return MJ_E_ARG;
   int64_t groups = (h->B + kObsEnvs - 1) / kObsEnvs;
   unsigned grid = (unsigned)(groups < 65536 ? groups : 65536);
-  k_observe<<<grid, kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, d_obs);
+  k_observe<<<grid, kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, d_obs);
   return check(hipGetLastError());
 }
 
 int mj_reward(const MjHandle *h, int32_t *d_delta, float *d_reward, uint8_t *d_terminated, void *stream)
 {
   if (!h || ((uintptr_t)d_delta & 15) || ((uintptr_t)d_reward & 15)) return MJ_E_ARG;
-  k_reward<<<blocks_for(h->B), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.illegal_penalty, d_delta, d_reward,
+  k_reward<<<blocks_for(h->B), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.illegal_penalty, d_delta, d_reward,
                                                                  d_terminated);
   return check(hipGetLastError());
 }
@@ -460,14 +587,14 @@ int mj_reward(const MjHandle *h, int32_t *d_delta, float *d_reward, uint8_t *d_t
 int mj_reset_done(MjHandle *h, void *stream)
 {
   if (!h) return MJ_E_ARG;
-  k_reset_done<<<blocks_for(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T);
+  k_new_games<<<step_blocks(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, 1);
   return check(hipGetLastError());
 }
 
 int mj_sample_random(const MjHandle *h, int8_t *d_actions, void *stream)
 {
   if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
-  k_sample<<<blocks_for(h->B), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->step, d_actions);
+  k_sample<<<blocks_for(h->B), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->step, d_actions);
   return check(hipGetLastError());
 }
 
@@ -482,12 +609,12 @@ int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, 
     // environments never interact, so many steps run inside one launch; chunked to bound a launch's duration
     for (int t = 0; t < n_steps && rc == MJ_OK; t += MJ_ROLLOUT_CHUNK) {
       int n = n_steps - t < MJ_ROLLOUT_CHUNK ? n_steps - t : MJ_ROLLOUT_CHUNK;
-      k_rollout<<<blocks_for(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
+      k_rollout<<<step_blocks(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
       rc = check(hipGetLastError());
     }
   } else {
     for (int t = 0; t < n_steps && rc == MJ_OK; t++) {
-      k_rollout<<<blocks_for(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset);
+      k_rollout<<<step_blocks(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset);
       rc = check(hipGetLastError());
       if (rc == MJ_OK) rc = mj_observe(h, d_obs, stream);
     }
@@ -505,7 +632,7 @@ int mj_export(const MjHandle *h, int64_t env_lo, int64_t n, MjEnvCanon *d_out, v
   if (!h || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
   if (n == 0) return MJ_OK;
   if (!d_out) return MJ_E_ARG;
-  k_export<<<blocks_for(n), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_out);
+  k_export<<<blocks_for(n), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_out);
   return check(hipGetLastError());
 }
 int mj_import(MjHandle *h, int64_t env_lo, int64_t n, const MjEnvCanon *d_in, void *stream)
@@ -513,7 +640,7 @@ int mj_import(MjHandle *h, int64_t env_lo, int64_t n, const MjEnvCanon *d_in, vo
   if (!h || env_lo < 0 || n < 0 || env_lo + n > h->B) return MJ_E_ARG;
   if (n == 0) return MJ_OK;
   if (!d_in) return MJ_E_ARG;
-  k_import<<<blocks_for(n), kBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_in);
+  k_import<<<blocks_for(n), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, env_lo, n, d_in);
   return check(hipGetLastError());
 }
 
@@ -522,7 +649,7 @@ int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandR
   if (!h || n < 0) return MJ_E_ARG;
   if (n == 0) return MJ_OK;                               // an empty batch needs no buffers
   if (!d_in || !d_out || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 7)) return MJ_E_ARG;
-  k_eval_hands<<<blocks_for(n), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->T, n, d_in, d_out);
+  k_eval_hands<<<blocks_for(n), kAuxBlock, h->probe_bytes, (hipStream_t)stream>>>(h->T, n, d_in, d_out);
   return check(hipGetLastError());
 }
 

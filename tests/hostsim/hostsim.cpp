@@ -32,6 +32,7 @@ static Ctx ctx_of(Sim *h, int64_t b)
   Ctx c;
   c.e = make_env(h->state.data(), h->B, b);
   c.L = h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
+  c.need_deal = false;
   return c;
 }
 static void reset_env(Ctx &c, bool first)
@@ -44,6 +45,16 @@ static void reset_env(Ctx &c, bool first)
     c.g.illegal_seat = 255;
   } else { c.e.episode[0]++; c.e.serial[0]++; }
   new_game(c);
+  if (c.need_deal) deal(c, true);
+}
+static uint32_t pack4(const int a[4])
+{
+  return (uint32_t)(uint8_t)a[0] | (uint32_t)(uint8_t)a[1] << 8 | (uint32_t)(uint8_t)a[2] << 16 | (uint32_t)(uint8_t)a[3] << 24;
+}
+static void step_and_deal(Ctx &c, const int a[4])
+{
+  step_env(c, pack4(a));
+  if (c.need_deal) deal(c, true);
 }
 
 extern "C" {
@@ -70,7 +81,7 @@ void hs_step(Sim *h, const int8_t *actions)
     Ctx c = ctx_of(h, b);
     load_glob(c.e, c.g);
     int a[4] = {actions[4 * b], actions[4 * b + 1], actions[4 * b + 2], actions[4 * b + 3]};
-    step_env(c, a);
+    step_and_deal(c, a);
     store_glob(c.e, c.g);
   }
   h->step++;
@@ -101,7 +112,7 @@ void hs_step_random(Sim *h, int n, int auto_reset)
     for (int t = 0; t < n; t++) {
       int a[4];
       for (int s = 0; s < 4; s++) a[s] = sample_action(MASK(c, s, 0), MASK(c, s, 1), h->R.seed, c.env_id, h->step + t, s);
-      step_env(c, a);
+      step_and_deal(c, a);
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }
     store_glob(c.e, c.g);
