@@ -18,6 +18,7 @@ struct Ctx {
   Glob g;
   uint32_t env_id;
   bool need_deal;      // set when a step ends in "deal the next kyoku": the caller shuffles and deals
+  bool need_turn;      // the seat to move still needs its legal mask (step_finish)
 };
 
 // ------------------------------------------------------------- field access
@@ -274,7 +275,8 @@ MJ_HD void deal_tiles(Ctx &c, const uint8_t *w, int64_t ws)
   c.g.draw_ptr = 53; c.g.live_left = 69;
   c.g.drawn = (uint8_t)take_tile(c, dealer, w[52 * ws]);
 }
-// second half: the waits of the four 13-tile hands (the dealer's without the drawn tile) and the dealer's mask
+// second half: the waits of the four 13-tile hands (the dealer's without the drawn tile); the dealer's mask
+// is left to step_finish
 MJ_HD void deal_finish(Ctx &c)
 {
   int dealer = dealer_of(c), dk = code_kind(c.g.drawn);
@@ -283,7 +285,13 @@ MJ_HD void deal_finish(Ctx &c)
     refresh_waits(c, s);
     if (s == dealer) hand_add(c, s, dk, 1);
   }
-  turn_mask(c);
+  c.need_deal = false;
+  c.need_turn = true;
+}
+MJ_HD void step_finish(Ctx &c)
+{
+  if (c.need_turn) turn_mask(c);
+  c.need_turn = false;
 }
 // whole deal from the environment's own wall in HBM
 MJ_HD void deal(Ctx &c, bool reshuffle)
@@ -291,7 +299,7 @@ MJ_HD void deal(Ctx &c, bool reshuffle)
   if (reshuffle) shuffle_wall(c);
   deal_tiles(c, c.e.wall, c.e.n);
   deal_finish(c);
-  c.need_deal = false;
+  step_finish(c);
 }
 
 MJ_HD void new_game(Ctx &c)
@@ -405,14 +413,8 @@ MJ_HD void abortive_draw(Ctx &c, int type)
   finish_kyoku(c, true, true);
 }
 
-MJ_HD void advance(Ctx &c)
-{
-  if (c.g.live_left == 0) { exhaustive_draw(c); return; }
-  draw_live(c, (c.g.last_discarder + 1) & 3);
-  turn_mask(c);
-}
-
-MJ_HD void finish_kan(Ctx &c)
+// the replacement draw that completes any kan (the mask follows in step_finish)
+MJ_HD void kan_draw(Ctx &c)
 {
   int s = c.g.cur;
   swf_set(c, s, SW_KANBY, 3, swf(c, s, SW_KANBY, 3) + 1);
@@ -424,11 +426,11 @@ MJ_HD void finish_kan(Ctx &c)
   c.g.drawn = (uint8_t)take_tile(c, s, id);
   c.g.rinshan = 1;
   c.g.kakan_tile = 255;
-  turn_mask(c);
 }
 
-// returns true when the kyoku ended here
-MJ_HD bool settle_discard(Ctx &c)
+// The discard was not won on: a pending riichi is established and paid for.  Returns the type of the abortive
+// draw that is now due (0 = none).
+MJ_HD int settle_discard(Ctx &c)
 {
   int d = c.g.last_discarder;
   if (c.g.riichi_pending) {
@@ -442,17 +444,32 @@ MJ_HD bool settle_discard(Ctx &c)
     c.g.riichi_pending = 0;
   }
   if (c.R.flags & F_ABORT) {
-    if (c.g.same_wind_cnt == 4) { abortive_draw(c, 5); return true; }
+    if (c.g.same_wind_cnt == 4) return 5;
     bool all_riichi = true, one_seat = false;
     for (int s = 0; s < 4; s++) {
       uint32_t sw = SW(c, s);
       if (!sw_get(sw, SW_RIICHI, 2)) all_riichi = false;
       if (sw_get(sw, SW_KANBY, 3) == 4) one_seat = true;
     }
-    if (all_riichi) { abortive_draw(c, 6); return true; }
-    if (c.g.n_kan == 4 && !one_seat) { abortive_draw(c, 7); return true; }
+    if (all_riichi) return 6;
+    if (c.g.n_kan == 4 && !one_seat) return 7;
   }
-  return false;
+  return 0;
+}
+
+// can seat o win on kind k discarded (or added to a kan) by someone else?  A fitting tile that can not be
+// won on leaves the seat furiten.
+MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
+{
+  if (!(WAITS(c, o) >> k & 1)) return false;
+  bool ok = false;
+  if (!furiten(c, o)) {
+    HandOut r;
+    eval_seat(c, o, k, false, chankan, r);
+    ok = r.yaku_ok;
+  }
+  if (!ok) mark_furiten(c, o);
+  return ok;
 }
 
 // what seat o may do about the tile just discarded by d
@@ -461,16 +478,7 @@ MJ_HD void response_options(Ctx &c, int o, int d, int code, uint64_t m[2])
   int k = code_kind(code);
   m[0] = m[1] = 0;
   uint32_t sw = SW(c, o);
-  if (WAITS(c, o) >> k & 1) {
-    bool ok = false;
-    if (!furiten(c, o)) {
-      HandOut r;
-      eval_seat(c, o, k, false, false, r);
-      ok = r.yaku_ok;
-    }
-    if (ok) set_action(m, A_RON);
-    else mark_furiten(c, o);
-  }
+  if (ron_option(c, o, k, false)) set_action(m, A_RON);
   if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0) {
     int su = suit_of(k), r = rank_of(k, su);
     uint32_t hw = HW(c, o, su);
@@ -506,7 +514,8 @@ MJ_HD void response_options(Ctx &c, int o, int d, int code, uint64_t m[2])
   if (m[0] | m[1]) set_action(m, A_PASS);
 }
 
-MJ_HD void discard(Ctx &c, int s, int k, int red)
+// seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later
+MJ_HD void apply_discard(Ctx &c, int s, int k, int red)
 {
   hand_add(c, s, k, -1);
   uint32_t sw = SW(c, s);
@@ -524,29 +533,9 @@ MJ_HD void discard(Ctx &c, int s, int k, int red)
   sw &= ~(1u << SW_FIRST);
   SW(c, s) = sw;
   c.g.kuikae0 = c.g.kuikae1 = 255;
-  refresh_waits(c, s);
   c.g.last_discard = (uint8_t)(k | red << 6);
   c.g.last_discarder = (uint8_t)s;
   c.g.drawn = 255;
-
-  int any = 0;
-  uint64_t m[4][2];
-#pragma unroll
-  for (int o = 0; o < 4; o++) {
-    m[o][0] = m[o][1] = 0;
-    if (o == s) continue;
-    response_options(c, o, s, c.g.last_discard, m[o]);
-    if (m[o][0] | m[o][1]) any |= 1 << o;
-  }
-  if (any) {
-    c.g.phase = PH_RESPOND;
-    c.g.actor_mask = (uint8_t)any;
-#pragma unroll
-    for (int o = 0; o < 4; o++) { MASK(c, o, 0) = m[o][0]; MASK(c, o, 1) = m[o][1]; }
-    return;
-  }
-  if (settle_discard(c)) return;
-  advance(c);
 }
 
 MJ_HD void remove_tiles(Ctx &c, int s, int k, int n_nonred, int take_red)
@@ -561,7 +550,8 @@ MJ_HD void push_meld(Ctx &c, int s, uint32_t m)
   swf_set(c, s, SW_NMELD, 3, j + 1);
 }
 
-MJ_HD void do_call(Ctx &c, int s, int a)
+// seat s takes the last discard with action a; returns true for an open kan (replacement draw due)
+MJ_HD bool apply_call(Ctx &c, int s, int a)
 {
   int d = c.g.last_discarder, k = code_kind(c.g.last_discard), cred = code_red(c.g.last_discard);
   int from_rel = (d - s) & 3;
@@ -575,41 +565,39 @@ MJ_HD void do_call(Ctx &c, int s, int a)
     remove_tiles(c, s, k, tr ? 1 : 2, tr);
     push_meld(c, s, m_make(MT_PON, k, from_rel, 0, tr | cred, cred));
     c.g.kuikae0 = (uint8_t)k; c.g.kuikae1 = 255;
-    turn_mask(c);
-  } else if (a == A_MINKAN) {
+    return false;
+  }
+  if (a == A_MINKAN) {
     int tr = has_red(c, s, k) ? 1 : 0;
     remove_tiles(c, s, k, tr ? 2 : 3, tr);
     push_meld(c, s, m_make(MT_MINKAN, k, from_rel, 0, tr | cred, cred));
-    refresh_waits(c, s);
-    finish_kan(c);
-  } else {
-    int v = a - A_CHI_L, tr = v >= 3 ? 1 : 0, pos = v % 3, base = k - pos;
-    for (int t = 0; t < 3; t++) {
-      if (t == pos) continue;
-      int kk = base + t, r = (tr && is_five(kk)) ? 1 : 0;
-      remove_tiles(c, s, kk, r ? 0 : 1, r);
-    }
-    push_meld(c, s, m_make(MT_CHI, base, from_rel, pos, tr | cred, cred));
-    int rk = k % 9;
-    c.g.kuikae0 = (uint8_t)k;
-    c.g.kuikae1 = 255;
-    if (pos == 0 && rk + 3 <= 8) c.g.kuikae1 = (uint8_t)(k + 3);
-    if (pos == 2 && rk - 3 >= 0) c.g.kuikae1 = (uint8_t)(k - 3);
-    turn_mask(c);
+    return true;
   }
+  int v = a - A_CHI_L, tr = v >= 3 ? 1 : 0, pos = v % 3, base = k - pos;
+  for (int t = 0; t < 3; t++) {
+    if (t == pos) continue;
+    int kk = base + t, r = (tr && is_five(kk)) ? 1 : 0;
+    remove_tiles(c, s, kk, r ? 0 : 1, r);
+  }
+  push_meld(c, s, m_make(MT_CHI, base, from_rel, pos, tr | cred, cred));
+  int rk = k % 9;
+  c.g.kuikae0 = (uint8_t)k;
+  c.g.kuikae1 = 255;
+  if (pos == 0 && rk + 3 <= 8) c.g.kuikae1 = (uint8_t)(k + 3);
+  if (pos == 2 && rk - 3 >= 0) c.g.kuikae1 = (uint8_t)(k - 3);
+  return false;
 }
 
-MJ_HD void own_kan(Ctx &c, int k)
+// KAN on the own turn; returns true for a concealed kan, false for a tile added to a pon (which can be robbed)
+MJ_HD bool apply_own_kan(Ctx &c, int k)
 {
   int s = c.g.cur;
   int tr = has_red(c, s, k) ? 1 : 0;
+  c.g.drawn = 255;
   if (count_of(c, s, k) == 4) {
     remove_tiles(c, s, k, tr ? 3 : 4, tr);
     push_meld(c, s, m_make(MT_ANKAN, k, 0, 0, tr, 0));
-    c.g.drawn = 255;
-    refresh_waits(c, s);
-    finish_kan(c);
-    return;
+    return true;
   }
   remove_tiles(c, s, k, tr ? 0 : 1, tr);
   uint64_t mw = MELDW(c, s);
@@ -623,31 +611,7 @@ MJ_HD void own_kan(Ctx &c, int k)
   }
   MELDW(c, s) = mw;
   c.g.kakan_tile = (uint8_t)(k | tr << 6);
-  c.g.drawn = 255;
-  refresh_waits(c, s);
-  int any = 0;
-  uint64_t m[4][2];
-#pragma unroll
-  for (int o = 0; o < 4; o++) {
-    m[o][0] = m[o][1] = 0;
-    if (o == s || !(WAITS(c, o) >> k & 1)) continue;
-    bool ok = false;
-    if (!furiten(c, o)) {
-      HandOut r;
-      eval_seat(c, o, k, false, true, r);
-      ok = r.yaku_ok;
-    }
-    if (ok) { set_action(m[o], A_RON); set_action(m[o], A_PASS); any |= 1 << o; }
-    else mark_furiten(c, o);
-  }
-  if (any) {
-    c.g.phase = PH_RESPOND_KAKAN;
-    c.g.actor_mask = (uint8_t)any;
-#pragma unroll
-    for (int o = 0; o < 4; o++) { MASK(c, o, 0) = m[o][0]; MASK(c, o, 1) = m[o][1]; }
-    return;
-  }
-  finish_kan(c);
+  return false;
 }
 
 MJ_HD void mark_passed_ron(Ctx &c)
@@ -656,18 +620,26 @@ MJ_HD void mark_passed_ron(Ctx &c)
     if ((c.g.actor_mask >> s & 1) && (MASK(c, s, 1) >> (A_RON - 64) & 1)) mark_furiten(c, s);
 }
 
-// One step of one environment; `acts` packs the four seats' actions as signed bytes (seat s in byte s).
-// When the step ends a kyoku and the game goes on, need_deal is set and the caller deals (shuffle, deal).
+// One step of one environment, as a fixed sequence of stages that every lane walks through in the same order
+// (each lane skips the stages it does not need), so that a wavefront executes each piece of code once per step:
+//   0 check the actions   1 apply them (discard, call, kan, declarations)   2 refresh the actor's waits
+//   3 offer responses (ron / pon / kan / chi, or robbing an added kan)      4 wins and draws: pay, rotate
+//   5 draw (live wall or replacement tile)
+// then, outside: deal when need_deal is set, and step_finish() for the mask of the seat to move.
+// `acts` packs the four seats' actions as signed bytes (seat s in byte s).
 MJ_HD void step_env(Ctx &c, uint32_t acts)
 {
   const int a[4] = {(int8_t)(acts), (int8_t)(acts >> 8), (int8_t)(acts >> 16), (int8_t)(acts >> 24)};
   c.need_deal = false;
+  c.need_turn = false;
 #pragma unroll
   for (int s = 0; s < 4; s++) DELTA(c, s) = 0;
   c.g.illegal_seat = 255;
   if (c.g.terminated) return;
+  // stage 0: an action outside the mask ends the game at once
+  const int actors = c.g.actor_mask;
   for (int s = 0; s < 4; s++) {
-    if (!(c.g.actor_mask >> s & 1)) continue;
+    if (!(actors >> s & 1)) continue;
     int x = a[s];
     bool ok = x >= 0 && x < N_ACTIONS && (MASK(c, s, x >> 6) >> (x & 63) & 1);
     if (!ok) {
@@ -680,39 +652,81 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       return;
     }
   }
-  int actors = c.g.actor_mask;
+  // stage 1: apply
+  int waits_seat = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
+  bool respond = false, rob = false, advance = false, kan_fin = false, win_tsumo = false, win_rob = false;
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = a[s];
-    if (act < A_DISCARD_RED) discard(c, s, act, 0);
-    else if (act < A_KAN) discard(c, s, 4 + 9 * (act - A_DISCARD_RED), 1);
-    else if (act < A_RIICHI) own_kan(c, act - A_KAN);
-    else if (act == A_RIICHI) { c.g.riichi_pending = (SW(c, s) >> SW_FIRST & 1) ? 2 : 1; turn_mask(c); }
-    else if (act == A_TSUMO) win(c, 1 << s, true, -1, code_kind(c.g.drawn), false);
-    else abortive_draw(c, 4);
-  } else if (c.g.phase == PH_RESPOND) {
-    int d = c.g.last_discarder, ronners = 0;
-    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] == A_RON) ronners |= 1 << s;
-    if (popc32((uint32_t)ronners) == 3 && (c.R.flags & F_ABORT)) { clear_masks(c); abortive_draw(c, 8); return; }
-    if (ronners) { clear_masks(c); win(c, ronners, false, d, code_kind(c.g.last_discard), false); return; }
-    mark_passed_ron(c);
-    int caller = -1, call = 0;
-    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] >= A_PON && a[s] <= A_MINKAN) { caller = s; call = a[s]; }
-    if (caller < 0) {
-      int nx = (d + 1) & 3;
-      if ((actors >> nx & 1) && a[nx] >= A_CHI_L && a[nx] < A_PASS) { caller = nx; call = a[nx]; }
-    }
-    clear_masks(c);
-    if (settle_discard(c)) return;
-    if (caller >= 0) do_call(c, caller, call);
-    else advance(c);
-  } else if (c.g.phase == PH_RESPOND_KAKAN) {
+    if (act < A_KAN) {
+      if (act < A_DISCARD_RED) apply_discard(c, s, act, 0);
+      else apply_discard(c, s, 4 + 9 * (act - A_DISCARD_RED), 1);
+      waits_seat = s; respond = true;
+    } else if (act < A_RIICHI) {
+      if (apply_own_kan(c, act - A_KAN)) kan_fin = true; else rob = true;
+      waits_seat = s;
+    } else if (act == A_RIICHI) {
+      c.g.riichi_pending = (SW(c, s) >> SW_FIRST & 1) ? 2 : 1;
+      c.need_turn = true;
+    } else if (act == A_TSUMO) {
+      win_mask = 1 << s; win_tsumo = true; win_tile = code_kind(c.g.drawn);
+    } else end_abort = 4;
+  } else {
     int ronners = 0;
     for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] == A_RON) ronners |= 1 << s;
-    if (ronners) { clear_masks(c); win(c, ronners, false, c.g.cur, code_kind(c.g.kakan_tile), true); return; }
-    mark_passed_ron(c);
-    clear_masks(c);
-    finish_kan(c);
+    if (c.g.phase == PH_RESPOND) {
+      int d = c.g.last_discarder;
+      if (popc32((uint32_t)ronners) == 3 && (c.R.flags & F_ABORT)) end_abort = 8;
+      else if (ronners) { win_mask = ronners; win_loser = d; win_tile = code_kind(c.g.last_discard); }
+      else {
+        mark_passed_ron(c);
+        int caller = -1, call = 0;
+        for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] >= A_PON && a[s] <= A_MINKAN) { caller = s; call = a[s]; }
+        int nx = (d + 1) & 3;
+        if (caller < 0 && (actors >> nx & 1) && a[nx] >= A_CHI_L && a[nx] < A_PASS) { caller = nx; call = a[nx]; }
+        end_abort = settle_discard(c);
+        if (!end_abort) {
+          if (caller < 0) advance = true;
+          else if (apply_call(c, caller, call)) { waits_seat = caller; kan_fin = true; }
+          else c.need_turn = true;
+        }
+      }
+    } else {
+      if (ronners) { win_mask = ronners; win_loser = c.g.cur; win_tile = code_kind(c.g.kakan_tile); win_rob = true; }
+      else { mark_passed_ron(c); kan_fin = true; }
+    }
   }
+  clear_masks(c);
+  // stage 2: the seat whose concealed hand is back to 13 - 3 * melds tiles gets its waits refreshed
+  if (waits_seat >= 0) refresh_waits(c, waits_seat);
+  // stage 3: responses of the other seats
+  if (respond || rob) {
+    int from = respond ? c.g.last_discarder : c.g.cur;
+    int code = respond ? c.g.last_discard : c.g.kakan_tile;
+    int any = 0;
+    for (int j = 1; j < 4; j++) {
+      int o = (from + j) & 3;
+      uint64_t m[2] = {0, 0};
+      if (respond) response_options(c, o, from, code, m);
+      else if (ron_option(c, o, code_kind(code), true)) { set_action(m, A_RON); set_action(m, A_PASS); }
+      if (m[0] | m[1]) { any |= 1 << o; MASK(c, o, 0) = m[0]; MASK(c, o, 1) = m[1]; }
+    }
+    if (any) {
+      c.g.phase = respond ? PH_RESPOND : PH_RESPOND_KAKAN;
+      c.g.actor_mask = (uint8_t)any;
+    } else if (respond) {
+      end_abort = settle_discard(c);
+      if (!end_abort) advance = true;
+    } else kan_fin = true;
+  }
+  bool exhaust = false;
+  if (advance && c.g.live_left == 0) { exhaust = true; advance = false; }
+  // stage 4: the kyoku ends
+  if (win_mask) win(c, win_mask, win_tsumo, win_loser, win_tile, win_rob);
+  else if (end_abort) abortive_draw(c, end_abort);
+  else if (exhaust) exhaustive_draw(c);
+  // stage 5: draws
+  if (advance) { draw_live(c, (c.g.last_discarder + 1) & 3); c.need_turn = true; }
+  if (kan_fin) { kan_draw(c); c.need_turn = true; }
 }
 
 // uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)

@@ -40,20 +40,28 @@ struct DevTables {
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
 constexpr int kDealSlotBytes = 272;      // per wave: 136 wall bytes + 136 swap targets
 
+// A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
+// occupies 2x or 4x as many wavefronts, which lets a SIMD overlap the LDS / memory latency of one wavefront
+// with the instructions of another and shrinks the set of divergent paths per wavefront.  The step is bound by
+// dependent-access latency, not by lane count, so small batches run faster that way.
 // LDS of a step kernel: probe tables | hot u64 arrays | hot u32 arrays | one deal slot per wave
-__host__ __device__ inline size_t step_lds_bytes(int probe_bytes)
+__host__ __device__ inline int envs_per_block(int lpw) { return (kBlock / 64) * lpw; }
+__host__ __device__ inline size_t step_lds_bytes(int probe_bytes, int lpw)
 {
-  return (size_t)probe_bytes + (size_t)kBlock * kHotBytesPerEnv + (size_t)(kBlock / 64) * kDealSlotBytes;
+  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * kHotBytesPerEnv + (size_t)(kBlock / 64) * kDealSlotBytes;
 }
 
 struct BlockMem {
   Lut L;
-  uint64_t *hq;                          // [kHotU64][kBlock]
-  uint32_t *hw;                          // [kHotU32][kBlock]
+  uint64_t *hq;                          // [kHotU64][envs per block]
+  uint32_t *hw;                          // [kHotU32][envs per block]
   uint8_t *slot;                         // this wave's deal slot
+  int epb, idx;                          // envs per block; this lane's env slot in the block
+  bool lane_on;                          // this lane carries an environment
 };
 
 // carve up the block's LDS and copy the probe tables in (ends with a block barrier)
+template <int LPW>
 __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds)
 {
   const uint4 *src = (const uint4 *)T.probe;
@@ -63,9 +71,12 @@ __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds
   m.L.rowid = lds;
   m.L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
   m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.keyinfo = T.keyinfo; m.L.recs = T.recs;
+  m.epb = envs_per_block(LPW);
+  m.idx = (int)(threadIdx.x >> 6) * LPW + (int)(threadIdx.x & 63);
+  m.lane_on = (threadIdx.x & 63) < LPW;
   m.hq = (uint64_t *)(lds + T.probe_bytes);
-  m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)kBlock * 8 * kHotU64);
-  m.slot = lds + T.probe_bytes + (size_t)kBlock * kHotBytesPerEnv + (threadIdx.x >> 6) * kDealSlotBytes;
+  m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)m.epb * 8 * kHotU64);
+  m.slot = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + (threadIdx.x >> 6) * kDealSlotBytes;
   __syncthreads();
   return m;
 }
@@ -73,7 +84,7 @@ __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds
 __device__ __forceinline__ Env block_env(const BlockMem &m, void *state, int64_t B, int64_t b)
 {
   Env e = make_env(state, B, b);
-  set_hot(e, m.hq + threadIdx.x, m.hw + threadIdx.x, kBlock);
+  set_hot(e, m.hq + m.idx, m.hw + m.idx, m.epb);
   return e;
 }
 __device__ __forceinline__ void load_hot(const BlockMem &m, void *state, int64_t B, int64_t b)
@@ -81,18 +92,18 @@ __device__ __forceinline__ void load_hot(const BlockMem &m, void *state, int64_t
   const uint64_t *gq = state_u64(state, B) + b;
   const uint32_t *gw = state_u32(state, B) + b;
 #pragma unroll
-  for (int f = 0; f < kHotU64; f++) m.hq[f * kBlock + threadIdx.x] = gq[(int64_t)f * B];
+  for (int f = 0; f < kHotU64; f++) m.hq[f * m.epb + m.idx] = gq[(int64_t)f * B];
 #pragma unroll
-  for (int f = 0; f < kHotU32; f++) m.hw[f * kBlock + threadIdx.x] = gw[(int64_t)f * B];
+  for (int f = 0; f < kHotU32; f++) m.hw[f * m.epb + m.idx] = gw[(int64_t)f * B];
 }
 __device__ __forceinline__ void store_hot(const BlockMem &m, void *state, int64_t B, int64_t b)
 {
   uint64_t *gq = state_u64(state, B) + b;
   uint32_t *gw = state_u32(state, B) + b;
 #pragma unroll
-  for (int f = 0; f < kHotU64; f++) gq[(int64_t)f * B] = m.hq[f * kBlock + threadIdx.x];
+  for (int f = 0; f < kHotU64; f++) gq[(int64_t)f * B] = m.hq[f * m.epb + m.idx];
 #pragma unroll
-  for (int f = 0; f < kHotU32; f++) gw[(int64_t)f * B] = m.hw[f * kBlock + threadIdx.x];
+  for (int f = 0; f < kHotU32; f++) gw[(int64_t)f * B] = m.hw[f * m.epb + m.idx];
 }
 
 // lanes of one wavefront exchange data through LDS: order the accesses
@@ -147,7 +158,7 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, uint8_t *slot, void
     if (lane == src) deal_tiles(c, wl, 1);
     wave_sync();
   }
-  if (need) { deal_finish(c); c.need_deal = false; }
+  if (need) deal_finish(c);
 }
 
 __device__ __forceinline__ void reset_env(Ctx &c, bool first)
@@ -166,15 +177,16 @@ __device__ __forceinline__ void reset_env(Ctx &c, bool first)
 }
 
 // mode 0: first initialisation of every env; mode 1: restart of the terminated ones
+template <int LPW>
 __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Rules R, DevTables T, int mode)
 {
   extern __shared__ __align__(16) uint8_t lds[];
-  BlockMem m = stage_block(T, lds);
-  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const bool active = b < B;
+  BlockMem m = stage_block<LPW>(T, lds);
+  const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
+  const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false;
+  c.need_deal = false; c.need_turn = false;
   bool touched = false;
   if (active) {
     if (mode == 0) { reset_env(c, true); touched = true; }
@@ -185,25 +197,26 @@ __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Ru
     }
   }
   deal_wave(c, active && c.need_deal, m.slot, state, B, b);
-  if (touched) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
+  if (touched) { step_finish(c); store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
+template <int LPW>
 __global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions)
 {
   extern __shared__ __align__(16) uint8_t lds[];
-  BlockMem m = stage_block(T, lds);
-  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const bool active = b < B;
+  BlockMem m = stage_block<LPW>(T, lds);
+  const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
+  const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false;
+  c.need_deal = false; c.need_turn = false;
   if (active) {
     load_hot(m, state, B, b);
     load_glob(c.e, c.g);
     step_env(c, ((const uint32_t *)actions)[b]);
   }
   deal_wave(c, active && c.need_deal, m.slot, state, B, b);
-  if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
+  if (active) { step_finish(c); store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
 // the random policy for every acting seat of the lane's environment, packed as four signed bytes
@@ -220,16 +233,17 @@ __device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step)
 }
 
 // n_steps of { sample, step, optional reset } without leaving the kernel: environments never interact
+template <int LPW>
 __global__ void __launch_bounds__(kBlock) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
                                                     int n_steps, int auto_reset)
 {
   extern __shared__ __align__(16) uint8_t lds[];
-  BlockMem m = stage_block(T, lds);
-  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  const bool active = b < B;
+  BlockMem m = stage_block<LPW>(T, lds);
+  const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
+  const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false;
+  c.need_deal = false; c.need_turn = false;
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
   for (int t = 0; t < n_steps; t++) {
     if (active) {
@@ -237,6 +251,7 @@ __global__ void __launch_bounds__(kBlock) k_rollout(void *state, int64_t B, Rule
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }
     deal_wave(c, active && c.need_deal, m.slot, state, B, b);
+    if (active) step_finish(c);
   }
   if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
@@ -246,10 +261,11 @@ __global__ void __launch_bounds__(kBlock) k_deal_from_wall(void *state, int64_t 
                                                            const uint8_t *wall)
 {
   extern __shared__ __align__(16) uint8_t lds[];
-  BlockMem m = stage_block(T, lds);
+  BlockMem m = stage_block<64>(T, lds);
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
   Ctx c;
   c.e = make_env(state, B, b); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
+  c.need_deal = false; c.need_turn = false;
   load_glob(c.e, c.g);
   for (int i = 0; i < 136; i++) WALL(c, i) = wall[i];
   deal(c, false);
@@ -446,6 +462,7 @@ struct MjHandle {
   void *d_state, *d_scratch;
   DevTables T;
   size_t lds_bytes, probe_bytes;
+  int lpw;
   hipEvent_t ev[2];
   int ev_steps;
   bool ev_valid;
@@ -475,7 +492,24 @@ ScratchLayout scratch_layout()
 }
 size_t scratch_bytes_impl() { return scratch_layout().total; }
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kAuxBlock - 1) / kAuxBlock); }
-inline unsigned step_blocks(int64_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
+inline unsigned step_blocks(int64_t n, int lpw) { int e = envs_per_block(lpw); return (unsigned)((n + e - 1) / e); }
+// lanes per wave for a batch: fill the machine's wave slots (256 CUs x 4 SIMDs x 2 resident waves of this kernel)
+inline int pick_lpw(int64_t B)
+{
+  const char *ov = std::getenv("MJ_LPW");
+  if (ov) { int v = std::atoi(ov); if (v == 64 || v == 32 || v == 16) return v; }
+  if (B >= 2048 * 64) return 64;
+  if (B >= 2048 * 32) return 32;
+  return 16;
+}
+#define MJ_LAUNCH_STEP(kern, h, st, ...)                                                                         \
+  do {                                                                                                           \
+    size_t lds_ = step_lds_bytes((int)(h)->probe_bytes, (h)->lpw);                                               \
+    unsigned nb_ = step_blocks((h)->B, (h)->lpw);                                                                \
+    if ((h)->lpw == 64) kern<64><<<nb_, kBlock, lds_, st>>>(__VA_ARGS__);                                        \
+    else if ((h)->lpw == 32) kern<32><<<nb_, kBlock, lds_, st>>>(__VA_ARGS__);                                   \
+    else kern<16><<<nb_, kBlock, lds_, st>>>(__VA_ARGS__);                                                       \
+  } while (0)
 inline int check(hipError_t e) { return e == hipSuccess ? MJ_OK : MJ_E_HIP; }
 
 }  // namespace
@@ -521,7 +555,8 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   int dev = 0, lds_max = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) { delete h; return MJ_E_HIP; }
-  h->lds_bytes = step_lds_bytes((int)sl.probe_bytes);
+  h->lpw = pick_lpw(B);
+  h->lds_bytes = step_lds_bytes((int)sl.probe_bytes, 64);
   h->probe_bytes = sl.probe_bytes;
   if ((size_t)lds_max < h->lds_bytes) { delete h; return MJ_E_UNSUPPORTED; }
   hipStream_t st = (hipStream_t)stream;
@@ -545,7 +580,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[0]));
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[1]));
   if (rc != MJ_OK) { delete h; return rc; }
-  k_new_games<<<step_blocks(B), kBlock, h->lds_bytes, st>>>(d_state, B, h->R, h->T, 0);
+  MJ_LAUNCH_STEP(k_new_games, h, st, d_state, B, h->R, h->T, 0);
   rc = check(hipGetLastError());
   if (rc != MJ_OK) { delete h; return rc; }
   *out = h;
@@ -555,7 +590,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
 int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
 {
   if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
-  k_step<<<step_blocks(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, d_actions);
+  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions);
   h->step++;
   return check(hipGetLastError());
 }
@@ -587,7 +622,7 @@ int mj_reward(const MjHandle *h, int32_t *d_delta, float *d_reward, uint8_t *d_t
 int mj_reset_done(MjHandle *h, void *stream)
 {
   if (!h) return MJ_E_ARG;
-  k_new_games<<<step_blocks(h->B), kBlock, h->lds_bytes, (hipStream_t)stream>>>(h->d_state, h->B, h->R, h->T, 1);
+  MJ_LAUNCH_STEP(k_new_games, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, 1);
   return check(hipGetLastError());
 }
 
@@ -609,12 +644,12 @@ int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, 
     // environments never interact, so many steps run inside one launch; chunked to bound a launch's duration
     for (int t = 0; t < n_steps && rc == MJ_OK; t += MJ_ROLLOUT_CHUNK) {
       int n = n_steps - t < MJ_ROLLOUT_CHUNK ? n_steps - t : MJ_ROLLOUT_CHUNK;
-      k_rollout<<<step_blocks(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
+      MJ_LAUNCH_STEP(k_rollout, h, st, h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
       rc = check(hipGetLastError());
     }
   } else {
     for (int t = 0; t < n_steps && rc == MJ_OK; t++) {
-      k_rollout<<<step_blocks(h->B), kBlock, h->lds_bytes, st>>>(h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset);
+      MJ_LAUNCH_STEP(k_rollout, h, st, h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset);
       rc = check(hipGetLastError());
       if (rc == MJ_OK) rc = mj_observe(h, d_obs, stream);
     }

@@ -32,7 +32,7 @@ static Ctx ctx_of(Sim *h, int64_t b)
   Ctx c;
   c.e = make_env(h->state.data(), h->B, b);
   c.L = h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
-  c.need_deal = false;
+  c.need_deal = false; c.need_turn = false;
   return c;
 }
 static void reset_env(Ctx &c, bool first)
@@ -46,6 +46,7 @@ static void reset_env(Ctx &c, bool first)
   } else { c.e.episode[0]++; c.e.serial[0]++; }
   new_game(c);
   if (c.need_deal) deal(c, true);
+  step_finish(c);
 }
 static uint32_t pack4(const int a[4])
 {
@@ -55,6 +56,7 @@ static void step_and_deal(Ctx &c, const int a[4])
 {
   step_env(c, pack4(a));
   if (c.need_deal) deal(c, true);
+  step_finish(c);
 }
 
 extern "C" {
