@@ -25,6 +25,9 @@
 #ifndef MJ_STAT
 #define MJ_STAT(x) ((void)0)
 #endif
+// Out-of-line functions must be LEAVES: an out-of-line function that called another out-of-line function from
+// divergent code gave wrong results on the GPU (values of lanes that did not take the call were lost), while
+// the same source was correct on the host.  Everything an out-of-line function calls is force-inlined.
 #ifndef MJ_HD_NOINLINE
 #define MJ_HD_NOINLINE __host__ __device__ __attribute__((noinline))
 #endif
@@ -54,7 +57,8 @@ struct Rules {
   uint32_t seed;
 };
 
-// the per-suit pattern table: probe part (LDS) and record part (global memory)
+// the per-suit pattern table: probe part (LDS) and record part (global memory).  The out-of-line functions
+// receive a pointer to this struct (the kernels keep one copy per block in LDS).
 struct Lut {
   const uint8_t *rowid;      // [3125] row of a prefix
   const uint32_t *bitmap;    // [rows][20] valid suffixes of a row
@@ -194,12 +198,19 @@ MJ_HD int meld_count(uint32_t m, int k)
   if (t >= MT_MINKAN) return k == b ? 4 : 0;
   return 0;
 }
-MJ_HD int hand_count(const uint32_t h[4], int k) { int su = suit_of(k); return cnt3(h[su], rank_of(k, su)); }
+// element su of four values without an indexed array (arrays indexed at run time live in scratch memory)
+MJ_HD uint32_t pick4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, int su)
+{
+  uint32_t lo = (su & 1) ? a1 : a0, hi = (su & 1) ? a3 : a2;
+  return (su & 2) ? hi : lo;
+}
+MJ_HD int hand_count(const uint32_t h[4], int k) { int su = suit_of(k); return cnt3(pick4(h[0], h[1], h[2], h[3], su), rank_of(k, su)); }
 
 MJ_HD bool suit_valid(const Lut &L, int su, uint32_t w) { return su == 3 ? honors_valid(w) : lut_valid(L, w); }
 // ranks r (bit r) with count < 4 whose addition makes the suit word valid
-MJ_HD uint32_t suit_addmask(const Lut &L, int su, uint32_t w)
+MJ_HD uint32_t suit_addmask(const Lut *Lp, int su, uint32_t w)
 {
+  const Lut &L = *Lp;
   uint32_t m = 0;
   if (su < 3) {
 #pragma unroll
@@ -259,8 +270,9 @@ MJ_HD uint64_t kinds_where(const uint32_t h[4], int v)     // 34-bit mask of kin
 
 // Waits of a (13 - 3*n_meld)-tile hand: kinds whose addition completes it and
 // of which the seat owns fewer than four.
-MJ_HD_NOINLINE uint64_t waits_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
+MJ_HD_NOINLINE uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
 {
+  const Lut &L = *Lp;
   MJ_STAT(n_waits);
   uint32_t h[4] = {h0, h1, h2, h3};
   uint64_t w = 0;
@@ -283,7 +295,7 @@ MJ_HD_NOINLINE uint64_t waits_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_
     for (int s = 0; s < 4; s++) {
       if (rem[s] == 0) continue;
       if (bad > 1 || (bad == 1 && bad_suit != s)) continue;
-      w |= (uint64_t)suit_addmask(L, s, h[s]) << (9 * s);
+      w |= (uint64_t)suit_addmask(Lp, s, h[s]) << (9 * s);
     }
   }
   if (n_meld == 0) {
@@ -300,62 +312,73 @@ MJ_HD_NOINLINE uint64_t waits_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_
 
 // Kinds whose discard leaves the 14 - 3*n_meld tiles of a hand tenpai (non-empty waits_of).  Shares the
 // per-suit work between the candidate discards: only the suit that loses the tile is looked up again.
-MJ_HD_NOINLINE uint64_t tenpai_discards_of(const Lut &L, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
+// Per-suit facts are packed into scalars (remainders 2 bits each, validity and "computed" flags 1 bit each,
+// add-masks 9 bits each) so that nothing here is an indexed array.
+MJ_HD_NOINLINE uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
                                            int n_meld)
 {
+  const Lut &L = *Lp;
   MJ_STAT(n_tenpai);
-  uint32_t h[4] = {h0, h1, h2, h3};
-  int rem[4];
-  bool v[4];
+  const uint32_t h[4] = {h0, h1, h2, h3};
+  uint32_t remp = 0, valid = 0;
   int n_invalid = 0, t1 = 0, t2 = 0;
 #pragma unroll
   for (int s = 0; s < 4; s++) {
-    rem[s] = tiles_in(h[s]) % 3;
-    t1 += rem[s] == 1; t2 += rem[s] == 2;
-    v[s] = suit_valid(L, s, h[s]);
-    n_invalid += v[s] ? 0 : 1;
+    int r = tiles_in(h[s]) % 3;
+    remp |= (uint32_t)r << (2 * s);
+    t1 += r == 1; t2 += r == 2;
+    bool v = r != 1 && suit_valid(L, s, h[s]);
+    valid |= (v ? 1u : 0u) << s;
+    n_invalid += v ? 0 : 1;
   }
   uint64_t out = 0;
   if (n_invalid <= 2) {
     uint64_t full = own4_mask(h, meldw, n_meld);
-    // add[s]: ranks whose addition makes suit s valid and of which fewer than four are owned; computed on demand
-    uint32_t add[4] = {0, 0, 0, 0};
-    bool have[4] = {false, false, false, false};
+    uint64_t addp = 0;            // add-mask of suit s in bits 9s..9s+8, valid once bit s of `have` is set
+    uint32_t have = 0;
     for (int s1 = 0; s1 < 4; s1++) {
-      if (h[s1] == 0) continue;
+      const uint32_t hs1 = pick4(h0, h1, h2, h3, s1);
+      if (hs1 == 0) continue;
+      const int rem1 = (int)(remp >> (2 * s1) & 3);
       // which suits may take the new tile when a tile leaves s1: the final remainders must be one 2 and three 0.
       // A suit that loses a tile goes 0 -> 2, 1 -> 0, 2 -> 1; one that gains a tile goes 0 -> 1, 1 -> 2, 2 -> 0.
-      int feas = 0;
-      if (t1 == 0 && t2 == 1) feas |= 1 << s1;                                  // the tile comes back into s1
+      uint32_t feas = 0;
+      if (t1 == 0 && t2 == 1) feas |= 1u << s1;                                  // the tile comes back into s1
       for (int s2 = 0; s2 < 4; s2++) {
         if (s2 == s1) continue;
-        bool f = (rem[s1] == 0 && rem[s2] == 2 && t2 == 1 && t1 == 0) || (rem[s1] == 1 && rem[s2] == 1 && t1 == 2 && t2 == 0) ||
-                 (rem[s1] == 1 && rem[s2] == 2 && t1 == 1 && t2 == 2);
-        if (f) feas |= 1 << s2;
+        const int rem2 = (int)(remp >> (2 * s2) & 3);
+        bool f = (rem1 == 0 && rem2 == 2 && t2 == 1 && t1 == 0) || (rem1 == 1 && rem2 == 1 && t1 == 2 && t2 == 0) ||
+                 (rem1 == 1 && rem2 == 2 && t1 == 1 && t2 == 2);
+        if (f) feas |= 1u << s2;
       }
       if (!feas) continue;
-      // the untouched suits must be valid as they are
-      int others_bad = 0, bad_other = -1;
-      for (int s = 0; s < 4; s++) if (s != s1 && !v[s]) { others_bad++; bad_other = s; }
-      if (others_bad > 1) continue;
-      int nr = s1 == 3 ? 7 : 9, basek = s1 == 3 ? 27 : 9 * s1;
+      // the untouched suits must be valid as they are (at most one of them may be the one that takes the tile)
+      const uint32_t bad_others = ~valid & 15u & ~(1u << s1);
+      if (popc32(bad_others) > 1) continue;
+      const int nr = s1 == 3 ? 7 : 9, basek = s1 == 3 ? 27 : 9 * s1;
       for (int r = 0; r < nr; r++) {
-        if (cnt3(h[s1], r) == 0) continue;
-        uint32_t g = h[s1] - (1u << (3 * r));
+        if (cnt3(hs1, r) == 0) continue;
+        const uint32_t g = hs1 - (1u << (3 * r));
         bool ok = false;
         // the new tile goes to another suit s2: g must be valid, and s2 is the only suit allowed to be invalid now
         if (suit_valid(L, s1, g)) {
-          for (int s2 = 0; s2 < 4 && !ok; s2++) {
-            if (s2 == s1 || !(feas >> s2 & 1)) continue;
-            if (others_bad == 1 && bad_other != s2) continue;
-            if (!have[s2]) { add[s2] = suit_addmask(L, s2, h[s2]) & ~(uint32_t)(full >> (9 * s2) & 0x1FF); have[s2] = true; }
-            ok = add[s2] != 0;
+          uint32_t cand = feas & ~(1u << s1);
+          if (bad_others) cand &= bad_others;
+          while (cand && !ok) {
+            const int s2 = __builtin_ctz(cand);
+            cand &= cand - 1;
+            if (!(have >> s2 & 1)) {
+              uint64_t am = suit_addmask(Lp, s2, pick4(h0, h1, h2, h3, s2)) & ~(uint32_t)(full >> (9 * s2) & 0x1FF);
+              addp |= am << (9 * s2);
+              have |= 1u << s2;
+            }
+            ok = (addp >> (9 * s2) & 0x1FF) != 0;
           }
         }
         // the new tile goes back into s1
-        if (!ok && (feas >> s1 & 1) && others_bad == 0) {
+        if (!ok && (feas >> s1 & 1) && bad_others == 0) {
           uint32_t blocked = (uint32_t)(full >> (9 * s1) & 0x1FF) & ~(1u << r);     // the discarded kind is owned one less
-          ok = (suit_addmask(L, s1, g) & ~blocked) != 0;
+          ok = (suit_addmask(Lp, s1, g) & ~blocked) != 0;
         }
         if (ok) out |= kbit(basek + r);
       }
@@ -366,9 +389,10 @@ MJ_HD_NOINLINE uint64_t tenpai_discards_of(const Lut &L, uint32_t h0, uint32_t h
     bool chiitoi_near = c.c2 + c.c3 + c.c4 >= 5, kokushi_near = c.total - c.yao_tiles <= 1;
     if (chiitoi_near || kokushi_near) {
       for (int su = 0; su < 4; su++) {
+        const uint32_t hw = pick4(h0, h1, h2, h3, su);
         int nr = su == 3 ? 7 : 9;
         for (int r = 0; r < nr; r++) {
-          int n = cnt3(h[su], r);
+          int n = cnt3(hw, r);
           if (n == 0) continue;
           int c1 = c.c1, c2 = c.c2, c3 = c.c3, c4 = c.c4;
           if (n == 1) c1--; else if (n == 2) { c2--; c1++; } else if (n == 3) { c3--; c2++; } else { c4--; c3++; }
@@ -576,7 +600,7 @@ MJ_HD void eval_decomp(EvalCtx &c, const Decomp &d)
   }
   if (w < 27) {
     int su = suit_of(w), r = rank_of(w, su);
-    uint32_t cr = d.crun[su];
+    uint32_t cr = pick4(d.crun[0], d.crun[1], d.crun[2], 0u, su);
     bool mid = r >= 1 && r <= 7 && cnt3(cr, r - 1) > 0;                 // run r-1, r, r+1
     bool low = r <= 6 && cnt3(cr, r) > 0;                               // run r, r+1, r+2
     bool high = r >= 2 && cnt3(cr, r - 2) > 0;                          // run r-2, r-1, r
@@ -587,8 +611,9 @@ MJ_HD void eval_decomp(EvalCtx &c, const Decomp &d)
   }
 }
 
-MJ_HD_NOINLINE void eval_hand(const Lut &L, const HandIn &q, HandOut &out)
+MJ_HD_NOINLINE void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
 {
+  const Lut &L = *Lp;
   MJ_STAT(n_eval);
   out.yaku = 0; out.points = 0; out.han = out.fu = out.units = out.shape_ok = out.yaku_ok = 0;
   out.n_dora = out.n_ura = out.n_aka = 0;
@@ -647,10 +672,15 @@ MJ_HD_NOINLINE void eval_hand(const Lut &L, const HandIn &q, HandOut &out)
     uint32_t m = meld_at(q.meldw, j);
     int t = m_type(m), k = m_kind(m), su = suit_of(k), r = rank_of(k, su);
     if (t != MT_ANKAN) c.menzen = false;
-    if (t == MT_CHI) { base.orun[su] += 1u << (3 * r); all[su] += 0111u << (3 * r); }
-    else if (t == MT_PON) { base.trip_o |= kbit(k); all[su] += 3u << (3 * r); }
-    else if (t == MT_ANKAN) { base.kan_c |= kbit(k); all[su] += 4u << (3 * r); }
-    else { base.kan_o |= kbit(k); all[su] += 4u << (3 * r); }
+    uint32_t add_all, add_run = 0;
+    if (t == MT_CHI) { add_run = 1u << (3 * r); add_all = 0111u << (3 * r); }
+    else if (t == MT_PON) { base.trip_o |= kbit(k); add_all = 3u << (3 * r); }
+    else if (t == MT_ANKAN) { base.kan_c |= kbit(k); add_all = 4u << (3 * r); }
+    else { base.kan_o |= kbit(k); add_all = 4u << (3 * r); }
+#pragma unroll
+    for (int i = 0; i < 4; i++) all[i] += su == i ? add_all : 0u;
+#pragma unroll
+    for (int i = 0; i < 3; i++) base.orun[i] += su == i ? add_run : 0u;
   }
   c.riichi = c.menzen ? q.riichi : 0;
   c.n_dora = c.n_ura = 0;

@@ -13,7 +13,7 @@ namespace mj {
 
 struct Ctx {
   Env e;
-  Lut L;
+  const Lut *L;
   Rules R;
   Glob g;
   uint32_t env_id;
@@ -132,10 +132,16 @@ MJ_HD uint64_t tenpai_discards(Ctx &c, int s)
   return tenpai_discards_of(c.L, HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3), MELDW(c, s), swf(c, s, SW_NMELD, 3));
 }
 
-MJ_HD void set_action(uint64_t m[2], int a) { m[a >> 6] |= 1ull << (a & 63); }
+// a legal-action mask in two registers (no indexed array, so it never lands in scratch memory)
+struct Mask2 { uint64_t w0, w1; };
+MJ_HD void set_action(Mask2 &m, int a)
+{
+  uint64_t bit = 1ull << (a & 63);
+  if (a < 64) m.w0 |= bit; else m.w1 |= bit;
+}
 
 // discards available from the hand of seat s, restricted to the kinds in `allowed`
-MJ_HD void discard_bits(Ctx &c, int s, uint64_t allowed, uint64_t m[2])
+MJ_HD void discard_bits(Ctx &c, int s, uint64_t allowed, Mask2 &m)
 {
   uint32_t sw = SW(c, s);
   for (int su = 0; su < 4; su++) {
@@ -156,7 +162,7 @@ MJ_HD void turn_mask(Ctx &c)
 {
   MJ_STAT(n_turn);
   int s = c.g.cur;
-  uint64_t m[2] = {0, 0};
+  Mask2 m = {0, 0};
   clear_masks(c);
   c.g.phase = PH_TURN;
   c.g.actor_mask = (uint8_t)(1 << s);
@@ -181,10 +187,11 @@ MJ_HD void turn_mask(Ctx &c)
       if (kan_ok && count_of(c, s, drawn_k) == 4) {
         // a concealed kan is allowed in riichi only when it leaves the waits as they were
         int su = suit_of(drawn_k), n_meld = (int)sw_get(sw, SW_NMELD, 3);
-        uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
-        h[su] -= 4u << (3 * rank_of(drawn_k, su));
+        uint32_t four = 4u << (3 * rank_of(drawn_k, su));
+        uint32_t h0 = HW(c, s, 0) - (su == 0 ? four : 0u), h1 = HW(c, s, 1) - (su == 1 ? four : 0u);
+        uint32_t h2 = HW(c, s, 2) - (su == 2 ? four : 0u), h3 = HW(c, s, 3) - (su == 3 ? four : 0u);
         uint64_t mw = MELDW(c, s) | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
-        if (waits_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld + 1) == WAITS(c, s)) set_action(m, A_KAN + drawn_k);
+        if (waits_of(c.L, h0, h1, h2, h3, mw, n_meld + 1) == WAITS(c, s)) set_action(m, A_KAN + drawn_k);
       }
     } else {
       uint64_t allowed = K_ALL;
@@ -213,8 +220,8 @@ MJ_HD void turn_mask(Ctx &c)
       }
     }
   }
-  MASK(c, s, 0) = m[0];
-  MASK(c, s, 1) = m[1];
+  MASK(c, s, 0) = m.w0;
+  MASK(c, s, 1) = m.w1;
 }
 
 MJ_HD void draw_live(Ctx &c, int s)
@@ -473,10 +480,10 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
 }
 
 // what seat o may do about the tile just discarded by d
-MJ_HD void response_options(Ctx &c, int o, int d, int code, uint64_t m[2])
+MJ_HD void response_options(Ctx &c, int o, int d, int code, Mask2 &m)
 {
   int k = code_kind(code);
-  m[0] = m[1] = 0;
+  m.w0 = m.w1 = 0;
   uint32_t sw = SW(c, o);
   if (ron_option(c, o, k, false)) set_action(m, A_RON);
   if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0) {
@@ -511,7 +518,7 @@ MJ_HD void response_options(Ctx &c, int o, int d, int code, uint64_t m[2])
       }
     }
   }
-  if (m[0] | m[1]) set_action(m, A_PASS);
+  if (m.w0 | m.w1) set_action(m, A_PASS);
 }
 
 // seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later
@@ -614,6 +621,8 @@ MJ_HD bool apply_own_kan(Ctx &c, int k)
   return false;
 }
 
+MJ_HD int act_of(uint32_t acts, int s) { return (int)(int8_t)(acts >> (8 * s)); }
+
 MJ_HD void mark_passed_ron(Ctx &c)
 {
   for (int s = 0; s < 4; s++)
@@ -629,7 +638,6 @@ MJ_HD void mark_passed_ron(Ctx &c)
 // `acts` packs the four seats' actions as signed bytes (seat s in byte s).
 MJ_HD void step_env(Ctx &c, uint32_t acts)
 {
-  const int a[4] = {(int8_t)(acts), (int8_t)(acts >> 8), (int8_t)(acts >> 16), (int8_t)(acts >> 24)};
   c.need_deal = false;
   c.need_turn = false;
 #pragma unroll
@@ -640,7 +648,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   const int actors = c.g.actor_mask;
   for (int s = 0; s < 4; s++) {
     if (!(actors >> s & 1)) continue;
-    int x = a[s];
+    int x = act_of(acts, s);
     bool ok = x >= 0 && x < N_ACTIONS && (MASK(c, s, x >> 6) >> (x & 63) & 1);
     if (!ok) {
       c.g.illegal_seat = (uint8_t)s;
@@ -656,7 +664,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   int waits_seat = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
   bool respond = false, rob = false, advance = false, kan_fin = false, win_tsumo = false, win_rob = false;
   if (c.g.phase == PH_TURN) {
-    int s = c.g.cur, act = a[s];
+    int s = c.g.cur, act = act_of(acts, s);
     if (act < A_KAN) {
       if (act < A_DISCARD_RED) apply_discard(c, s, act, 0);
       else apply_discard(c, s, 4 + 9 * (act - A_DISCARD_RED), 1);
@@ -672,7 +680,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
     } else end_abort = 4;
   } else {
     int ronners = 0;
-    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] == A_RON) ronners |= 1 << s;
+    for (int s = 0; s < 4; s++) if ((actors >> s & 1) && act_of(acts, s) == A_RON) ronners |= 1 << s;
     if (c.g.phase == PH_RESPOND) {
       int d = c.g.last_discarder;
       if (popc32((uint32_t)ronners) == 3 && (c.R.flags & F_ABORT)) end_abort = 8;
@@ -680,9 +688,9 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       else {
         mark_passed_ron(c);
         int caller = -1, call = 0;
-        for (int s = 0; s < 4; s++) if ((actors >> s & 1) && a[s] >= A_PON && a[s] <= A_MINKAN) { caller = s; call = a[s]; }
+        for (int s = 0; s < 4; s++) if ((actors >> s & 1) && act_of(acts, s) >= A_PON && act_of(acts, s) <= A_MINKAN) { caller = s; call = act_of(acts, s); }
         int nx = (d + 1) & 3;
-        if (caller < 0 && (actors >> nx & 1) && a[nx] >= A_CHI_L && a[nx] < A_PASS) { caller = nx; call = a[nx]; }
+        if (caller < 0 && (actors >> nx & 1) && act_of(acts, nx) >= A_CHI_L && act_of(acts, nx) < A_PASS) { caller = nx; call = act_of(acts, nx); }
         end_abort = settle_discard(c);
         if (!end_abort) {
           if (caller < 0) advance = true;
@@ -705,10 +713,10 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
     int any = 0;
     for (int j = 1; j < 4; j++) {
       int o = (from + j) & 3;
-      uint64_t m[2] = {0, 0};
+      Mask2 m = {0, 0};
       if (respond) response_options(c, o, from, code, m);
       else if (ron_option(c, o, code_kind(code), true)) { set_action(m, A_RON); set_action(m, A_PASS); }
-      if (m[0] | m[1]) { any |= 1 << o; MASK(c, o, 0) = m[0]; MASK(c, o, 1) = m[1]; }
+      if (m.w0 | m.w1) { any |= 1 << o; MASK(c, o, 0) = m.w0; MASK(c, o, 1) = m.w1; }
     }
     if (any) {
       c.g.phase = respond ? PH_RESPOND : PH_RESPOND_KAKAN;

@@ -39,6 +39,7 @@ struct DevTables {
 };
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
 constexpr int kDealSlotBytes = 272;      // per wave: 136 wall bytes + 136 swap targets
+constexpr int kLutBytes = 64;            // the block's copy of the table pointers
 
 // A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
 // occupies 2x or 4x as many wavefronts, which lets a SIMD overlap the LDS / memory latency of one wavefront
@@ -48,11 +49,12 @@ constexpr int kDealSlotBytes = 272;      // per wave: 136 wall bytes + 136 swap 
 __host__ __device__ inline int envs_per_block(int lpw) { return (kBlock / 64) * lpw; }
 __host__ __device__ inline size_t step_lds_bytes(int probe_bytes, int lpw)
 {
-  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * kHotBytesPerEnv + (size_t)(kBlock / 64) * kDealSlotBytes;
+  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * kHotBytesPerEnv + (size_t)(kBlock / 64) * kDealSlotBytes + kLutBytes;
 }
 
+static_assert(sizeof(Lut) <= kLutBytes, "table pointer block");
 struct BlockMem {
-  Lut L;
+  const Lut *L;                          // in LDS
   uint64_t *hq;                          // [kHotU64][envs per block]
   uint32_t *hw;                          // [kHotU32][envs per block]
   uint8_t *slot;                         // this wave's deal slot
@@ -68,15 +70,19 @@ __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds
   uint4 *dst = (uint4 *)lds;
   for (int i = threadIdx.x; i < T.probe_bytes / 16; i += blockDim.x) dst[i] = src[i];
   BlockMem m;
-  m.L.rowid = lds;
-  m.L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
-  m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.keyinfo = T.keyinfo; m.L.recs = T.recs;
   m.epb = envs_per_block(LPW);
   m.idx = (int)(threadIdx.x >> 6) * LPW + (int)(threadIdx.x & 63);
   m.lane_on = (threadIdx.x & 63) < LPW;
   m.hq = (uint64_t *)(lds + T.probe_bytes);
   m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)m.epb * 8 * kHotU64);
   m.slot = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + (threadIdx.x >> 6) * kDealSlotBytes;
+  Lut *L = (Lut *)(lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + (kBlock / 64) * kDealSlotBytes);
+  if (threadIdx.x == 0) {
+    L->rowid = lds;
+    L->bitmap = (const uint32_t *)(lds + kRowIdBytes);
+    L->base = T.base; L->rowrank = T.rowrank; L->keyinfo = T.keyinfo; L->recs = T.recs;
+  }
+  m.L = L;
   __syncthreads();
   return m;
 }
@@ -116,7 +122,7 @@ __device__ __forceinline__ void wave_sync()
 
 // Deal for every lane of the wavefront that needs one.  All 64 lanes must call this together.
 // Per environment in turn: 34 lanes run Philox and turn the words into swap targets, the owner lane applies
-// the 135 swaps on the wall in LDS, all lanes copy the wall to HBM, the owner takes its tiles from LDS.
+// the 135 swaps on the wall in LDS, copies the wall to HBM and takes its tiles from LDS.
 // Afterwards the owners compute waits and masks side by side.
 __device__ __forceinline__ void deal_wave(Ctx &c, bool need, uint8_t *slot, void *state, int64_t B, int64_t b)
 {
@@ -124,12 +130,10 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, uint8_t *slot, void
   uint8_t *wl = slot, *kk = slot + 136;
   unsigned long long pending = __ballot(need ? 1 : 0);
   const uint32_t my_serial = need ? c.e.serial[0] : 0u;
-  const uint32_t b_lo = (uint32_t)b, b_hi = (uint32_t)((uint64_t)b >> 32);
   while (pending) {
     const int src = __builtin_ctzll(pending);
     pending &= pending - 1;
     const uint32_t serial = __shfl(my_serial, src), env_id = __shfl(c.env_id, src);
-    const int64_t bsrc = (int64_t)(((uint64_t)__shfl(b_hi, src) << 32) | __shfl(b_lo, src));
     if (lane < 34) {
       uint32_t r[4];
       philox(serial, (uint32_t)lane, 0, 0, c.R.seed, env_id, r);
@@ -151,11 +155,12 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, uint8_t *slot, void
       }
     }
     wave_sync();
-    uint8_t *gw = state_u8(state, B) + bsrc;
-    gw[(int64_t)lane * B] = wl[lane];
-    gw[(int64_t)(lane + 64) * B] = wl[lane + 64];
-    if (lane < 8) gw[(int64_t)(lane + 128) * B] = wl[lane + 128];
-    if (lane == src) deal_tiles(c, wl, 1);
+    if (lane == src) {
+      // the owner itself copies the wall to HBM: it is the lane that later draws from it, and a lane's own
+      // stores are ordered before its own loads (stores of other lanes could be hidden by a stale L1 line)
+      for (int i = 0; i < 136; i++) WALL(c, i) = wl[i];
+      deal_tiles(c, wl, 1);
+    }
     wave_sync();
   }
   if (need) deal_finish(c);
@@ -234,7 +239,7 @@ __device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step)
 
 // n_steps of { sample, step, optional reset } without leaving the kernel: environments never interact
 template <int LPW>
-__global__ void __launch_bounds__(kBlock) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
+__global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
                                                     int n_steps, int auto_reset)
 {
   extern __shared__ __align__(16) uint8_t lds[];
@@ -342,9 +347,13 @@ __global__ void __launch_bounds__(kAuxBlock) k_eval_hands(DevTables T, int64_t n
     for (int j = threadIdx.x; j < T.probe_bytes / 16; j += blockDim.x) dst[j] = src[j];
     __syncthreads();
   }
-  Lut L;
-  L.rowid = lds; L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
-  L.base = T.base; L.rowrank = T.rowrank; L.keyinfo = T.keyinfo; L.recs = T.recs;
+  __shared__ Lut Ls;
+  if (threadIdx.x == 0) {
+    Ls.rowid = lds; Ls.bitmap = (const uint32_t *)(lds + kRowIdBytes);
+    Ls.base = T.base; Ls.rowrank = T.rowrank; Ls.keyinfo = T.keyinfo; Ls.recs = T.recs;
+  }
+  __syncthreads();
+  const Lut *L = &Ls;
   int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (i >= n) return;
   const uint32_t *qw = (const uint32_t *)(in + i);

@@ -31,7 +31,7 @@ static Ctx ctx_of(Sim *h, int64_t b)
 {
   Ctx c;
   c.e = make_env(h->state.data(), h->B, b);
-  c.L = h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
+  c.L = &h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false;
   return c;
 }
@@ -172,7 +172,7 @@ void hs_eval_hands(Sim *h, int64_t n, const MjHandQuery *in, MjHandResult *out)
     hi.seat_wind = q.seat_wind; hi.round_wind = q.round_wind; hi.n_ind = q.n_ind; hi.n_aka = q.n_aka; hi.kuitan = q.kuitan;
     for (int j = 0; j < 5; j++) { hi.ind[j] = q.ind[j]; hi.ura[j] = q.ura[j]; }
     HandOut ho;
-    eval_hand(h->L, hi, ho);
+    eval_hand(&h->L, hi, ho);
     MjHandResult r;
     memset(&r, 0, sizeof r);
     r.yaku = ho.yaku; r.points = ho.points; r.han = (uint8_t)ho.han; r.fu = (uint8_t)ho.fu;
@@ -187,7 +187,7 @@ uint64_t hs_waits(Sim *h, const uint8_t *hand, const uint16_t *meld, int n_meld)
   for (int k = 0; k < 34; k++) { int su = suit_of(k); hw[su] |= (uint32_t)hand[k] << (3 * rank_of(k, su)); }
   uint64_t mw = 0;
   for (int j = 0; j < 4; j++) mw |= (uint64_t)meld[j] << (16 * j);
-  return waits_of(h->L, hw[0], hw[1], hw[2], hw[3], mw, n_meld);
+  return waits_of(&h->L, hw[0], hw[1], hw[2], hw[3], mw, n_meld);
 }
 
 }  // extern "C"

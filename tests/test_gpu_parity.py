@@ -86,6 +86,36 @@ def test_fused_rollout_equals_unfused_and_oracle():
     assert np.array_equal(o.observe(), obs.cpu().numpy())
 
 
+def test_fused_rollout_many_games():
+    """4096 games, red rules, 900 fused steps with auto-reset: every field of every game against the oracle"""
+    B = 4096
+    o = mjo.Oracle(B, 12, mjo.RULES_RED, mjo.MODE_HALF)
+    g = GpuEngine(B, seed=12, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    for n in (450, 450):
+        o.step_random(n); g.step_random(n)
+        d = diff_records(o.export(), g.export())
+        assert not d, (n, d[:4])
+    assert np.array_equal(o.observe(), g.observe())
+
+
+@pytest.mark.parametrize("lpw", [16, 32, 64])
+def test_every_lanes_per_wave_variant(lpw, monkeypatch):
+    """the step kernels exist in three variants (16 / 32 / 64 environments per wavefront); the library picks one
+    by batch size, MJ_LPW forces it"""
+    monkeypatch.setenv("MJ_LPW", str(lpw))
+    B = 777
+    o = mjo.Oracle(B, 21, mjo.RULES_RED, mjo.MODE_HALF)
+    g = GpuEngine(B, seed=21, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    o.step_random(400); g.step_random(400)
+    assert not diff_records(o.export(), g.export())
+    for _ in range(40):
+        a = o.sample_random()
+        assert np.array_equal(a, g.sample_random())
+        o.step(a); g.step(a)
+        o.reset_done(); g.reset_done()
+    assert not diff_records(o.export(), g.export())
+
+
 def test_full_size_sampled_envs():
     """B=65,536 in the benchmark's launch shape; sampled environments recomputed one by one by the oracle"""
     B, steps = 65536, 400
