@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--batch", type=int, default=65536)
     ap.add_argument("--no-extras", action="store_true", help="skip the red-rule and observation side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only-obs", action="store_true",
+                    help="only the configs[4] side run (B = 2^20, red rules, observation written every step), 30 steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB three times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -81,6 +83,13 @@ def main():
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}))
         return
 
+    if args.only_obs:
+        Bo = 1 << 20
+        env = mj.MahjongEnv(Bo, seed=0, flags=mj.RULES_RED, mode=mj.MODE_HALF)
+        obs = torch.empty((Bo, 4, 56, 34), dtype=torch.uint8, device="cuda:0")
+        dt, _ = timed_rollout(env, torch, 10, 30, obs)
+        print(json.dumps({"obs_B": Bo, "obs_env_steps_per_s": Bo * 30 / dt}))
+        return
     env = mj.MahjongEnv(B, seed=0, flags=mj.RULES_NORED, mode=mj.MODE_HALF)
     dt, step_ms = timed_rollout(env, torch, W, K)
     value = B * K / dt

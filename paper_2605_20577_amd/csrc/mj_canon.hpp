@@ -130,10 +130,17 @@ MJ_HD uint64_t obs_seat_masks(const Env &e, int s, uint64_t out[OB_SEAT_WORDS])
   uint32_t rv[4] = {0, 0, 0, 0}, ml[4] = {0, 0, 0, 0};
   uint64_t redvis = 0;
   int nriv = (int)sw_get(sw, SW_NRIVER, 6);
-  for (int i = 0; i < nriv; i++) {
-    int t = e.river[(s * 32 + i) * n];
-    bump(rv, t & 63, 1);
-    if (t & 64) redvis |= kbit(t & 63);
+  // the river bytes are one load each from rows B apart: issue them in groups of eight before using them
+  for (int i0 = 0; i0 < nriv; i0 += 8) {
+    int t[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) t[j] = (i0 + j < nriv) ? e.river[(s * 32 + i0 + j) * n] : 255;
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      if (t[j] == 255) continue;
+      bump(rv, t[j] & 63, 1);
+      if (t[j] & 64) redvis |= kbit(t[j] & 63);
+    }
   }
   uint64_t mw = e.meld[s * n];
   int nm = (int)sw_get(sw, SW_NMELD, 3);

@@ -181,11 +181,19 @@ __device__ __forceinline__ void reset_env(Ctx &c, bool first)
   new_game(c);
 }
 
-// mode 0: first initialisation of every env; mode 1: restart of the terminated ones
+// mode 0: first initialisation of every env; mode 1: restart of the terminated ones (a block without a
+// terminated env leaves before it stages anything)
 template <int LPW>
 __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Rules R, DevTables T, int mode)
 {
   extern __shared__ __align__(16) uint8_t lds[];
+  if (mode == 1) {
+    const int idx = (int)(threadIdx.x >> 6) * LPW + (int)(threadIdx.x & 63);
+    const int64_t b0 = (int64_t)blockIdx.x * envs_per_block(LPW) + idx;
+    int term = 0;
+    if ((threadIdx.x & 63) < LPW && b0 < B) term = (int)(make_env(state, B, b0).glob[0] >> 24 & 0xFFu);   // Glob::terminated
+    if (!__syncthreads_or(term)) return;
+  }
   BlockMem m = stage_block<LPW>(T, lds);
   const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
   const bool active = m.lane_on && b < B;
@@ -196,9 +204,8 @@ __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Ru
   if (active) {
     if (mode == 0) { reset_env(c, true); touched = true; }
     else {
-      load_hot(m, state, B, b);
       load_glob(c.e, c.g);
-      if (c.g.terminated) { reset_env(c, false); touched = true; }
+      if (c.g.terminated) { load_hot(m, state, B, b); reset_env(c, false); touched = true; }
     }
   }
   deal_wave(c, active && c.need_deal, m.slot, state, B, b);
@@ -390,10 +397,10 @@ __global__ void __launch_bounds__(kAuxBlock) k_eval_hands(DevTables T, int64_t n
 }
 
 // Observation writer.  A block takes kObsEnvs environments at a time:
-//  1. 4 lanes per env build the per-seat masks, lane 0 of each quad also the env masks (LDS);
+//  1. 4 lanes per env build the per-seat masks, then one lane per env the env masks (LDS);
 //  2. one lane per (env, viewer) concatenates the 56 planes of 34 bits into a 1904-bit string (LDS);
 //  3. all lanes expand bits to bytes, 16 bytes per store, consecutive lanes on consecutive addresses.
-constexpr int kObsEnvs = 16;
+constexpr int kObsEnvs = 32;             // 49 KB of LDS per block; 16 per block reached 3.9 TB/s, 32 reach 5.2 TB/s
 constexpr int kObsBits = 56 * 34;                 // 1904
 constexpr int kObsWords = 60;                     // u32 words per (env, viewer), 1920 bits
 
@@ -454,7 +461,9 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
       o.y = (((v >> 4) & 0xFu) * 0x00204081u) & 0x01010101u;
       o.z = (((v >> 8) & 0xFu) * 0x00204081u) & 0x01010101u;
       o.w = (((v >> 12) & 0xFu) * 0x00204081u) & 0x01010101u;
-      dst[i] = o;
+      // streaming stores: the tensor is written once and not read back by this kernel (+30 % over plain stores)
+      __builtin_nontemporal_store(o.x, &dst[i].x); __builtin_nontemporal_store(o.y, &dst[i].y);
+      __builtin_nontemporal_store(o.z, &dst[i].z); __builtin_nontemporal_store(o.w, &dst[i].w);
     }
     __syncthreads();
   }
