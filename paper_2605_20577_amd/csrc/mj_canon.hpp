@@ -43,7 +43,7 @@ MJ_HD void export_env(const Env &e, MjEnvCanon &o)
     o.r_dora[s] = (uint8_t)(rw >> 24); o.r_ura[s] = (uint8_t)(rw >> 32); o.r_aka[s] = (uint8_t)(rw >> 40);
   }
   o.episode = e.episode[0]; o.kyoku_serial = e.serial[0];
-  for (int i = 0; i < 136; i++) o.wall[i] = e.wall[i * n];
+  for (int i = 0; i < 136; i++) o.wall[i] = (uint8_t)wall_at(e, i);
   o.kyoku = g.kyoku; o.honba = g.honba; o.kyotaku = g.kyotaku; o.terminated = g.terminated;
   o.draw_ptr = g.draw_ptr; o.n_kan = g.n_kan; o.live_left = g.live_left; o.n_dora = g.n_dora;
   o.drawn = g.drawn; o.phase = g.phase; o.cur = g.cur; o.actor_mask = g.actor_mask;
@@ -86,7 +86,9 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
     e.seatw[s * n] = sw;
   }
   e.episode[0] = o.episode; e.serial[0] = o.kyoku_serial;
-  for (int i = 0; i < 136; i++) e.wall[i * n] = o.wall[i];
+  for (int i = 0; i < 34; i++)
+    e.wallw[i * n] = (uint32_t)o.wall[4 * i] | (uint32_t)o.wall[4 * i + 1] << 8 | (uint32_t)o.wall[4 * i + 2] << 16 |
+                     (uint32_t)o.wall[4 * i + 3] << 24;
   g.kyoku = o.kyoku; g.honba = o.honba; g.kyotaku = o.kyotaku; g.terminated = o.terminated;
   g.draw_ptr = o.draw_ptr; g.n_kan = o.n_kan; g.live_left = o.live_left; g.n_dora = o.n_dora;
   g.drawn = o.drawn; g.phase = o.phase; g.cur = o.cur; g.actor_mask = o.actor_mask;
@@ -170,7 +172,7 @@ MJ_HD void obs_env_masks(const Env &e, const Glob &g, uint32_t rule_flags, uint6
   uint32_t ind[4] = {0, 0, 0, 0};
   uint64_t redvis = seat_red;
   for (int i = 0; i < g.n_dora; i++) {
-    int id = e.wall[(126 + i) * n];
+    int id = wall_at(e, 126 + i);
     bump(ind, id >> 2, 1);
     if ((rule_flags & F_RED) && (id == 16 || id == 52 || id == 88)) redvis |= kbit(id >> 2);
   }

@@ -79,7 +79,9 @@ struct Env {
   uint64_t *yaku, *resw;                              // cold [4] [4]
   int32_t *gain;                                      // cold [4]
   uint32_t *glob;                                     // cold [7] (held in registers during a step)
-  uint8_t *wall, *river;                              // cold [136] [128]
+  uint32_t *wallw;                                    // cold [34]: the 136 wall bytes, four per word
+  uint32_t *nextw, *nserial;                          // cold [34] [1]: the wall of kyoku_serial + 1, made ahead of time
+  uint8_t *river;                                     // cold [128]
 };
 
 // control bytes kept in registers during a step (7 words in HBM)
@@ -180,13 +182,14 @@ MJ_HD uint32_t fields_eq(uint32_t w, int v)   // bit 3r set where field r == v
   return m0 & m1 & m2 & O111;
 }
 MJ_HD uint32_t fields_nonzero(uint32_t w) { return (w | (w >> 1) | (w >> 2)) & O111; }
-// compress the bits at positions 0,3,6,... of nine fields into 9 consecutive bits
+// compress the bits at positions 0,3,6,...,24 of nine fields into 9 consecutive bits (four fold-and-mask steps)
 MJ_HD uint32_t squeeze9(uint32_t m)
 {
-  uint32_t r = 0;
-#pragma unroll
-  for (int i = 0; i < 9; i++) r |= ((m >> (3 * i)) & 1u) << i;
-  return r;
+  uint32_t x = m & O111;
+  x = (x | (x >> 2)) & 0x10C30C3u;      // pairs   at 0,6,12,18 and bit 24
+  x = (x | (x >> 4)) & 0x100F00Fu;      // nibbles at 0,12      and bit 24
+  x = (x | (x >> 8)) & 0x10000FFu;      // byte    at 0         and bit 24
+  return (x | (x >> 16)) & 0x1FFu;
 }
 
 // kinds (34-bit mask) of which the seat owns four, concealed and melds together

@@ -30,7 +30,13 @@ MJ_HD uint64_t &DK(Ctx &c, int s) { return c.e.dk[(int64_t)s * c.e.hs]; }
 MJ_HD uint64_t &MASK(Ctx &c, int s, int w) { return c.e.mask[(int64_t)(s * 2 + w) * c.e.hs]; }
 MJ_HD int32_t &SCORE(Ctx &c, int s) { return c.e.score[(int64_t)s * c.e.hs]; }
 MJ_HD int32_t &DELTA(Ctx &c, int s) { return c.e.delta[(int64_t)s * c.e.hs]; }
-MJ_HD uint8_t &WALL(Ctx &c, int i) { return c.e.wall[(int64_t)i * c.e.n]; }
+MJ_HD int wall_at(const Env &e, int i) { return (int)(e.wallw[(int64_t)(i >> 2) * e.n] >> (8 * (i & 3)) & 255u); }
+MJ_HD void wall_set(const Env &e, int i, int v)
+{
+  uint32_t &w = e.wallw[(int64_t)(i >> 2) * e.n];
+  w = (w & ~(255u << (8 * (i & 3)))) | (uint32_t)v << (8 * (i & 3));
+}
+MJ_HD int WALL(Ctx &c, int i) { return wall_at(c.e, i); }
 MJ_HD uint8_t &RIVER(Ctx &c, int s, int i) { return c.e.river[(int64_t)(s * 32 + i) * c.e.n]; }
 
 MJ_HD int swf(Ctx &c, int s, int pos, int bits) { return (int)sw_get(SW(c, s), pos, bits); }
@@ -140,21 +146,23 @@ MJ_HD void set_action(Mask2 &m, int a)
   if (a < 64) m.w0 |= bit; else m.w1 |= bit;
 }
 
-// discards available from the hand of seat s, restricted to the kinds in `allowed`
+// discards available from the hand of seat s, restricted to the kinds in `allowed`: the non-red discard of
+// kind k is action k, so the set of held kinds IS the low part of the mask; red fives are patched in
 MJ_HD void discard_bits(Ctx &c, int s, uint64_t allowed, Mask2 &m)
 {
   uint32_t sw = SW(c, s);
+  uint64_t held = 0;
+#pragma unroll
   for (int su = 0; su < 4; su++) {
     uint32_t hw = HW(c, s, su);
-    int nr = su == 3 ? 7 : 9, basek = su == 3 ? 27 : 9 * su;
-    for (int r = 0; r < nr; r++) {
-      int n = cnt3(hw, r), k = basek + r;
-      if (n == 0 || !(allowed >> k & 1)) continue;
-      bool red = su < 3 && r == 4 && (sw >> su & 1u);
-      if (n - (red ? 1 : 0) > 0) set_action(m, A_DISCARD + k);
-      if (red) set_action(m, A_DISCARD_RED + su);
+    held |= (uint64_t)squeeze9(fields_nonzero(hw)) << (9 * su);
+    if (su < 3 && (sw >> su & 1u)) {                       // the red five of this suit is in the hand
+      uint64_t five = kbit(9 * su + 4);
+      if (allowed & five) m.w0 |= 1ull << (A_DISCARD_RED + su);
+      if (cnt3(hw, 4) == 1) held &= ~five;                 // ... and it is the only five
     }
   }
+  m.w0 |= held & allowed;
 }
 
 // legal actions of the seat to move
@@ -239,7 +247,7 @@ MJ_HD void draw_live(Ctx &c, int s)
 MJ_HD void shuffle_wall(Ctx &c)
 {
   uint32_t serial = c.e.serial[0];
-  for (int i = 0; i < 136; i++) WALL(c, i) = (uint8_t)i;
+  for (int i = 0; i < 136; i++) wall_set(c.e, i, i);
   for (int j = 0; j < 34; j++) {
     uint32_t r[4];
     philox(serial, (uint32_t)j, 0, 0, c.R.seed, c.env_id, r);
@@ -248,21 +256,19 @@ MJ_HD void shuffle_wall(Ctx &c)
       int i = 4 * j + t;
       if (i >= 135) break;
       int k = i + (int)mulhi(r[t], (uint32_t)(136 - i));
-      uint8_t a = WALL(c, i), b = WALL(c, k);
-      WALL(c, i) = b; WALL(c, k) = a;
+      int a = WALL(c, i), b = WALL(c, k);
+      wall_set(c.e, i, b); wall_set(c.e, k, a);
     }
   }
 }
 
-// first half of a deal: per-kyoku state back to its start, 4 x 13 tiles and the dealer's first draw, read
-// from the wall copy at w[i * ws] (the same bytes as the environment's wall)
-MJ_HD void deal_tiles(Ctx &c, const uint8_t *w, int64_t ws)
+// a deal, part 1: every per-kyoku field back to its start (the final rank of the game is kept)
+MJ_HD void deal_reset(Ctx &c)
 {
   MJ_STAT(n_deal);
 #pragma unroll
   for (int i = 0; i < 16; i++) c.e.hand[(int64_t)i * c.e.hs] = 0;
   for (int s = 0; s < 4; s++) {
-    // everything per seat back to the start of a kyoku, the final rank of the game kept
     uint32_t keep = SW(c, s) & (3u << SW_RANK);
     SW(c, s) = keep | (255u << SW_RIDX) | (1u << SW_FIRST);
     MELDW(c, s) = 0;
@@ -273,25 +279,26 @@ MJ_HD void deal_tiles(Ctx &c, const uint8_t *w, int64_t ws)
   c.g.last_discard = 255; c.g.last_discarder = 255; c.g.kakan_tile = 255;
   c.g.kuikae0 = c.g.kuikae1 = 255;
   c.g.first_wind = 255; c.g.same_wind_cnt = 0;
+  c.g.cur = (uint8_t)dealer_of(c);
+  c.g.draw_ptr = 52; c.g.live_left = 70; c.g.drawn = 255;
+}
+// part 2: 4 x 13 tiles from the wall; the seat with seat wind j takes wall[13j .. 13j+12]
+MJ_HD void deal_hands(Ctx &c)
+{
   int dealer = dealer_of(c);
   for (int j = 0; j < 4; j++) {
     int s = (dealer + j) & 3;
-    for (int t = 0; t < 13; t++) take_tile(c, s, w[(int64_t)(13 * j + t) * ws]);
+    for (int t = 0; t < 13; t++) take_tile(c, s, WALL(c, 13 * j + t));
   }
-  c.g.cur = (uint8_t)dealer;
-  c.g.draw_ptr = 53; c.g.live_left = 69;
-  c.g.drawn = (uint8_t)take_tile(c, dealer, w[52 * ws]);
 }
-// second half: the waits of the four 13-tile hands (the dealer's without the drawn tile); the dealer's mask
-// is left to step_finish
-MJ_HD void deal_finish(Ctx &c)
+// part 3: the waits of the four 13-tile hands;  part 4: the dealer draws (the mask follows in step_finish)
+MJ_HD void deal_waits(Ctx &c)
 {
-  int dealer = dealer_of(c), dk = code_kind(c.g.drawn);
-  for (int s = 0; s < 4; s++) {
-    if (s == dealer) hand_add(c, s, dk, -1);
-    refresh_waits(c, s);
-    if (s == dealer) hand_add(c, s, dk, 1);
-  }
+  for (int s = 0; s < 4; s++) refresh_waits(c, s);
+}
+MJ_HD void deal_first_draw(Ctx &c)
+{
+  draw_live(c, dealer_of(c));
   c.need_deal = false;
   c.need_turn = true;
 }
@@ -304,8 +311,10 @@ MJ_HD void step_finish(Ctx &c)
 MJ_HD void deal(Ctx &c, bool reshuffle)
 {
   if (reshuffle) shuffle_wall(c);
-  deal_tiles(c, c.e.wall, c.e.n);
-  deal_finish(c);
+  deal_reset(c);
+  deal_hands(c);
+  deal_waits(c);
+  deal_first_draw(c);
   step_finish(c);
 }
 

@@ -38,18 +38,18 @@ struct DevTables {
   int probe_bytes;                       // multiple of 16
 };
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
-constexpr int kDealSlotBytes = 272;      // per wave: 136 wall bytes + 136 swap targets
 constexpr int kLutBytes = 64;            // the block's copy of the table pointers
+constexpr int kRefillEvery = 32;         // steps between refills of the walls made ahead of time
 
 // A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
 // occupies 2x or 4x as many wavefronts, which lets a SIMD overlap the LDS / memory latency of one wavefront
 // with the instructions of another and shrinks the set of divergent paths per wavefront.  The step is bound by
 // dependent-access latency, not by lane count, so small batches run faster that way.
-// LDS of a step kernel: probe tables | hot u64 arrays | hot u32 arrays | one deal slot per wave
+// LDS of a step kernel: probe tables | hot u64 arrays | hot u32 arrays | table pointers | 136 wall bytes per env
 __host__ __device__ inline int envs_per_block(int lpw) { return (kBlock / 64) * lpw; }
 __host__ __device__ inline size_t step_lds_bytes(int probe_bytes, int lpw)
 {
-  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * kHotBytesPerEnv + (size_t)(kBlock / 64) * kDealSlotBytes + kLutBytes;
+  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * (kHotBytesPerEnv + 136) + kLutBytes;
 }
 
 static_assert(sizeof(Lut) <= kLutBytes, "table pointer block");
@@ -57,7 +57,7 @@ struct BlockMem {
   const Lut *L;                          // in LDS
   uint64_t *hq;                          // [kHotU64][envs per block]
   uint32_t *hw;                          // [kHotU32][envs per block]
-  uint8_t *slot;                         // this wave's deal slot
+  uint8_t *col;                          // this lane's column of the [136][envs per block] shuffle area
   int epb, idx;                          // envs per block; this lane's env slot in the block
   bool lane_on;                          // this lane carries an environment
 };
@@ -75,14 +75,14 @@ __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds
   m.lane_on = (threadIdx.x & 63) < LPW;
   m.hq = (uint64_t *)(lds + T.probe_bytes);
   m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)m.epb * 8 * kHotU64);
-  m.slot = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + (threadIdx.x >> 6) * kDealSlotBytes;
-  Lut *L = (Lut *)(lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + (kBlock / 64) * kDealSlotBytes);
+  Lut *L = (Lut *)(lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv);
   if (threadIdx.x == 0) {
     L->rowid = lds;
     L->bitmap = (const uint32_t *)(lds + kRowIdBytes);
     L->base = T.base; L->rowrank = T.rowrank; L->keyinfo = T.keyinfo; L->recs = T.recs;
   }
   m.L = L;
+  m.col = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + kLutBytes + m.idx;
   __syncthreads();
   return m;
 }
@@ -112,58 +112,184 @@ __device__ __forceinline__ void store_hot(const BlockMem &m, void *state, int64_
   for (int f = 0; f < kHotU32; f++) gw[(int64_t)f * B] = m.hw[f * m.epb + m.idx];
 }
 
-// lanes of one wavefront exchange data through LDS: order the accesses
-__device__ __forceinline__ void wave_sync()
-{
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
 // Deal for every lane of the wavefront that needs one.  All 64 lanes must call this together.
-// Per environment in turn: 34 lanes run Philox and turn the words into swap targets, the owner lane applies
-// the 135 swaps on the wall in LDS, copies the wall to HBM and takes its tiles from LDS.
-// Afterwards the owners compute waits and masks side by side.
-__device__ __forceinline__ void deal_wave(Ctx &c, bool need, uint8_t *slot, void *state, int64_t B, int64_t b)
+// One environment at a time, with values that are uniform over the wavefront:
+//   - 34 lanes run Philox (counter word 1 = lane) and turn their four words into four swap targets;
+//   - the wall lives in ONE vector register, four tile ids per lane in lanes 0..33; the 135 swaps of the
+//     Fisher-Yates pass are readlane / select pairs on it (no memory in the loop);
+//   - lanes 0..33 store their word of the wall to HBM, the 4 x 13 tiles are accumulated into sixteen packed
+//     hand words with scalar arithmetic, lanes 0..3 compute the waits of the four hands with one call;
+//   - the owner lane writes the results into its state and takes the dealer's first draw.
+__device__ __forceinline__ uint32_t set_byte(uint32_t w, int pos, uint32_t v) { return (w & ~(255u << (8 * pos))) | v << (8 * pos); }
+
+__device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_t B, int64_t b)
 {
   const int lane = threadIdx.x & 63;
-  uint8_t *wl = slot, *kk = slot + 136;
   unsigned long long pending = __ballot(need ? 1 : 0);
   const uint32_t my_serial = need ? c.e.serial[0] : 0u;
+  const uint32_t my_kyoku = c.g.kyoku;
+  const uint32_t b_lo = (uint32_t)b, b_hi = (uint32_t)((uint64_t)b >> 32);
+  const bool red_rules = (c.R.flags & F_RED) != 0;
   while (pending) {
     const int src = __builtin_ctzll(pending);
     pending &= pending - 1;
-    const uint32_t serial = __shfl(my_serial, src), env_id = __shfl(c.env_id, src);
+    const uint32_t serial = __builtin_amdgcn_readlane(my_serial, src);
+    const uint32_t env_id = __builtin_amdgcn_readlane(c.env_id, src);
+    const int dealer = (int)(__builtin_amdgcn_readlane(my_kyoku, src) & 3u);
+    const int64_t bsrc = (int64_t)(((uint64_t)__builtin_amdgcn_readlane(b_hi, src) << 32) | __builtin_amdgcn_readlane(b_lo, src));
+    // swap targets: lane j holds k[4j .. 4j+3]; position 135 is never swapped (target = itself)
+    uint32_t kv0 = 0, kv1 = 0, kv2 = 0, kv3 = 0;
     if (lane < 34) {
       uint32_t r[4];
       philox(serial, (uint32_t)lane, 0, 0, c.R.seed, env_id, r);
+      const int i = 4 * lane;
+      kv0 = i + mulhi(r[0], (uint32_t)(136 - i));
+      kv1 = i + 1 + mulhi(r[1], (uint32_t)(135 - i));
+      kv2 = i + 2 + mulhi(r[2], (uint32_t)(134 - i));
+      kv3 = i + 3 < 135 ? i + 3 + mulhi(r[3], (uint32_t)(133 - i)) : (uint32_t)(i + 3);
+    }
+    // the wall: ids 4*lane .. 4*lane+3 in the four bytes of lane's word
+    uint32_t wv = lane < 34 ? (uint32_t)(4 * lane) * 0x01010101u + 0x03020100u : 0u;
+    for (int j = 0; j < 34; j++) {
 #pragma unroll
       for (int t = 0; t < 4; t++) {
-        int i = 4 * lane + t;
-        if (i < 135) kk[i] = (uint8_t)(i + (int)mulhi(r[t], (uint32_t)(136 - i)));
+        const uint32_t kvt = t == 0 ? kv0 : t == 1 ? kv1 : t == 2 ? kv2 : kv3;
+        const int k = (int)__builtin_amdgcn_readlane(kvt, j);
+        const int lk = k >> 2, pk = k & 3;
+        const uint32_t wa = __builtin_amdgcn_readlane(wv, j);
+        const uint32_t wb = __builtin_amdgcn_readlane(wv, lk);
+        const uint32_t x = (wa >> (8 * t)) & 255u, y = (wb >> (8 * pk)) & 255u;
+        if (lk == j) {
+          wv = lane == j ? set_byte(set_byte(wa, t, y), pk, x) : wv;
+        } else {
+          wv = lane == j ? set_byte(wa, t, y) : lane == lk ? set_byte(wb, pk, x) : wv;
+        }
       }
     }
-    wl[lane] = (uint8_t)lane;
-    wl[lane + 64] = (uint8_t)(lane + 64);
-    if (lane < 8) wl[lane + 128] = (uint8_t)(lane + 128);
-    wave_sync();
-    if (lane == src) {
-      for (int i = 0; i < 135; i++) {
-        int k = kk[i];
-        uint8_t x = wl[i], y = wl[k];
-        wl[i] = y; wl[k] = x;
+    // the wall goes to HBM, one word per lane
+    if (lane < 34) (state_u32(state, B) + (int64_t)(kHotU32 + 11) * B + bsrc)[(int64_t)lane * B] = wv;
+    // 4 x 13 tiles -> packed hand words (index j = seat wind), all in uniform values
+    uint32_t hw[4][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    uint32_t red[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+#pragma unroll
+      for (int t = 0; t < 13; t++) {
+        const int i = 13 * j + t;
+        const uint32_t id = (__builtin_amdgcn_readlane(wv, i >> 2) >> (8 * (i & 3))) & 255u;
+        const int kind = (int)(id >> 2), su = suit_of(kind);
+        const uint32_t inc = 1u << (3 * rank_of(kind, su));
+#pragma unroll
+        for (int q = 0; q < 4; q++) hw[j][q] += su == q ? inc : 0u;
+        if (red_rules && (id == 16u || id == 52u || id == 88u)) red[j] |= 1u << su;
       }
     }
-    wave_sync();
-    if (lane == src) {
-      // the owner itself copies the wall to HBM: it is the lane that later draws from it, and a lane's own
-      // stores are ordered before its own loads (stores of other lanes could be hidden by a stale L1 line)
-      for (int i = 0; i < 136; i++) WALL(c, i) = wl[i];
-      deal_tiles(c, wl, 1);
+    // waits of the four 13-tile hands: lane L < 4 takes seat L, whose seat wind is (L - dealer) & 3
+    uint64_t wt = 0;
+    if (lane < 4) {
+      const int j = (lane - dealer) & 3;
+      const uint32_t h0 = pick4(hw[0][0], hw[1][0], hw[2][0], hw[3][0], j), h1 = pick4(hw[0][1], hw[1][1], hw[2][1], hw[3][1], j);
+      const uint32_t h2 = pick4(hw[0][2], hw[1][2], hw[2][2], hw[3][2], j), h3 = pick4(hw[0][3], hw[1][3], hw[2][3], hw[3][3], j);
+      wt = waits_of(c.L, h0, h1, h2, h3, 0, 0);
     }
-    wave_sync();
+    const uint32_t wt_lo = (uint32_t)wt, wt_hi = (uint32_t)(wt >> 32);
+    uint64_t w4[4];
+#pragma unroll
+    for (int s = 0; s < 4; s++)
+      w4[s] = (uint64_t)__builtin_amdgcn_readlane(wt_hi, s) << 32 | __builtin_amdgcn_readlane(wt_lo, s);
+    const uint32_t first_id = (__builtin_amdgcn_readlane(wv, 13) >> 0) & 255u;        // wall[52]
+    if (lane == src) {
+      deal_reset(c);
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const int s = (dealer + j) & 3;
+#pragma unroll
+        for (int q = 0; q < 4; q++) HW(c, s, q) = hw[j][q];
+        SW(c, s) |= red[j];
+      }
+#pragma unroll
+      for (int s = 0; s < 4; s++) WAITS(c, s) = w4[s];
+      // the dealer's first draw (wall[52]) without going through HBM
+      c.g.draw_ptr = 53; c.g.live_left = 69; c.g.rinshan = 0;
+      c.g.drawn = (uint8_t)take_tile(c, dealer, (int)first_id);
+      c.need_deal = false;
+      c.need_turn = true;
+    }
   }
-  if (need) deal_finish(c);
+}
+
+// Walls are made ahead of time: the wall of a deal depends only on (seed, env id, kyoku_serial), so each lane
+// shuffles the wall of its NEXT deal every kRefillEvery steps, all lanes side by side, and a deal then only
+// copies 34 words.  (A deal that finds no wall ready, e.g. the second deal inside one interval, falls back to
+// the wave-cooperative shuffle above.)  Plain per-lane Fisher-Yates on a byte column in LDS.
+__device__ __forceinline__ void refill_next_wall(Ctx &c, uint8_t *col, int stride, uint32_t target_serial)
+{
+  for (int i = 0; i < 136; i++) col[i * stride] = (uint8_t)i;
+  for (int j = 0; j < 34; j++) {
+    uint32_t r[4];
+    philox(target_serial, (uint32_t)j, 0, 0, c.R.seed, c.env_id, r);
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      const int i = 4 * j + t;
+      if (i >= 135) break;
+      const int k = i + (int)mulhi(r[t], (uint32_t)(136 - i));
+      const uint8_t x = col[i * stride], y = col[k * stride];
+      col[i * stride] = y; col[k * stride] = x;
+    }
+  }
+  for (int j = 0; j < 34; j++) {
+    const uint32_t w = (uint32_t)col[(4 * j) * stride] | (uint32_t)col[(4 * j + 1) * stride] << 8 |
+                       (uint32_t)col[(4 * j + 2) * stride] << 16 | (uint32_t)col[(4 * j + 3) * stride] << 24;
+    c.e.nextw[(int64_t)j * c.e.n] = w;
+  }
+  c.e.nserial[0] = target_serial;
+}
+
+// the deal of a lane whose next wall is ready: copy it, take the tiles out of the registers
+__device__ __forceinline__ void deal_from_next(Ctx &c)
+{
+  uint32_t w[14];                       // the 52 dealt tiles and the first draw; the rest is only copied
+#pragma unroll
+  for (int j = 0; j < 14; j++) w[j] = c.e.nextw[(int64_t)j * c.e.n];
+#pragma unroll
+  for (int j = 0; j < 14; j++) c.e.wallw[(int64_t)j * c.e.n] = w[j];
+#pragma unroll 4
+  for (int j = 14; j < 34; j++) c.e.wallw[(int64_t)j * c.e.n] = c.e.nextw[(int64_t)j * c.e.n];
+  deal_reset(c);
+  const int dealer = dealer_of(c);
+  const bool red_rules = (c.R.flags & F_RED) != 0;
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    uint32_t hw[4] = {0, 0, 0, 0}, red = 0;
+#pragma unroll
+    for (int t = 0; t < 13; t++) {
+      const int i = 13 * j + t;
+      const uint32_t id = (w[i >> 2] >> (8 * (i & 3))) & 255u;
+      const int kind = (int)(id >> 2), su = suit_of(kind);
+      const uint32_t inc = 1u << (3 * rank_of(kind, su));
+#pragma unroll
+      for (int q = 0; q < 4; q++) hw[q] += su == q ? inc : 0u;
+      if (red_rules && (id == 16u || id == 52u || id == 88u)) red |= 1u << su;
+    }
+    const int s = (dealer + j) & 3;
+#pragma unroll
+    for (int q = 0; q < 4; q++) HW(c, s, q) = hw[q];
+    SW(c, s) |= red;
+  }
+  deal_waits(c);
+  c.g.draw_ptr = 53; c.g.live_left = 69; c.g.rinshan = 0;
+  c.g.drawn = (uint8_t)take_tile(c, dealer, (int)(w[13] & 255u));
+  c.need_deal = false;
+  c.need_turn = true;
+}
+
+// every deal of a step: the ready ones lane by lane, the others through the wave-cooperative shuffle
+__device__ __forceinline__ void deal_stage(Ctx &c, bool active, void *state, int64_t B, int64_t b)
+{
+  const bool need = active && c.need_deal;
+  const bool ready = need && c.e.nserial[0] == c.e.serial[0];
+  if (ready) deal_from_next(c);
+  deal_wave(c, need && !ready, state, B, b);
 }
 
 __device__ __forceinline__ void reset_env(Ctx &c, bool first)
@@ -202,18 +328,21 @@ __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Ru
   c.need_deal = false; c.need_turn = false;
   bool touched = false;
   if (active) {
-    if (mode == 0) { reset_env(c, true); touched = true; }
-    else {
+    if (mode == 0) {
+      reset_env(c, true); touched = true;
+      refill_next_wall(c, m.col, m.epb, 0);          // every lane deals now: make the first walls side by side
+    } else {
       load_glob(c.e, c.g);
       if (c.g.terminated) { load_hot(m, state, B, b); reset_env(c, false); touched = true; }
     }
   }
-  deal_wave(c, active && c.need_deal, m.slot, state, B, b);
+  deal_stage(c, active, state, B, b);
   if (touched) { step_finish(c); store_hot(m, state, B, b); store_glob(c.e, c.g); }
+  if (mode == 0 && active) refill_next_wall(c, m.col, m.epb, 1);
 }
 
 template <int LPW>
-__global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions)
+__global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions, int refill)
 {
   extern __shared__ __align__(16) uint8_t lds[];
   BlockMem m = stage_block<LPW>(T, lds);
@@ -225,9 +354,10 @@ __global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R
   if (active) {
     load_hot(m, state, B, b);
     load_glob(c.e, c.g);
+    if (refill && c.e.nserial[0] != c.e.serial[0] + 1) refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
     step_env(c, ((const uint32_t *)actions)[b]);
   }
-  deal_wave(c, active && c.need_deal, m.slot, state, B, b);
+  deal_stage(c, active, state, B, b);
   if (active) { step_finish(c); store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
@@ -259,10 +389,12 @@ __global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, R
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
   for (int t = 0; t < n_steps; t++) {
     if (active) {
+      if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
+        refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
       step_env(c, sample_actors(c, step0 + t));
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }
-    deal_wave(c, active && c.need_deal, m.slot, state, B, b);
+    deal_stage(c, active, state, B, b);
     if (active) step_finish(c);
   }
   if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
@@ -279,7 +411,7 @@ __global__ void __launch_bounds__(kBlock) k_deal_from_wall(void *state, int64_t 
   c.e = make_env(state, B, b); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false;
   load_glob(c.e, c.g);
-  for (int i = 0; i < 136; i++) WALL(c, i) = wall[i];
+  for (int i = 0; i < 136; i++) wall_set(c.e, i, wall[i]);
   deal(c, false);
   store_glob(c.e, c.g);
 }
@@ -608,7 +740,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
 int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
 {
   if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
-  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions);
+  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kRefillEvery == 0));
   h->step++;
   return check(hipGetLastError());
 }

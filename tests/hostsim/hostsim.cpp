@@ -133,7 +133,7 @@ void hs_deal_from_wall(Sim *h, int64_t b, const uint8_t *wall)
 {
   Ctx c = ctx_of(h, b);
   load_glob(c.e, c.g);
-  for (int i = 0; i < 136; i++) WALL(c, i) = wall[i];
+  for (int i = 0; i < 136; i++) wall_set(c.e, i, wall[i]);
   deal(c, false);
   store_glob(c.e, c.g);
 }
