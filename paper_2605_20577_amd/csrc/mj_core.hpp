@@ -216,9 +216,25 @@ MJ_HD uint32_t suit_addmask(const Lut *Lp, int su, uint32_t w)
   const Lut &L = *Lp;
   uint32_t m = 0;
   if (su < 3) {
+    // nine probes whose keys differ from the key of w by one power of five: adding to ranks 1..5 changes the
+    // prefix (five row reads), adding to ranks 6..9 keeps the row of w and moves along it.  All row reads are
+    // issued before the first bitmap read, so the LDS latency is paid twice, not eighteen times.
+    const uint32_t p = prefix5(w), sfx = suffix5(w);
+    const uint32_t full = (w >> 2) & O111;                 // fields that already hold four
+    uint32_t row[6];
+    row[5] = L.rowid[p];
+    uint32_t pw = 1;
 #pragma unroll
-    for (int r = 0; r < 9; r++)
-      if (cnt3(w, r) < 4 && lut_valid(L, w + (1u << (3 * r)))) m |= 1u << r;
+    for (int r = 0; r < 5; r++) { row[r] = L.rowid[p + ((full >> (3 * r) & 1u) ? 0u : pw)]; pw *= 5; }   // full field: no probe
+    pw = 1;
+#pragma unroll
+    for (int r = 0; r < 9; r++) {
+      const uint32_t sr = (r < 5 || (full >> (3 * r) & 1u)) ? sfx : sfx + pw;
+      if (r >= 5) pw *= 5;
+      const uint32_t bit = (L.bitmap[row[r < 5 ? r : 5] * 20 + (sr >> 5)] >> (sr & 31)) & 1u;
+      m |= bit << r;
+    }
+    m &= ~squeeze9(full);
   } else {
     // honors: a single becomes the pair, a pair becomes a triplet; the other counts must already fit
     uint32_t one = fields_eq(w, 1), two = fields_eq(w, 2), four = (w >> 2) & O111;

@@ -11,6 +11,13 @@
 
 namespace mj {
 
+// -DMJ_PROFILE: cycles per stage, accumulated per lane, printed by k_rollout (never in the shipped library)
+#ifdef MJ_PROFILE
+#define MJ_TICK(c, i) do { long long now_ = clock64(); (c).t[i] += now_ - (c).t0; (c).t0 = now_; } while (0)
+#else
+#define MJ_TICK(c, i) ((void)0)
+#endif
+
 struct Ctx {
   Env e;
   const Lut *L;
@@ -19,6 +26,9 @@ struct Ctx {
   uint32_t env_id;
   bool need_deal;      // set when a step ends in "deal the next kyoku": the caller shuffles and deals
   bool need_turn;      // the seat to move still needs its legal mask (step_finish)
+#ifdef MJ_PROFILE
+  long long t[12], t0;  // cycle counters per stage (profiling builds only)
+#endif
 };
 
 // ------------------------------------------------------------- field access
@@ -132,12 +142,6 @@ MJ_HD void mark_furiten(Ctx &c, int s)
   SW(c, s) |= sw_get(SW(c, s), SW_RIICHI, 2) ? (1u << SW_FRIICHI) : (1u << SW_FTEMP);
 }
 
-// kinds whose discard leaves the 14-tile hand of seat s tenpai
-MJ_HD uint64_t tenpai_discards(Ctx &c, int s)
-{
-  return tenpai_discards_of(c.L, HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3), MELDW(c, s), swf(c, s, SW_NMELD, 3));
-}
-
 // a legal-action mask in two registers (no indexed array, so it never lands in scratch memory)
 struct Mask2 { uint64_t w0, w1; };
 MJ_HD void set_action(Mask2 &m, int a)
@@ -146,84 +150,85 @@ MJ_HD void set_action(Mask2 &m, int a)
   if (a < 64) m.w0 |= bit; else m.w1 |= bit;
 }
 
-// discards available from the hand of seat s, restricted to the kinds in `allowed`: the non-red discard of
-// kind k is action k, so the set of held kinds IS the low part of the mask; red fives are patched in
-MJ_HD void discard_bits(Ctx &c, int s, uint64_t allowed, Mask2 &m)
+// discards available from a hand (four suit words, red bits in sw), restricted to the kinds in `allowed`: the
+// non-red discard of kind k is action k, so the set of held kinds IS the low part of the mask; red fives are
+// patched in
+MJ_HD void discard_bits(const uint32_t h[4], uint32_t sw, uint64_t allowed, Mask2 &m)
 {
-  uint32_t sw = SW(c, s);
   uint64_t held = 0;
 #pragma unroll
   for (int su = 0; su < 4; su++) {
-    uint32_t hw = HW(c, s, su);
-    held |= (uint64_t)squeeze9(fields_nonzero(hw)) << (9 * su);
+    held |= (uint64_t)squeeze9(fields_nonzero(h[su])) << (9 * su);
     if (su < 3 && (sw >> su & 1u)) {                       // the red five of this suit is in the hand
       uint64_t five = kbit(9 * su + 4);
       if (allowed & five) m.w0 |= 1ull << (A_DISCARD_RED + su);
-      if (cnt3(hw, 4) == 1) held &= ~five;                 // ... and it is the only five
+      if (cnt3(h[su], 4) == 1) held &= ~five;              // ... and it is the only five
     }
   }
   m.w0 |= held & allowed;
 }
 
-// legal actions of the seat to move
+// legal actions of the seat to move; the seat's words are read once and handed to the helpers
 MJ_HD void turn_mask(Ctx &c)
 {
   MJ_STAT(n_turn);
-  int s = c.g.cur;
+  const int s = c.g.cur;
   Mask2 m = {0, 0};
   clear_masks(c);
   c.g.phase = PH_TURN;
   c.g.actor_mask = (uint8_t)(1 << s);
-  int drawn_k = c.g.drawn == 255 ? -1 : code_kind(c.g.drawn);
-  uint32_t sw = SW(c, s);
-  int riichi = (int)sw_get(sw, SW_RIICHI, 2);
+  const int drawn_k = c.g.drawn == 255 ? -1 : code_kind(c.g.drawn);
+  const uint32_t sw = SW(c, s);
+  const uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
+  const uint64_t mw = MELDW(c, s), waits = WAITS(c, s);
+  const int riichi = (int)sw_get(sw, SW_RIICHI, 2), n_meld = (int)sw_get(sw, SW_NMELD, 3);
 
   if (c.g.riichi_pending) {
-    discard_bits(c, s, tenpai_discards(c, s), m);
+    discard_bits(h, sw, tenpai_discards_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld), m);
   } else {
-    bool can_tsumo = false;
-    if (drawn_k >= 0 && (WAITS(c, s) >> drawn_k & 1)) {
+    if (drawn_k >= 0 && (waits >> drawn_k & 1)) {
       HandOut r;
       eval_seat(c, s, drawn_k, true, false, r);
-      can_tsumo = r.yaku_ok;
+      if (r.yaku_ok) set_action(m, A_TSUMO);
     }
-    if (can_tsumo) set_action(m, A_TSUMO);
-    bool kan_ok = drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
+    const bool kan_ok = drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
     if (riichi) {
       if (code_red(c.g.drawn)) set_action(m, A_DISCARD_RED + drawn_k / 9);
       else set_action(m, A_DISCARD + drawn_k);
-      if (kan_ok && count_of(c, s, drawn_k) == 4) {
+      if (kan_ok && hand_count(h, drawn_k) == 4) {
         // a concealed kan is allowed in riichi only when it leaves the waits as they were
-        int su = suit_of(drawn_k), n_meld = (int)sw_get(sw, SW_NMELD, 3);
-        uint32_t four = 4u << (3 * rank_of(drawn_k, su));
-        uint32_t h0 = HW(c, s, 0) - (su == 0 ? four : 0u), h1 = HW(c, s, 1) - (su == 1 ? four : 0u);
-        uint32_t h2 = HW(c, s, 2) - (su == 2 ? four : 0u), h3 = HW(c, s, 3) - (su == 3 ? four : 0u);
-        uint64_t mw = MELDW(c, s) | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
-        if (waits_of(c.L, h0, h1, h2, h3, mw, n_meld + 1) == WAITS(c, s)) set_action(m, A_KAN + drawn_k);
+        const int su = suit_of(drawn_k);
+        const uint32_t four = 4u << (3 * rank_of(drawn_k, su));
+        const uint64_t mw2 = mw | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
+        if (waits_of(c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
+                     h[3] - (su == 3 ? four : 0u), mw2, n_meld + 1) == waits)
+          set_action(m, A_KAN + drawn_k);
       }
     } else {
       uint64_t allowed = K_ALL;
       if (c.g.kuikae0 != 255) allowed &= ~kbit(c.g.kuikae0);
       if (c.g.kuikae1 != 255) allowed &= ~kbit(c.g.kuikae1);
-      discard_bits(c, s, allowed, m);
-      int n_meld = (int)sw_get(sw, SW_NMELD, 3);
-      uint64_t mw = MELDW(c, s);
-      if (kan_ok) {
-        for (int su = 0; su < 4; su++) {
-          uint32_t four = fields_eq(HW(c, s, su), 4);
-          while (four) { int b = ctz64(four); four &= four - 1; set_action(m, A_KAN + (su == 3 ? 27 : 9 * su) + b / 3); }
-        }
-        for (int j = 0; j < n_meld; j++) {
-          uint32_t ml = meld_at(mw, j);
-          if (m_type(ml) == MT_PON && count_of(c, s, m_kind(ml)) >= 1) set_action(m, A_KAN + m_kind(ml));
-        }
+      discard_bits(h, sw, allowed, m);
+      bool menzen = true;
+      uint64_t kans = 0;                                    // kinds that may be declared as a kan
+#pragma unroll
+      for (int su = 0; su < 4; su++) kans |= (uint64_t)squeeze9(fields_eq(h[su], 4)) << (9 * su);
+      for (int j = 0; j < n_meld; j++) {
+        const uint32_t ml = meld_at(mw, j);
+        if (m_type(ml) != MT_ANKAN) menzen = false;
+        if (m_type(ml) == MT_PON && hand_count(h, m_kind(ml)) >= 1) kans |= kbit(m_kind(ml));
       }
-      if (drawn_k >= 0 && menzen_of(c, s) && SCORE(c, s) >= 1000 && c.g.live_left >= 4) {
-        if (tenpai_discards(c, s)) set_action(m, A_RIICHI);
+      if (kan_ok) {                                         // KAN k is action 37 + k: bits 37..70
+        m.w0 |= kans << A_KAN;
+        m.w1 |= kans >> (64 - A_KAN);
+      }
+      if (drawn_k >= 0 && menzen && SCORE(c, s) >= 1000 && c.g.live_left >= 4) {
+        if (tenpai_discards_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld)) set_action(m, A_RIICHI);
       }
       if ((c.R.flags & F_ABORT) && (sw >> SW_FIRST & 1) && drawn_k >= 0) {
         uint64_t present = 0;
-        for (int su = 0; su < 4; su++) present |= (uint64_t)squeeze9(fields_nonzero(HW(c, s, su))) << (9 * su);
+#pragma unroll
+        for (int su = 0; su < 4; su++) present |= (uint64_t)squeeze9(fields_nonzero(h[su])) << (9 * su);
         if (popc64(present & K_YAOCHU) >= 9) set_action(m, A_KYUUSHU);
       }
     }
@@ -669,6 +674,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       return;
     }
   }
+  MJ_TICK(c, 1);
   // stage 1: apply
   int waits_seat = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
   bool respond = false, rob = false, advance = false, kan_fin = false, win_tsumo = false, win_rob = false;
@@ -713,13 +719,16 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
     }
   }
   clear_masks(c);
+  MJ_TICK(c, 2);
   // stage 2: the seat whose concealed hand is back to 13 - 3 * melds tiles gets its waits refreshed
   if (waits_seat >= 0) refresh_waits(c, waits_seat);
+  MJ_TICK(c, 3);
   // stage 3: responses of the other seats
   if (respond || rob) {
     int from = respond ? c.g.last_discarder : c.g.cur;
     int code = respond ? c.g.last_discard : c.g.kakan_tile;
     int any = 0;
+#pragma unroll
     for (int j = 1; j < 4; j++) {
       int o = (from + j) & 3;
       Mask2 m = {0, 0};
@@ -735,12 +744,14 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       if (!end_abort) advance = true;
     } else kan_fin = true;
   }
+  MJ_TICK(c, 4);
   bool exhaust = false;
   if (advance && c.g.live_left == 0) { exhaust = true; advance = false; }
   // stage 4: the kyoku ends
   if (win_mask) win(c, win_mask, win_tsumo, win_loser, win_tile, win_rob);
   else if (end_abort) abortive_draw(c, end_abort);
   else if (exhaust) exhaustive_draw(c);
+  MJ_TICK(c, 5);
   // stage 5: draws
   if (advance) { draw_live(c, (c.g.last_discarder + 1) & 3); c.need_turn = true; }
   if (kan_fin) { kan_draw(c); c.need_turn = true; }

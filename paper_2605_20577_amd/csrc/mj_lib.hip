@@ -387,16 +387,34 @@ __global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, R
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false;
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
+#ifdef MJ_PROFILE
+  for (int i = 0; i < 12; i++) c.t[i] = 0;
+  c.t0 = clock64();
+#endif
   for (int t = 0; t < n_steps; t++) {
+    uint32_t acts = 0;
     if (active) {
       if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
         refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
-      step_env(c, sample_actors(c, step0 + t));
+      MJ_TICK(c, 10);
+      acts = sample_actors(c, step0 + t);
+      MJ_TICK(c, 0);
+      step_env(c, acts);
+      MJ_TICK(c, 6);
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }
+    MJ_TICK(c, 7);
     deal_stage(c, active, state, B, b);
+    MJ_TICK(c, 8);
     if (active) step_finish(c);
+    MJ_TICK(c, 9);
   }
+#ifdef MJ_PROFILE
+  if (blockIdx.x == 7 && threadIdx.x == 0 && n_steps == 128)
+    printf("PROF/step: refill %lld sample %lld | check %lld apply %lld waits %lld respond %lld end %lld draw %lld | reset %lld deal %lld mask %lld\n",
+           c.t[10] / 128, c.t[0] / 128, c.t[1] / 128, c.t[2] / 128, c.t[3] / 128, c.t[4] / 128, c.t[5] / 128, c.t[6] / 128,
+           c.t[7] / 128, c.t[8] / 128, c.t[9] / 128);
+#endif
   if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
