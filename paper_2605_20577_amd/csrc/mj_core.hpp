@@ -81,6 +81,8 @@ struct Env {
   uint32_t *glob;                                     // cold [7] (held in registers during a step)
   uint32_t *wallw;                                    // cold [34]: the 136 wall bytes, four per word
   uint32_t *nextw, *nserial;                          // cold [34] [1]: the wall of kyoku_serial + 1, made ahead of time
+  uint32_t *nexth, *nextred;                          // cold [16] [1]: its four dealt hands by seat wind, red fives
+  uint64_t *nextwaits;                                // cold [4]: their waits
   uint8_t *river;                                     // cold [128]
 };
 

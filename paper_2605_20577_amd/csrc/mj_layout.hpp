@@ -4,20 +4,20 @@
 // wavefront (64 consecutive environments) touch consecutive addresses.
 // Sections, in this order, each array of length B:
 //   u64 hot : discarded_kinds[4] waits[4] mask[8] meld[4]                   (20 arrays)
-//   u64 cold: yaku[4] result[4]                                             ( 8 arrays)
+//   u64 cold: yaku[4] result[4] next_waits[4]                               (12 arrays)
 //   u32 hot : score[4] delta[4] episode serial hand[16] seatw[4]            (30 arrays)
 //   u32 cold: gain[4] glob[7] wall[34] (136 tile ids, four per word)
-//             next_wall[34] next_serial (the wall of the next deal, made ahead)   (80 arrays)
+//             next_wall[34] next_serial next_hand[16] next_red (the next deal, made ahead) (97 arrays)
 //   u8  cold: river[128]                                                    (128 arrays)
-// = 792 bytes per environment, 280 of them hot.  The next wall is not part of the logical state: it is a pure
-// function of (seed, env id, kyoku_serial + 1), valid when next_serial says so.  The step kernels copy the
+// = 892 bytes per environment, 280 of them hot.  The "next" arrays are not part of the logical state: they are
+// a pure function of (seed, env id, kyoku_serial + 1), valid when next_serial says so.  The step kernels copy the
 // hot arrays of their block into LDS, run there, and copy them back.
 #pragma once
 #include "mj_core.hpp"
 
 namespace mj {
 
-constexpr int kHotU64 = 20, kColdU64 = 8, kHotU32 = 30, kColdU32 = 80, kU8Arrays = 128;
+constexpr int kHotU64 = 20, kColdU64 = 12, kHotU32 = 30, kColdU32 = 97, kU8Arrays = 128;
 constexpr int kU64Arrays = kHotU64 + kColdU64, kU32Arrays = kHotU32 + kColdU32;
 constexpr int64_t kBytesPerEnv = 8 * kU64Arrays + 4 * kU32Arrays + kU8Arrays;
 constexpr int kHotBytesPerEnv = 8 * kHotU64 + 4 * kHotU32;
@@ -45,7 +45,8 @@ MJ_HD Env make_env(void *state, int64_t B, int64_t b)
   e.yaku = q + (int64_t)kHotU64 * B; e.resw = q + (int64_t)(kHotU64 + 4) * B;
   e.gain = (int32_t *)(w + (int64_t)kHotU32 * B); e.glob = w + (int64_t)(kHotU32 + 4) * B;
   e.wallw = w + (int64_t)(kHotU32 + 11) * B; e.nextw = w + (int64_t)(kHotU32 + 45) * B;
-  e.nserial = w + (int64_t)(kHotU32 + 79) * B; e.river = y;
+  e.nserial = w + (int64_t)(kHotU32 + 79) * B; e.nexth = w + (int64_t)(kHotU32 + 80) * B;
+  e.nextred = w + (int64_t)(kHotU32 + 96) * B; e.nextwaits = q + (int64_t)(kHotU64 + 8) * B; e.river = y;
   return e;
 }
 

@@ -219,8 +219,8 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_
 }
 
 // Walls are made ahead of time: the wall of a deal depends only on (seed, env id, kyoku_serial), so each lane
-// shuffles the wall of its NEXT deal every kRefillEvery steps, all lanes side by side, and a deal then only
-// copies 34 words.  (A deal that finds no wall ready, e.g. the second deal inside one interval, falls back to
+// shuffles the wall of its NEXT deal every kRefillEvery steps, all lanes side by side, deals it into four
+// hands and computes their waits; the deal itself then only copies about 60 words.  (A deal that finds no wall ready, e.g. the second deal inside one interval, falls back to
 // the wave-cooperative shuffle above.)  Plain per-lane Fisher-Yates on a byte column in LDS.
 __device__ __forceinline__ void refill_next_wall(Ctx &c, uint8_t *col, int stride, uint32_t target_serial)
 {
@@ -242,43 +242,56 @@ __device__ __forceinline__ void refill_next_wall(Ctx &c, uint8_t *col, int strid
                        (uint32_t)col[(4 * j + 2) * stride] << 16 | (uint32_t)col[(4 * j + 3) * stride] << 24;
     c.e.nextw[(int64_t)j * c.e.n] = w;
   }
+  // the four dealt hands (by seat wind j) and their waits, so that the deal itself is only a copy.
+  // Field 3k of a 102-bit accumulator counts kind k: kinds 0..20 in `lo`, 21..33 in `hi`.
+  const bool red_rules = (c.R.flags & F_RED) != 0;
+  uint32_t reds = 0;
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    uint64_t lo = 0, hi = 0;
+#pragma unroll
+    for (int t = 0; t < 13; t++) {
+      const uint32_t id = col[(13 * j + t) * stride];
+      const uint32_t kind = id >> 2;
+      if (kind < 21) lo += 1ull << (3 * kind); else hi += 1ull << (3 * (kind - 21));
+      if (red_rules && (id == 16u || id == 52u || id == 88u)) reds |= 1u << (3 * j + kind / 9);
+    }
+    const uint32_t h0 = (uint32_t)lo & 0x7FFFFFFu, h1 = (uint32_t)(lo >> 27) & 0x7FFFFFFu;
+    const uint32_t h2 = (uint32_t)(lo >> 54) | ((uint32_t)hi & 0x3FFFFu) << 9, h3 = (uint32_t)(hi >> 18);
+    c.e.nexth[(int64_t)(4 * j) * c.e.n] = h0; c.e.nexth[(int64_t)(4 * j + 1) * c.e.n] = h1;
+    c.e.nexth[(int64_t)(4 * j + 2) * c.e.n] = h2; c.e.nexth[(int64_t)(4 * j + 3) * c.e.n] = h3;
+    c.e.nextwaits[(int64_t)j * c.e.n] = waits_of(c.L, h0, h1, h2, h3, 0, 0);
+  }
+  c.e.nextred[0] = reds;
   c.e.nserial[0] = target_serial;
 }
 
-// the deal of a lane whose next wall is ready: copy it, take the tiles out of the registers
+// the deal of a lane whose next deal is ready: copies only
 __device__ __forceinline__ void deal_from_next(Ctx &c)
 {
-  uint32_t w[14];                       // the 52 dealt tiles and the first draw; the rest is only copied
+  const int64_t n = c.e.n;
+  uint32_t hw[16];
+  uint64_t wt[4];
 #pragma unroll
-  for (int j = 0; j < 14; j++) w[j] = c.e.nextw[(int64_t)j * c.e.n];
+  for (int i = 0; i < 16; i++) hw[i] = c.e.nexth[(int64_t)i * n];
 #pragma unroll
-  for (int j = 0; j < 14; j++) c.e.wallw[(int64_t)j * c.e.n] = w[j];
-#pragma unroll 4
-  for (int j = 14; j < 34; j++) c.e.wallw[(int64_t)j * c.e.n] = c.e.nextw[(int64_t)j * c.e.n];
+  for (int j = 0; j < 4; j++) wt[j] = c.e.nextwaits[(int64_t)j * n];
+  const uint32_t reds = c.e.nextred[0];
+  const uint32_t first = c.e.nextw[13 * n] & 255u;          // wall[52]
+#pragma unroll 2
+  for (int j = 0; j < 34; j++) c.e.wallw[(int64_t)j * n] = c.e.nextw[(int64_t)j * n];
   deal_reset(c);
   const int dealer = dealer_of(c);
-  const bool red_rules = (c.R.flags & F_RED) != 0;
 #pragma unroll
   for (int j = 0; j < 4; j++) {
-    uint32_t hw[4] = {0, 0, 0, 0}, red = 0;
-#pragma unroll
-    for (int t = 0; t < 13; t++) {
-      const int i = 13 * j + t;
-      const uint32_t id = (w[i >> 2] >> (8 * (i & 3))) & 255u;
-      const int kind = (int)(id >> 2), su = suit_of(kind);
-      const uint32_t inc = 1u << (3 * rank_of(kind, su));
-#pragma unroll
-      for (int q = 0; q < 4; q++) hw[q] += su == q ? inc : 0u;
-      if (red_rules && (id == 16u || id == 52u || id == 88u)) red |= 1u << su;
-    }
     const int s = (dealer + j) & 3;
 #pragma unroll
-    for (int q = 0; q < 4; q++) HW(c, s, q) = hw[q];
-    SW(c, s) |= red;
+    for (int q = 0; q < 4; q++) HW(c, s, q) = hw[4 * j + q];
+    SW(c, s) |= (reds >> (3 * j)) & 7u;
+    WAITS(c, s) = wt[j];
   }
-  deal_waits(c);
   c.g.draw_ptr = 53; c.g.live_left = 69; c.g.rinshan = 0;
-  c.g.drawn = (uint8_t)take_tile(c, dealer, (int)(w[13] & 255u));
+  c.g.drawn = (uint8_t)take_tile(c, dealer, (int)first);
   c.need_deal = false;
   c.need_turn = true;
 }
