@@ -43,7 +43,7 @@ MJ_HD void export_env(const Env &e, MjEnvCanon &o)
     o.r_dora[s] = (uint8_t)(rw >> 24); o.r_ura[s] = (uint8_t)(rw >> 32); o.r_aka[s] = (uint8_t)(rw >> 40);
   }
   o.episode = e.episode[0]; o.kyoku_serial = e.serial[0];
-  for (int i = 0; i < 136; i++) o.wall[i] = (uint8_t)wall_at(e, i);
+  for (int i = 0; i < 136; i++) o.wall[i] = (uint8_t)wall_at(e, g.wall_sel, i);
   o.kyoku = g.kyoku; o.honba = g.honba; o.kyotaku = g.kyotaku; o.terminated = g.terminated;
   o.draw_ptr = g.draw_ptr; o.n_kan = g.n_kan; o.live_left = g.live_left; o.n_dora = g.n_dora;
   o.drawn = g.drawn; o.phase = g.phase; o.cur = g.cur; o.actor_mask = g.actor_mask;
@@ -86,6 +86,7 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
     e.seatw[s * n] = sw;
   }
   e.episode[0] = o.episode; e.serial[0] = o.kyoku_serial;
+  e.nserial[0] = 0xFFFFFFFFu;                      // whatever was made ahead of time is gone
   for (int i = 0; i < 34; i++)
     e.wallw[i * n] = (uint32_t)o.wall[4 * i] | (uint32_t)o.wall[4 * i + 1] << 8 | (uint32_t)o.wall[4 * i + 2] << 16 |
                      (uint32_t)o.wall[4 * i + 3] << 24;
@@ -96,7 +97,7 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
   g.last_discarder = o.last_discarder; g.kakan_tile = o.kakan_tile; g.kuikae0 = o.kuikae[0]; g.kuikae1 = o.kuikae[1];
   g.first_wind = o.first_wind; g.same_wind_cnt = o.same_wind_cnt; g.illegal_seat = o.illegal_seat;
   g.end_type = o.end_type; g.winners = o.winners; g.loser = o.loser; g.tenpai_mask = o.tenpai_mask;
-  g.pad0 = g.pad1 = 0;
+  g.wall_sel = 0; g.pad1 = 0;                      // the imported wall goes to buffer 0
   store_glob(e, g);
 }
 
@@ -172,7 +173,7 @@ MJ_HD void obs_env_masks(const Env &e, const Glob &g, uint32_t rule_flags, uint6
   uint32_t ind[4] = {0, 0, 0, 0};
   uint64_t redvis = seat_red;
   for (int i = 0; i < g.n_dora; i++) {
-    int id = wall_at(e, 126 + i);
+    int id = wall_at(e, g.wall_sel, 126 + i);
     bump(ind, id >> 2, 1);
     if ((rule_flags & F_RED) && (id == 16 || id == 52 || id == 88)) redvis |= kbit(id >> 2);
   }

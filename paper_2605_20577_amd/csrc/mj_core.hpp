@@ -79,8 +79,9 @@ struct Env {
   uint64_t *yaku, *resw;                              // cold [4] [4]
   int32_t *gain;                                      // cold [4]
   uint32_t *glob;                                     // cold [7] (held in registers during a step)
-  uint32_t *wallw;                                    // cold [34]: the 136 wall bytes, four per word
-  uint32_t *nextw, *nserial;                          // cold [34] [1]: the wall of kyoku_serial + 1, made ahead of time
+  uint32_t *wallw;                                    // cold [2][34]: two wall buffers of 136 bytes, four per word;
+                                                      // Glob::wall_sel names the current one, the other holds
+  uint32_t *nserial;                                  // cold [1]: ... the wall of this kyoku_serial, made ahead of time
   uint32_t *nexth, *nextred;                          // cold [16] [1]: its four dealt hands by seat wind, red fives
   uint64_t *nextwaits;                                // cold [4]: their waits
   uint8_t *river;                                     // cold [128]
@@ -94,7 +95,9 @@ struct Glob {
   uint8_t riichi_pending, rinshan, last_discard, last_discarder;
   uint8_t kakan_tile, kuikae0, kuikae1, first_wind;
   uint8_t same_wind_cnt, illegal_seat, end_type, winners;
-  uint8_t loser, tenpai_mask, pad0, pad1;
+  uint8_t loser, tenpai_mask;
+  uint8_t wall_sel;     // which of the two wall buffers holds the current wall (not part of the logical state)
+  uint8_t pad1;
 };
 union GlobU { Glob g; uint32_t w[7]; };
 

@@ -26,6 +26,8 @@ struct Ctx {
   uint32_t env_id;
   bool need_deal;      // set when a step ends in "deal the next kyoku": the caller shuffles and deals
   bool need_turn;      // the seat to move still needs its legal mask (step_finish)
+  uint32_t live_word;  // the wall word that holds the next live tile, loaded at the start of the step ...
+  int live_ptr;        // ... for this draw pointer (-1: nothing loaded)
 #ifdef MJ_PROFILE
   long long t[12], t0;  // cycle counters per stage (profiling builds only)
 #endif
@@ -40,13 +42,14 @@ MJ_HD uint64_t &DK(Ctx &c, int s) { return c.e.dk[(int64_t)s * c.e.hs]; }
 MJ_HD uint64_t &MASK(Ctx &c, int s, int w) { return c.e.mask[(int64_t)(s * 2 + w) * c.e.hs]; }
 MJ_HD int32_t &SCORE(Ctx &c, int s) { return c.e.score[(int64_t)s * c.e.hs]; }
 MJ_HD int32_t &DELTA(Ctx &c, int s) { return c.e.delta[(int64_t)s * c.e.hs]; }
-MJ_HD int wall_at(const Env &e, int i) { return (int)(e.wallw[(int64_t)(i >> 2) * e.n] >> (8 * (i & 3)) & 255u); }
-MJ_HD void wall_set(const Env &e, int i, int v)
+// tile i of wall buffer `sel`
+MJ_HD int wall_at(const Env &e, int sel, int i) { return (int)(e.wallw[(int64_t)(sel * 34 + (i >> 2)) * e.n] >> (8 * (i & 3)) & 255u); }
+MJ_HD void wall_set(const Env &e, int sel, int i, int v)
 {
-  uint32_t &w = e.wallw[(int64_t)(i >> 2) * e.n];
+  uint32_t &w = e.wallw[(int64_t)(sel * 34 + (i >> 2)) * e.n];
   w = (w & ~(255u << (8 * (i & 3)))) | (uint32_t)v << (8 * (i & 3));
 }
-MJ_HD int WALL(Ctx &c, int i) { return wall_at(c.e, i); }
+MJ_HD int WALL(Ctx &c, int i) { return wall_at(c.e, c.g.wall_sel, i); }
 MJ_HD uint8_t &RIVER(Ctx &c, int s, int i) { return c.e.river[(int64_t)(s * 32 + i) * c.e.n]; }
 
 MJ_HD int swf(Ctx &c, int s, int pos, int bits) { return (int)sw_get(SW(c, s), pos, bits); }
@@ -240,7 +243,8 @@ MJ_HD void turn_mask(Ctx &c)
 MJ_HD void draw_live(Ctx &c, int s)
 {
   c.g.cur = (uint8_t)s;
-  int id = WALL(c, c.g.draw_ptr);
+  int id = c.live_ptr == (int)c.g.draw_ptr ? (int)(c.live_word >> (8 * (c.g.draw_ptr & 3)) & 255u) : WALL(c, c.g.draw_ptr);
+  c.live_ptr = -1;
   c.g.draw_ptr++;
   c.g.live_left--;
   c.g.rinshan = 0;
@@ -252,7 +256,7 @@ MJ_HD void draw_live(Ctx &c, int s)
 MJ_HD void shuffle_wall(Ctx &c)
 {
   uint32_t serial = c.e.serial[0];
-  for (int i = 0; i < 136; i++) wall_set(c.e, i, i);
+  for (int i = 0; i < 136; i++) wall_set(c.e, c.g.wall_sel, i, i);
   for (int j = 0; j < 34; j++) {
     uint32_t r[4];
     philox(serial, (uint32_t)j, 0, 0, c.R.seed, c.env_id, r);
@@ -262,7 +266,7 @@ MJ_HD void shuffle_wall(Ctx &c)
       if (i >= 135) break;
       int k = i + (int)mulhi(r[t], (uint32_t)(136 - i));
       int a = WALL(c, i), b = WALL(c, k);
-      wall_set(c.e, i, b); wall_set(c.e, k, a);
+      wall_set(c.e, c.g.wall_sel, i, b); wall_set(c.e, c.g.wall_sel, k, a);
     }
   }
 }
@@ -657,7 +661,13 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
 #pragma unroll
   for (int s = 0; s < 4; s++) DELTA(c, s) = 0;
   c.g.illegal_seat = 255;
+  c.live_ptr = -1;
   if (c.g.terminated) return;
+  // the next live tile is needed at the end of most steps: start its load now
+  if (c.g.draw_ptr <= 121) {
+    c.live_word = c.e.wallw[(int64_t)(c.g.wall_sel * 34 + (c.g.draw_ptr >> 2)) * c.e.n];
+    c.live_ptr = c.g.draw_ptr;
+  }
   // stage 0: an action outside the mask ends the game at once
   const int actors = c.g.actor_mask;
   for (int s = 0; s < 4; s++) {

@@ -6,8 +6,8 @@
 //   u64 hot : discarded_kinds[4] waits[4] mask[8] meld[4]                   (20 arrays)
 //   u64 cold: yaku[4] result[4] next_waits[4]                               (12 arrays)
 //   u32 hot : score[4] delta[4] episode serial hand[16] seatw[4]            (30 arrays)
-//   u32 cold: gain[4] glob[7] wall[34] (136 tile ids, four per word)
-//             next_wall[34] next_serial next_hand[16] next_red (the next deal, made ahead) (97 arrays)
+//   u32 cold: gain[4] glob[7] wall[2][34] (two buffers of 136 tile ids, four per word: the current wall and
+//             the next one) next_serial next_hand[16] next_red (the next deal, made ahead)     (97 arrays)
 //   u8  cold: river[128]                                                    (128 arrays)
 // = 892 bytes per environment, 280 of them hot.  The "next" arrays are not part of the logical state: they are
 // a pure function of (seed, env id, kyoku_serial + 1), valid when next_serial says so.  The step kernels copy the
@@ -44,7 +44,7 @@ MJ_HD Env make_env(void *state, int64_t B, int64_t b)
   set_hot(e, q, w, B);
   e.yaku = q + (int64_t)kHotU64 * B; e.resw = q + (int64_t)(kHotU64 + 4) * B;
   e.gain = (int32_t *)(w + (int64_t)kHotU32 * B); e.glob = w + (int64_t)(kHotU32 + 4) * B;
-  e.wallw = w + (int64_t)(kHotU32 + 11) * B; e.nextw = w + (int64_t)(kHotU32 + 45) * B;
+  e.wallw = w + (int64_t)(kHotU32 + 11) * B;
   e.nserial = w + (int64_t)(kHotU32 + 79) * B; e.nexth = w + (int64_t)(kHotU32 + 80) * B;
   e.nextred = w + (int64_t)(kHotU32 + 96) * B; e.nextwaits = q + (int64_t)(kHotU64 + 8) * B; e.river = y;
   return e;

@@ -167,7 +167,8 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_
       }
     }
     // the wall goes to HBM, one word per lane
-    if (lane < 34) (state_u32(state, B) + (int64_t)(kHotU32 + 11) * B + bsrc)[(int64_t)lane * B] = wv;
+    const int sel = (int)__builtin_amdgcn_readlane((uint32_t)c.g.wall_sel, src);
+    if (lane < 34) (state_u32(state, B) + (int64_t)(kHotU32 + 11 + 34 * sel) * B + bsrc)[(int64_t)lane * B] = wv;
     // 4 x 13 tiles -> packed hand words (index j = seat wind), all in uniform values
     uint32_t hw[4][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
     uint32_t red[4] = {0, 0, 0, 0};
@@ -240,7 +241,7 @@ __device__ __forceinline__ void refill_next_wall(Ctx &c, uint8_t *col, int strid
   for (int j = 0; j < 34; j++) {
     const uint32_t w = (uint32_t)col[(4 * j) * stride] | (uint32_t)col[(4 * j + 1) * stride] << 8 |
                        (uint32_t)col[(4 * j + 2) * stride] << 16 | (uint32_t)col[(4 * j + 3) * stride] << 24;
-    c.e.nextw[(int64_t)j * c.e.n] = w;
+    c.e.wallw[(int64_t)((1 - c.g.wall_sel) * 34 + j) * c.e.n] = w;
   }
   // the four dealt hands (by seat wind j) and their waits, so that the deal itself is only a copy.
   // Field 3k of a 102-bit accumulator counts kind k: kinds 0..20 in `lo`, 21..33 in `hi`.
@@ -277,9 +278,8 @@ __device__ __forceinline__ void deal_from_next(Ctx &c)
 #pragma unroll
   for (int j = 0; j < 4; j++) wt[j] = c.e.nextwaits[(int64_t)j * n];
   const uint32_t reds = c.e.nextred[0];
-  const uint32_t first = c.e.nextw[13 * n] & 255u;          // wall[52]
-#pragma unroll 2
-  for (int j = 0; j < 34; j++) c.e.wallw[(int64_t)j * n] = c.e.nextw[(int64_t)j * n];
+  c.g.wall_sel ^= 1;                                        // the spare wall becomes the wall: no copy
+  const uint32_t first = c.e.wallw[(int64_t)(c.g.wall_sel * 34 + 13) * n] & 255u;      // wall[52]
   deal_reset(c);
   const int dealer = dealer_of(c);
 #pragma unroll
@@ -338,7 +338,7 @@ __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Ru
   const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false; c.need_turn = false;
+  c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   bool touched = false;
   if (active) {
     if (mode == 0) {
@@ -363,7 +363,7 @@ __global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R
   const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false; c.need_turn = false;
+  c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   if (active) {
     load_hot(m, state, B, b);
     load_glob(c.e, c.g);
@@ -398,7 +398,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, R
   const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false; c.need_turn = false;
+  c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
 #ifdef MJ_PROFILE
   for (int i = 0; i < 12; i++) c.t[i] = 0;
@@ -440,9 +440,9 @@ __global__ void __launch_bounds__(kBlock) k_deal_from_wall(void *state, int64_t 
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
   Ctx c;
   c.e = make_env(state, B, b); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
-  c.need_deal = false; c.need_turn = false;
+  c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   load_glob(c.e, c.g);
-  for (int i = 0; i < 136; i++) wall_set(c.e, i, wall[i]);
+  for (int i = 0; i < 136; i++) wall_set(c.e, c.g.wall_sel, i, wall[i]);
   deal(c, false);
   store_glob(c.e, c.g);
 }

@@ -32,7 +32,7 @@ static Ctx ctx_of(Sim *h, int64_t b)
   Ctx c;
   c.e = make_env(h->state.data(), h->B, b);
   c.L = &h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
-  c.need_deal = false; c.need_turn = false;
+  c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   return c;
 }
 static void reset_env(Ctx &c, bool first)
@@ -133,7 +133,7 @@ void hs_deal_from_wall(Sim *h, int64_t b, const uint8_t *wall)
 {
   Ctx c = ctx_of(h, b);
   load_glob(c.e, c.g);
-  for (int i = 0; i < 136; i++) wall_set(c.e, i, wall[i]);
+  for (int i = 0; i < 136; i++) wall_set(c.e, c.g.wall_sel, i, wall[i]);
   deal(c, false);
   store_glob(c.e, c.g);
 }
