@@ -87,6 +87,7 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
   }
   e.episode[0] = o.episode; e.serial[0] = o.kyoku_serial;
   e.nserial[0] = 0xFFFFFFFFu;                      // whatever was made ahead of time is gone
+  e.tdisc[0] = 0;                                  // ... and so is the cache of tenpai-keeping discards
   for (int i = 0; i < 34; i++)
     e.wallw[i * n] = (uint32_t)o.wall[4 * i] | (uint32_t)o.wall[4 * i + 1] << 8 | (uint32_t)o.wall[4 * i + 2] << 16 |
                      (uint32_t)o.wall[4 * i + 3] << 24;

@@ -25,12 +25,10 @@
 #ifndef MJ_STAT
 #define MJ_STAT(x) ((void)0)
 #endif
-// Out-of-line functions must be LEAVES: an out-of-line function that called another out-of-line function from
-// divergent code gave wrong results on the GPU (values of lanes that did not take the call were lost), while
-// the same source was correct on the host.  Everything an out-of-line function calls is force-inlined.
-#ifndef MJ_HD_NOINLINE
-#define MJ_HD_NOINLINE __host__ __device__ __attribute__((noinline))
-#endif
+// Everything is force-inlined: the kernels contain no function calls.  Out-of-line device functions (tried for
+// the hand evaluator and the waits search) gave wrong results on the GPU on rare paths while the same source was
+// right on the host, and each call site cost a few hundred instructions of register save and restore.  The big
+// functions therefore have few call sites each (loops over seats are kept rolled around them).
 
 namespace mj {
 
@@ -44,6 +42,8 @@ enum { MT_CHI = 1, MT_PON = 2, MT_MINKAN = 3, MT_ANKAN = 4, MT_KAKAN = 5 };
 constexpr uint64_t K_TERMINALS = 0x4060301ull;                       // kinds 0,8,9,17,18,26
 constexpr uint64_t K_HONORS = 0x7Full << 27;
 constexpr uint64_t K_YAOCHU = K_TERMINALS | K_HONORS;
+constexpr uint64_t TD_UNKNOWN = 1ull << 62;     // tenpai_discards_of without the search: "some discard may keep tenpai"
+constexpr uint64_t TD_VALID = 1ull << 63;       // Env::tdisc holds the tenpai-keeping discards of the hand as it is now
 constexpr uint64_t K_WINDS = 0xFull << 27;
 constexpr uint64_t K_DRAGONS = 0x7ull << 31;
 constexpr uint64_t K_ALL = (1ull << 34) - 1;
@@ -74,6 +74,7 @@ struct Lut {
 struct Env {
   int64_t n, hs;
   uint64_t *dk, *waits, *mask, *meld;                 // hot  [4] [4] [8] [4]
+  uint64_t *tdisc;                                    // hot  [1]: discards of the seat to move that keep its hand tenpai (TD_VALID set), a cache
   int32_t *score, *delta;                             // hot  [4] [4]
   uint32_t *episode, *serial, *hand, *seatw;          // hot  [1] [1] [16] [4]
   uint64_t *yaku, *resw;                              // cold [4] [4]
@@ -254,22 +255,87 @@ MJ_HD uint32_t suit_addmask(const Lut *Lp, int su, uint32_t w)
   }
   return m;
 }
-// kinds of which the seat owns four or more once its melds are counted (concealed four-of-a-kind included)
+// honors: ranks whose removal leaves the counts valid (closed form, like honors_valid)
+MJ_HD uint32_t honors_submask(uint32_t w)
+{
+  uint32_t one = fields_eq(w, 1), two = fields_eq(w, 2), three = fields_eq(w, 3), four = (w >> 2) & O111;
+  int n1 = popc32(one), n2 = popc32(two), n4 = popc32(four);
+  uint32_t cand = 0;
+  if (n1 == 1 && n4 == 0 && n2 <= 1) cand |= one;       // the lone single goes
+  if (n1 == 0 && n4 == 0 && n2 == 0) cand |= three;     // a triplet becomes the pair
+  if (n1 == 0 && n4 == 1 && n2 <= 1) cand |= four;      // the four become a triplet
+  return squeeze9(cand) & 0x7Fu;
+}
+// One numbered suit, every table probe issued together (rows first, then bitmap words: two LDS round trips in
+// all): is w valid, which ranks can take a tile (count < 4) so that it becomes valid, and -- WITH_SUB -- which
+// held ranks can lose a tile so that it is valid.
+struct SuitFacts { uint32_t valid, addm, subm; };
+template <bool WITH_SUB>
+MJ_HD SuitFacts suit_facts(const Lut &L, uint32_t w)
+{
+  const uint32_t p = prefix5(w), sfx = suffix5(w);
+  const uint32_t full = (w >> 2) & O111, present = fields_nonzero(w);
+  uint32_t rowa[5], rows[5];
+  const uint32_t rowp = L.rowid[p];
+  uint32_t pw = 1;
+#pragma unroll
+  for (int r = 0; r < 5; r++) {                            // a full / an empty field probes the key of w itself
+    rowa[r] = L.rowid[p + ((full >> (3 * r) & 1u) ? 0u : pw)];
+    rows[r] = WITH_SUB ? L.rowid[p - ((present >> (3 * r) & 1u) ? pw : 0u)] : 0u;
+    pw *= 5;
+  }
+  const uint32_t wi = sfx >> 5, bi = sfx & 31;
+  SuitFacts f;
+  f.valid = (L.bitmap[rowp * 20 + wi] >> bi) & 1u;
+  f.addm = 0; f.subm = 0;
+#pragma unroll
+  for (int r = 0; r < 5; r++) {
+    f.addm |= ((L.bitmap[rowa[r] * 20 + wi] >> bi) & 1u) << r;
+    if (WITH_SUB) f.subm |= ((L.bitmap[rows[r] * 20 + wi] >> bi) & 1u) << r;
+  }
+  pw = 1;
+#pragma unroll
+  for (int r = 5; r < 9; r++) {
+    const uint32_t sa = sfx + ((full >> (3 * r) & 1u) ? 0u : pw);
+    f.addm |= ((L.bitmap[rowp * 20 + (sa >> 5)] >> (sa & 31)) & 1u) << r;
+    if (WITH_SUB) {
+      const uint32_t ss = sfx - ((present >> (3 * r) & 1u) ? pw : 0u);
+      f.subm |= ((L.bitmap[rowp * 20 + (ss >> 5)] >> (ss & 31)) & 1u) << r;
+    }
+    pw *= 5;
+  }
+  f.addm &= ~squeeze9(full);
+  f.subm &= squeeze9(present);
+  return f;
+}
+// kinds of which the seat owns four once its melds are counted: the melds' tiles are added to the concealed
+// counts field by field (a kind never exceeds four copies, so no field overflows)
 MJ_HD uint64_t own4_mask(const uint32_t h[4], uint64_t meldw, int n_meld)
 {
-  uint64_t full = 0;
-#pragma unroll
-  for (int su = 0; su < 4; su++) full |= (uint64_t)squeeze9((h[su] >> 2) & O111) << (9 * su);
+  uint32_t o0 = h[0], o1 = h[1], o2 = h[2], o3 = h[3];
   for (int j = 0; j < n_meld; j++) {
-    uint32_t m = meld_at(meldw, j);
-    int t = m_type(m), b = m_kind(m), span = t == MT_CHI ? 3 : 1;
-    for (int d = 0; d < span; d++) {
-      int k = b + d, own = hand_count(h, k);
-      for (int i = 0; i < n_meld; i++) own += meld_count(meld_at(meldw, i), k);
-      if (own >= 4) full |= kbit(k);
-    }
+    const uint32_t m = meld_at(meldw, j);
+    const int t = m_type(m), b = m_kind(m), su = suit_of(b);
+    const uint32_t add = (t == MT_CHI ? 0111u : t == MT_PON ? 3u : 4u) << (3 * rank_of(b, su));
+    o0 += su == 0 ? add : 0u; o1 += su == 1 ? add : 0u; o2 += su == 2 ? add : 0u; o3 += su == 3 ? add : 0u;
   }
-  return full;
+  return (uint64_t)squeeze9((o0 >> 2) & O111) | (uint64_t)squeeze9((o1 >> 2) & O111) << 9 |
+         (uint64_t)squeeze9((o2 >> 2) & O111) << 18 | (uint64_t)squeeze9((o3 >> 2) & O111) << 27;
+}
+// cheap necessary conditions for the two special forms: kinds held at least twice; tiles that are neither terminals nor honors
+MJ_HD int kinds_held_twice(const uint32_t h[4])
+{
+  int n = 0;
+#pragma unroll
+  for (int su = 0; su < 4; su++) n += popc32(((h[su] >> 1) | (h[su] >> 2)) & O111);
+  return n;
+}
+MJ_HD int simple_tiles(const uint32_t h[4])
+{
+  int n = 0;
+#pragma unroll
+  for (int su = 0; su < 3; su++) n += tiles_in(h[su] & ~(7u | 7u << 24));
+  return n;
 }
 struct SpecialCounts { int c1, c2, c3, c4, yao_tiles, total; };
 MJ_HD SpecialCounts special_counts(const uint32_t h[4])
@@ -294,35 +360,34 @@ MJ_HD uint64_t kinds_where(const uint32_t h[4], int v)     // 34-bit mask of kin
 
 // Waits of a (13 - 3*n_meld)-tile hand: kinds whose addition completes it and
 // of which the seat owns fewer than four.
-MJ_HD_NOINLINE uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
+MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
 {
   const Lut &L = *Lp;
   MJ_STAT(n_waits);
-  uint32_t h[4] = {h0, h1, h2, h3};
+  const uint32_t h[4] = {h0, h1, h2, h3};
   uint64_t w = 0;
-  int rem[4], r1 = 0, r2 = 0;
+  int r1 = 0, r2 = 0;
+  uint32_t bad = 0, nonzero = 0;
 #pragma unroll
   for (int s = 0; s < 4; s++) {
-    rem[s] = tiles_in(h[s]) % 3;
-    r1 += rem[s] == 1; r2 += rem[s] == 2;
+    const int rem = tiles_in(h[s]) % 3;
+    r1 += rem == 1; r2 += rem == 2;
+    if (rem != 0) nonzero |= 1u << s;
+    if (rem == 1 || !suit_valid(L, s, h[s])) bad |= 1u << s;
   }
   // standard form: the suit that takes the tile has remainder 1 (it then holds the pair) or is one of two
-  // suits with remainder 2; every other suit must already be valid
-  if ((r1 == 1 && r2 == 0) || (r1 == 0 && r2 == 2)) {
-    int bad = 0, bad_suit = -1;
-#pragma unroll
-    for (int s = 0; s < 4; s++)
-      if (rem[s] == 1 || !suit_valid(L, s, h[s])) { bad++; bad_suit = s; }
-    // with remainder pattern (1,0,0,0) the remainder-1 suit is the only "bad" one allowed;
-    // with (2,2,0,0) either no suit is bad (both candidates) or one of the two is (then it must take the tile)
-#pragma unroll
-    for (int s = 0; s < 4; s++) {
-      if (rem[s] == 0) continue;
-      if (bad > 1 || (bad == 1 && bad_suit != s)) continue;
-      w |= (uint64_t)suit_addmask(Lp, s, h[s]) << (9 * s);
+  // suits with remainder 2; every other suit must already be valid.  With remainder pattern (1,0,0,0) the
+  // remainder-1 suit is the only "bad" one allowed; with (2,2,0,0) either no suit is bad (both are candidates)
+  // or one of the two is (then it must take the tile).
+  if (((r1 == 1 && r2 == 0) || (r1 == 0 && r2 == 2)) && (bad & (bad - 1)) == 0) {
+    uint32_t cands = bad ? (bad & nonzero) : nonzero;
+    while (cands) {
+      const int s = __builtin_ctz(cands);
+      cands &= cands - 1;
+      w |= (uint64_t)suit_addmask(Lp, s, pick4(h0, h1, h2, h3, s)) << (9 * s);
     }
   }
-  if (n_meld == 0) {
+  if (n_meld == 0 && (kinds_held_twice(h) == 6 || simple_tiles(h) == 0)) {
     SpecialCounts c = special_counts(h);
     if (c.c2 == 6 && c.c1 == 1 && c.c3 == 0 && c.c4 == 0) w |= kinds_where(h, 1);      // seven pairs
     if (c.yao_tiles == c.total && c.c3 == 0 && c.c4 == 0) {                            // thirteen orphans
@@ -334,40 +399,51 @@ MJ_HD_NOINLINE uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32
   return w;
 }
 
-// Kinds whose discard leaves the 14 - 3*n_meld tiles of a hand tenpai (non-empty waits_of).  Shares the
-// per-suit work between the candidate discards: only the suit that loses the tile is looked up again.
-// Per-suit facts are packed into scalars (remainders 2 bits each, validity and "computed" flags 1 bit each,
-// add-masks 9 bits each) so that nothing here is an indexed array.
-MJ_HD_NOINLINE uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
-                                           int n_meld)
+// Kinds whose discard leaves the 14 - 3*n_meld tiles of a hand tenpai (non-empty waits_of).  Per suit, three
+// facts are looked up once for the hand as it is: valid, ranks that may leave (the rest stays valid), ranks that
+// may come (the suit becomes valid and the kind is not exhausted).  A discard from suit s1 whose wait lies in
+// another suit s2 is then pure mask logic; only a discard whose wait lies in its own suit needs a lookup per
+// candidate, and that case needs the three other suits to be valid already.
+// With exact == false only the cheap necessary conditions are tested: the result is 0 (no discard keeps tenpai)
+// or TD_UNKNOWN.
+MJ_HD uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
+                                           int n_meld, bool exact)
 {
   const Lut &L = *Lp;
   MJ_STAT(n_tenpai);
   const uint32_t h[4] = {h0, h1, h2, h3};
   uint32_t remp = 0, valid = 0;
-  int n_invalid = 0, t1 = 0, t2 = 0;
+  int t1 = 0, t2 = 0;
 #pragma unroll
   for (int s = 0; s < 4; s++) {
-    int r = tiles_in(h[s]) % 3;
+    const int r = tiles_in(h[s]) % 3;
     remp |= (uint32_t)r << (2 * s);
     t1 += r == 1; t2 += r == 2;
-    bool v = r != 1 && suit_valid(L, s, h[s]);
-    valid |= (v ? 1u : 0u) << s;
-    n_invalid += v ? 0 : 1;
+    if (r != 1 && suit_valid(L, s, h[s])) valid |= 1u << s;
   }
   uint64_t out = 0;
-  if (n_invalid <= 2) {
-    uint64_t full = own4_mask(h, meldw, n_meld);
-    uint64_t addp = 0;            // add-mask of suit s in bits 9s..9s+8, valid once bit s of `have` is set
-    uint32_t have = 0;
+  const bool special = n_meld == 0 && (kinds_held_twice(h) >= 6 || simple_tiles(h) <= 1);
+  const bool standard = popc32(~valid & 15u) <= 2;      // a discard and a draw touch at most two suits
+  if (!exact) return (standard || special) ? TD_UNKNOWN : 0;
+  if (standard) {                       // rare: the search proper
+    const SuitFacts f0 = suit_facts<true>(L, h0), f1 = suit_facts<true>(L, h1), f2 = suit_facts<true>(L, h2);
+    const uint64_t full = own4_mask(h, meldw, n_meld);
+    const uint64_t subp = (uint64_t)f0.subm | (uint64_t)f1.subm << 9 | (uint64_t)f2.subm << 18 | (uint64_t)honors_submask(h3) << 27;
+    const uint64_t addp = ((uint64_t)f0.addm | (uint64_t)f1.addm << 9 | (uint64_t)f2.addm << 18 |
+                           (uint64_t)suit_addmask(Lp, 3, h3) << 27) & ~full;
+    uint32_t can_take = 0;
+#pragma unroll
+    for (int s = 0; s < 4; s++) if ((addp >> (9 * s)) & 0x1FF) can_take |= 1u << s;
+    uint64_t own_suit = 0;              // held kinds whose discard has to be tried with the wait in the same suit
+#pragma unroll
     for (int s1 = 0; s1 < 4; s1++) {
-      const uint32_t hs1 = pick4(h0, h1, h2, h3, s1);
-      if (hs1 == 0) continue;
+      if (h[s1] == 0) continue;
       const int rem1 = (int)(remp >> (2 * s1) & 3);
       // which suits may take the new tile when a tile leaves s1: the final remainders must be one 2 and three 0.
       // A suit that loses a tile goes 0 -> 2, 1 -> 0, 2 -> 1; one that gains a tile goes 0 -> 1, 1 -> 2, 2 -> 0.
       uint32_t feas = 0;
       if (t1 == 0 && t2 == 1) feas |= 1u << s1;                                  // the tile comes back into s1
+#pragma unroll
       for (int s2 = 0; s2 < 4; s2++) {
         if (s2 == s1) continue;
         const int rem2 = (int)(remp >> (2 * s2) & 3);
@@ -375,57 +451,43 @@ MJ_HD_NOINLINE uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t 
                  (rem1 == 1 && rem2 == 2 && t1 == 1 && t2 == 2);
         if (f) feas |= 1u << s2;
       }
-      if (!feas) continue;
       // the untouched suits must be valid as they are (at most one of them may be the one that takes the tile)
       const uint32_t bad_others = ~valid & 15u & ~(1u << s1);
       if (popc32(bad_others) > 1) continue;
-      const int nr = s1 == 3 ? 7 : 9, basek = s1 == 3 ? 27 : 9 * s1;
-      for (int r = 0; r < nr; r++) {
-        if (cnt3(hs1, r) == 0) continue;
-        const uint32_t g = hs1 - (1u << (3 * r));
-        bool ok = false;
-        // the new tile goes to another suit s2: g must be valid, and s2 is the only suit allowed to be invalid now
-        if (suit_valid(L, s1, g)) {
-          uint32_t cand = feas & ~(1u << s1);
-          if (bad_others) cand &= bad_others;
-          while (cand && !ok) {
-            const int s2 = __builtin_ctz(cand);
-            cand &= cand - 1;
-            if (!(have >> s2 & 1)) {
-              uint64_t am = suit_addmask(Lp, s2, pick4(h0, h1, h2, h3, s2)) & ~(uint32_t)(full >> (9 * s2) & 0x1FF);
-              addp |= am << (9 * s2);
-              have |= 1u << s2;
-            }
-            ok = (addp >> (9 * s2) & 0x1FF) != 0;
-          }
-        }
-        // the new tile goes back into s1
-        if (!ok && (feas >> s1 & 1) && bad_others == 0) {
-          uint32_t blocked = (uint32_t)(full >> (9 * s1) & 0x1FF) & ~(1u << r);     // the discarded kind is owned one less
-          ok = (suit_addmask(Lp, s1, g) & ~blocked) != 0;
-        }
-        if (ok) out |= kbit(basek + r);
-      }
+      const uint64_t field = 0x1FFull << (9 * s1);
+      // the wait lies in another suit s2: what stays in s1 must be valid, and s2 is the only suit that may be invalid
+      uint32_t cand = feas & ~(1u << s1);
+      if (bad_others) cand &= bad_others;
+      if (cand & can_take) out |= subp & field;
+      // the wait lies in s1 itself
+      if ((feas >> s1 & 1) && bad_others == 0)
+        own_suit |= (uint64_t)squeeze9(fields_nonzero(h[s1])) << (9 * s1);
+    }
+    own_suit &= ~out;
+    while (own_suit) {
+      const int k = ctz64(own_suit);
+      own_suit &= own_suit - 1;
+      const int su = suit_of(k), r = rank_of(k, su);
+      const uint32_t g = pick4(h0, h1, h2, h3, su) - (1u << (3 * r));
+      const uint32_t blocked = (uint32_t)(full >> (9 * su) & 0x1FF) & ~(1u << r);     // the discarded kind is owned one less
+      if (suit_addmask(Lp, su, g) & ~blocked) out |= kbit(k);
     }
   }
-  if (n_meld == 0) {
-    SpecialCounts c = special_counts(h);
-    bool chiitoi_near = c.c2 + c.c3 + c.c4 >= 5, kokushi_near = c.total - c.yao_tiles <= 1;
-    if (chiitoi_near || kokushi_near) {
-      for (int su = 0; su < 4; su++) {
-        const uint32_t hw = pick4(h0, h1, h2, h3, su);
-        int nr = su == 3 ? 7 : 9;
-        for (int r = 0; r < nr; r++) {
-          int n = cnt3(hw, r);
-          if (n == 0) continue;
-          int c1 = c.c1, c2 = c.c2, c3 = c.c3, c4 = c.c4;
-          if (n == 1) c1--; else if (n == 2) { c2--; c1++; } else if (n == 3) { c3--; c2++; } else { c4--; c3++; }
-          bool yao = su == 3 || r == 0 || r == 8;
-          int nonyao = c.total - c.yao_tiles - (yao ? 0 : 1);
-          bool t = (c2 == 6 && c1 == 1 && c3 == 0 && c4 == 0) ||
-                   (nonyao == 0 && c3 == 0 && c4 == 0 && ((c1 == 13 && c2 == 0) || (c1 == 11 && c2 == 1)));
-          if (t) out |= kbit((su == 3 ? 27 : 9 * su) + r);
-        }
+  if (special) {
+    // seven pairs and thirteen orphans in closed form: the counts of singles, pairs, triplets after the discard
+    const SpecialCounts c = special_counts(h);
+    if (c.c4 == 0) {
+      const uint64_t one = kinds_where(h, 1), two = kinds_where(h, 2), three = kinds_where(h, 3);
+      if (c.c3 == 0 && c.c2 == 6 && c.c1 == 2) out |= one;
+      if (c.c3 == 0 && c.c2 == 7 && c.c1 == 0) out |= two;
+      if (c.c3 == 1 && c.c2 == 5 && c.c1 == 1) out |= three;
+      const int nonyao = c.total - c.yao_tiles;
+      if (nonyao == 0) {
+        if (c.c3 == 0 && c.c1 == 12 && c.c2 == 1) out |= one | two;
+        if (c.c3 == 0 && c.c1 == 10 && c.c2 == 2) out |= two;
+        if (c.c3 == 1 && c.c1 == 11 && c.c2 == 0) out |= three;
+      } else if (nonyao == 1 && c.c3 == 0) {
+        if ((c.c1 == 14 && c.c2 == 0) || (c.c1 == 12 && c.c2 == 1)) out |= one & ~K_YAOCHU;
       }
     }
   }
@@ -635,7 +697,7 @@ MJ_HD void eval_decomp(EvalCtx &c, const Decomp &d)
   }
 }
 
-MJ_HD_NOINLINE void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
+MJ_HD void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
 {
   const Lut &L = *Lp;
   MJ_STAT(n_eval);

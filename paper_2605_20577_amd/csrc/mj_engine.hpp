@@ -29,7 +29,7 @@ struct Ctx {
   uint32_t live_word;  // the wall word that holds the next live tile, loaded at the start of the step ...
   int live_ptr;        // ... for this draw pointer (-1: nothing loaded)
 #ifdef MJ_PROFILE
-  long long t[12], t0;  // cycle counters per stage (profiling builds only)
+  long long t[16], t0;  // cycle counters per stage (profiling builds only)
 #endif
 };
 
@@ -39,6 +39,7 @@ MJ_HD uint32_t &SW(Ctx &c, int s) { return c.e.seatw[(int64_t)s * c.e.hs]; }
 MJ_HD uint64_t &MELDW(Ctx &c, int s) { return c.e.meld[(int64_t)s * c.e.hs]; }
 MJ_HD uint64_t &WAITS(Ctx &c, int s) { return c.e.waits[(int64_t)s * c.e.hs]; }
 MJ_HD uint64_t &DK(Ctx &c, int s) { return c.e.dk[(int64_t)s * c.e.hs]; }
+MJ_HD uint64_t &TD(Ctx &c) { return c.e.tdisc[0]; }
 MJ_HD uint64_t &MASK(Ctx &c, int s, int w) { return c.e.mask[(int64_t)(s * 2 + w) * c.e.hs]; }
 MJ_HD int32_t &SCORE(Ctx &c, int s) { return c.e.score[(int64_t)s * c.e.hs]; }
 MJ_HD int32_t &DELTA(Ctx &c, int s) { return c.e.delta[(int64_t)s * c.e.hs]; }
@@ -185,49 +186,58 @@ MJ_HD void turn_mask(Ctx &c)
   const uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
   const uint64_t mw = MELDW(c, s), waits = WAITS(c, s);
   const int riichi = (int)sw_get(sw, SW_RIICHI, 2), n_meld = (int)sw_get(sw, SW_NMELD, 3);
+  MJ_TICK(c, 11);
 
-  if (c.g.riichi_pending) {
-    discard_bits(h, sw, tenpai_discards_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld), m);
-  } else {
-    if (drawn_k >= 0 && (waits >> drawn_k & 1)) {
-      HandOut r;
-      eval_seat(c, s, drawn_k, true, false, r);
-      if (r.yaku_ok) set_action(m, A_TSUMO);
+  // Discards that keep the hand tenpai: needed for the riichi declaration and the discard that follows it, and
+  // kept for the next step, where the discard then tells whether the seat's waits are empty without a search.
+  // A seat in riichi can only discard the drawn tile, which gives back the hand it had: nothing to find out.
+  bool menzen = true;
+  for (int j = 0; j < n_meld; j++) if (m_type(meld_at(mw, j)) != MT_ANKAN) menzen = false;
+  const bool may_riichi = !c.g.riichi_pending && !riichi && drawn_k >= 0 && menzen && SCORE(c, s) >= 1000 && c.g.live_left >= 4;
+  uint64_t td = 0;
+  if (!riichi) td = tenpai_discards_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld, may_riichi || c.g.riichi_pending);
+  TD(c) = (td & TD_UNKNOWN) ? 0 : td | TD_VALID;        // the set itself is only searched for when the mask needs it
+  MJ_TICK(c, 14);
+  if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
+    HandOut r;
+    eval_seat(c, s, drawn_k, true, false, r);
+    if (r.yaku_ok) set_action(m, A_TSUMO);
+  }
+  MJ_TICK(c, 12);
+  const bool kan_ok = !c.g.riichi_pending && drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
+  if (riichi) {
+    if (code_red(c.g.drawn)) set_action(m, A_DISCARD_RED + drawn_k / 9);
+    else set_action(m, A_DISCARD + drawn_k);
+    if (kan_ok && hand_count(h, drawn_k) == 4) {
+      // a concealed kan is allowed in riichi only when it leaves the waits as they were
+      const int su = suit_of(drawn_k);
+      const uint32_t four = 4u << (3 * rank_of(drawn_k, su));
+      const uint64_t mw2 = mw | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
+      if (waits_of(c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
+                   h[3] - (su == 3 ? four : 0u), mw2, n_meld + 1) == waits)
+        set_action(m, A_KAN + drawn_k);
     }
-    const bool kan_ok = drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
-    if (riichi) {
-      if (code_red(c.g.drawn)) set_action(m, A_DISCARD_RED + drawn_k / 9);
-      else set_action(m, A_DISCARD + drawn_k);
-      if (kan_ok && hand_count(h, drawn_k) == 4) {
-        // a concealed kan is allowed in riichi only when it leaves the waits as they were
-        const int su = suit_of(drawn_k);
-        const uint32_t four = 4u << (3 * rank_of(drawn_k, su));
-        const uint64_t mw2 = mw | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
-        if (waits_of(c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
-                     h[3] - (su == 3 ? four : 0u), mw2, n_meld + 1) == waits)
-          set_action(m, A_KAN + drawn_k);
-      }
-    } else {
-      uint64_t allowed = K_ALL;
+  } else {
+    uint64_t allowed = td;                                  // after the declaration: tenpai-keeping discards only
+    if (!c.g.riichi_pending) {
+      allowed = K_ALL;
       if (c.g.kuikae0 != 255) allowed &= ~kbit(c.g.kuikae0);
       if (c.g.kuikae1 != 255) allowed &= ~kbit(c.g.kuikae1);
-      discard_bits(h, sw, allowed, m);
-      bool menzen = true;
+    }
+    discard_bits(h, sw, allowed, m);
+    if (!c.g.riichi_pending) {
       uint64_t kans = 0;                                    // kinds that may be declared as a kan
 #pragma unroll
       for (int su = 0; su < 4; su++) kans |= (uint64_t)squeeze9(fields_eq(h[su], 4)) << (9 * su);
       for (int j = 0; j < n_meld; j++) {
         const uint32_t ml = meld_at(mw, j);
-        if (m_type(ml) != MT_ANKAN) menzen = false;
         if (m_type(ml) == MT_PON && hand_count(h, m_kind(ml)) >= 1) kans |= kbit(m_kind(ml));
       }
       if (kan_ok) {                                         // KAN k is action 37 + k: bits 37..70
         m.w0 |= kans << A_KAN;
         m.w1 |= kans >> (64 - A_KAN);
       }
-      if (drawn_k >= 0 && menzen && SCORE(c, s) >= 1000 && c.g.live_left >= 4) {
-        if (tenpai_discards_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld)) set_action(m, A_RIICHI);
-      }
+      if (td && may_riichi) set_action(m, A_RIICHI);
       if ((c.R.flags & F_ABORT) && (sw >> SW_FIRST & 1) && drawn_k >= 0) {
         uint64_t present = 0;
 #pragma unroll
@@ -235,6 +245,7 @@ MJ_HD void turn_mask(Ctx &c)
         if (popc64(present & K_YAOCHU) >= 9) set_action(m, A_KYUUSHU);
       }
     }
+    MJ_TICK(c, 13);
   }
   MASK(c, s, 0) = m.w0;
   MASK(c, s, 1) = m.w1;
@@ -497,13 +508,11 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   return ok;
 }
 
-// what seat o may do about the tile just discarded by d
-MJ_HD void response_options(Ctx &c, int o, int d, int code, Mask2 &m)
+// the calls (pon, open kan, chi) seat o may make on the tile just discarded by d
+MJ_HD void call_options(Ctx &c, int o, int d, int code, Mask2 &m)
 {
   int k = code_kind(code);
-  m.w0 = m.w1 = 0;
   uint32_t sw = SW(c, o);
-  if (ron_option(c, o, k, false)) set_action(m, A_RON);
   if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0) {
     int su = suit_of(k), r = rank_of(k, su);
     uint32_t hw = HW(c, o, su);
@@ -536,7 +545,6 @@ MJ_HD void response_options(Ctx &c, int o, int d, int code, Mask2 &m)
       }
     }
   }
-  if (m.w0 | m.w1) set_action(m, A_PASS);
 }
 
 // seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later
@@ -580,7 +588,7 @@ MJ_HD bool apply_call(Ctx &c, int s, int a)
 {
   int d = c.g.last_discarder, k = code_kind(c.g.last_discard), cred = code_red(c.g.last_discard);
   int from_rel = (d - s) & 3;
-  RIVER(c, d, swf(c, d, SW_NRIVER, 6) - 1) |= 0x80;
+  RIVER(c, d, swf(c, d, SW_NRIVER, 6) - 1) = (uint8_t)(c.g.last_discard | 0x80);      // the called tile, marked; no read-back
   clear_first_and_ippatsu(c);
   c.g.cur = (uint8_t)s;
   c.g.drawn = 255;
@@ -686,14 +694,16 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   }
   MJ_TICK(c, 1);
   // stage 1: apply
-  int waits_seat = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
+  int waits_seat = -1, waits_k = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
   bool respond = false, rob = false, advance = false, kan_fin = false, win_tsumo = false, win_rob = false;
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
     if (act < A_KAN) {
-      if (act < A_DISCARD_RED) apply_discard(c, s, act, 0);
-      else apply_discard(c, s, 4 + 9 * (act - A_DISCARD_RED), 1);
-      waits_seat = s; respond = true;
+      const int k = act < A_DISCARD_RED ? act : 4 + 9 * (act - A_DISCARD_RED);
+      // a seat in riichi gives back the drawn tile: its waits stay; any other seat's waits follow from the discard
+      if (!sw_get(SW(c, s), SW_RIICHI, 2)) { waits_seat = s; waits_k = k; }
+      apply_discard(c, s, k, act < A_DISCARD_RED ? 0 : 1);
+      respond = true;
     } else if (act < A_RIICHI) {
       if (apply_own_kan(c, act - A_KAN)) kan_fin = true; else rob = true;
       waits_seat = s;
@@ -731,20 +741,30 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   clear_masks(c);
   MJ_TICK(c, 2);
   // stage 2: the seat whose concealed hand is back to 13 - 3 * melds tiles gets its waits refreshed
-  if (waits_seat >= 0) refresh_waits(c, waits_seat);
+  if (waits_seat >= 0) {
+    bool search = true;
+    if (waits_k >= 0) {                    // a discard: the cache made with the turn's mask says whether any wait is left
+      const uint64_t td = TD(c);
+      if (td & TD_VALID) {
+        search = td >> waits_k & 1;
+        if (!search) WAITS(c, waits_seat) = 0;
+      }
+    }
+    if (search) refresh_waits(c, waits_seat);
+  }
   MJ_TICK(c, 3);
   // stage 3: responses of the other seats
   if (respond || rob) {
     int from = respond ? c.g.last_discarder : c.g.cur;
     int code = respond ? c.g.last_discard : c.g.kakan_tile;
     int any = 0;
-#pragma unroll
-    for (int j = 1; j < 4; j++) {
-      int o = (from + j) & 3;
+#pragma unroll 1
+    for (int j = 1; j < 4; j++) {            // one copy of the code for the three seats (one evaluation site)
+      const int o = (from + j) & 3;
       Mask2 m = {0, 0};
-      if (respond) response_options(c, o, from, code, m);
-      else if (ron_option(c, o, code_kind(code), true)) { set_action(m, A_RON); set_action(m, A_PASS); }
-      if (m.w0 | m.w1) { any |= 1 << o; MASK(c, o, 0) = m.w0; MASK(c, o, 1) = m.w1; }
+      if (ron_option(c, o, code_kind(code), rob)) set_action(m, A_RON);
+      if (respond) call_options(c, o, from, code, m);
+      if (m.w0 | m.w1) { set_action(m, A_PASS); any |= 1 << o; MASK(c, o, 0) = m.w0; MASK(c, o, 1) = m.w1; }
     }
     if (any) {
       c.g.phase = respond ? PH_RESPOND : PH_RESPOND_KAKAN;

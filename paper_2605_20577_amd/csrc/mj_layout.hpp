@@ -3,21 +3,22 @@
 // For B environments every field is an array over b, so the 64 lanes of a
 // wavefront (64 consecutive environments) touch consecutive addresses.
 // Sections, in this order, each array of length B:
-//   u64 hot : discarded_kinds[4] waits[4] mask[8] meld[4]                   (20 arrays)
+//   u64 hot : discarded_kinds[4] waits[4] mask[8] meld[4] tenpai_discards   (21 arrays)
 //   u64 cold: yaku[4] result[4] next_waits[4]                               (12 arrays)
 //   u32 hot : score[4] delta[4] episode serial hand[16] seatw[4]            (30 arrays)
 //   u32 cold: gain[4] glob[7] wall[2][34] (two buffers of 136 tile ids, four per word: the current wall and
 //             the next one) next_serial next_hand[16] next_red (the next deal, made ahead)     (97 arrays)
 //   u8  cold: river[128]                                                    (128 arrays)
-// = 892 bytes per environment, 280 of them hot.  The "next" arrays are not part of the logical state: they are
-// a pure function of (seed, env id, kyoku_serial + 1), valid when next_serial says so.  The step kernels copy the
+// = 900 bytes per environment, 288 of them hot.  The "next" arrays are not part of the logical state: they are
+// a pure function of (seed, env id, kyoku_serial + 1), valid when next_serial says so; tenpai_discards is a cache
+// (a function of the hand of the seat to move, valid when its top bit is set).  The step kernels copy the
 // hot arrays of their block into LDS, run there, and copy them back.
 #pragma once
 #include "mj_core.hpp"
 
 namespace mj {
 
-constexpr int kHotU64 = 20, kColdU64 = 12, kHotU32 = 30, kColdU32 = 97, kU8Arrays = 128;
+constexpr int kHotU64 = 21, kColdU64 = 12, kHotU32 = 30, kColdU32 = 97, kU8Arrays = 128;
 constexpr int kU64Arrays = kHotU64 + kColdU64, kU32Arrays = kHotU32 + kColdU32;
 constexpr int64_t kBytesPerEnv = 8 * kU64Arrays + 4 * kU32Arrays + kU8Arrays;
 constexpr int kHotBytesPerEnv = 8 * kHotU64 + 4 * kHotU32;
@@ -29,7 +30,7 @@ MJ_HD uint8_t *state_u8(void *state, int64_t B) { return (uint8_t *)(state_u32(s
 MJ_HD void set_hot(Env &e, uint64_t *q, uint32_t *w, int64_t hs)
 {
   e.hs = hs;
-  e.dk = q; e.waits = q + 4 * hs; e.mask = q + 8 * hs; e.meld = q + 16 * hs;
+  e.dk = q; e.waits = q + 4 * hs; e.mask = q + 8 * hs; e.meld = q + 16 * hs; e.tdisc = q + 20 * hs;
   e.score = (int32_t *)w; e.delta = (int32_t *)(w + 4 * hs); e.episode = w + 8 * hs; e.serial = w + 9 * hs;
   e.hand = w + 10 * hs; e.seatw = w + 26 * hs;
 }

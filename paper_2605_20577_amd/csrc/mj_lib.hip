@@ -39,6 +39,9 @@ struct DevTables {
 };
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
 constexpr int kLutBytes = 64;            // the block's copy of the table pointers
+#ifndef MJ_OCC
+#define MJ_OCC 2                         // waves per SIMD the register budget of the stepping kernels is sized for
+#endif
 constexpr int kRefillEvery = 32;         // steps between refills of the walls made ahead of time
 
 // A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
@@ -247,7 +250,7 @@ __device__ __forceinline__ void refill_next_wall(Ctx &c, uint8_t *col, int strid
   // Field 3k of a 102-bit accumulator counts kind k: kinds 0..20 in `lo`, 21..33 in `hi`.
   const bool red_rules = (c.R.flags & F_RED) != 0;
   uint32_t reds = 0;
-#pragma unroll
+#pragma unroll 1
   for (int j = 0; j < 4; j++) {
     uint64_t lo = 0, hi = 0;
 #pragma unroll
@@ -323,7 +326,7 @@ __device__ __forceinline__ void reset_env(Ctx &c, bool first)
 // mode 0: first initialisation of every env; mode 1: restart of the terminated ones (a block without a
 // terminated env leaves before it stages anything)
 template <int LPW>
-__global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Rules R, DevTables T, int mode)
+__global__ void __launch_bounds__(kBlock, MJ_OCC) k_new_games(void *state, int64_t B, Rules R, DevTables T, int mode)
 {
   extern __shared__ __align__(16) uint8_t lds[];
   if (mode == 1) {
@@ -355,7 +358,7 @@ __global__ void __launch_bounds__(kBlock) k_new_games(void *state, int64_t B, Ru
 }
 
 template <int LPW>
-__global__ void __launch_bounds__(kBlock) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions, int refill)
+__global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions, int refill)
 {
   extern __shared__ __align__(16) uint8_t lds[];
   BlockMem m = stage_block<LPW>(T, lds);
@@ -389,7 +392,7 @@ __device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step)
 
 // n_steps of { sample, step, optional reset } without leaving the kernel: environments never interact
 template <int LPW>
-__global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
+__global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
                                                     int n_steps, int auto_reset)
 {
   extern __shared__ __align__(16) uint8_t lds[];
@@ -401,7 +404,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, R
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
 #ifdef MJ_PROFILE
-  for (int i = 0; i < 12; i++) c.t[i] = 0;
+  for (int i = 0; i < 16; i++) c.t[i] = 0;
   c.t0 = clock64();
 #endif
   for (int t = 0; t < n_steps; t++) {
@@ -424,15 +427,15 @@ __global__ void __launch_bounds__(kBlock, 2) k_rollout(void *state, int64_t B, R
   }
 #ifdef MJ_PROFILE
   if (blockIdx.x == 7 && threadIdx.x == 0 && n_steps == 128)
-    printf("PROF/step: refill %lld sample %lld | check %lld apply %lld waits %lld respond %lld end %lld draw %lld | reset %lld deal %lld mask %lld\n",
+    printf("PROF/step: refill %lld sample %lld | check %lld apply %lld waits %lld respond %lld end %lld draw %lld | reset %lld deal %lld mask %lld (pre %lld tsumo %lld bits %lld riichi %lld)\n",
            c.t[10] / 128, c.t[0] / 128, c.t[1] / 128, c.t[2] / 128, c.t[3] / 128, c.t[4] / 128, c.t[5] / 128, c.t[6] / 128,
-           c.t[7] / 128, c.t[8] / 128, c.t[9] / 128);
+           c.t[7] / 128, c.t[8] / 128, c.t[9] / 128, c.t[11] / 128, c.t[12] / 128, c.t[13] / 128, c.t[14] / 128);
 #endif
   if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
 
 // test / scripting aid: give env b the wall in `wall` and deal the current kyoku again from it
-__global__ void __launch_bounds__(kBlock) k_deal_from_wall(void *state, int64_t B, Rules R, DevTables T, int64_t b,
+__global__ void __launch_bounds__(kBlock, MJ_OCC) k_deal_from_wall(void *state, int64_t B, Rules R, DevTables T, int64_t b,
                                                            const uint8_t *wall)
 {
   extern __shared__ __align__(16) uint8_t lds[];
@@ -508,7 +511,7 @@ __global__ void __launch_bounds__(kAuxBlock) k_import(void *state, int64_t B, in
   import_env(make_env(state, B, lo + i), o);
 }
 
-__global__ void __launch_bounds__(kAuxBlock) k_eval_hands(DevTables T, int64_t n, const MjHandQuery *in, MjHandResult *out)
+__global__ void __launch_bounds__(kAuxBlock, MJ_OCC) k_eval_hands(DevTables T, int64_t n, const MjHandQuery *in, MjHandResult *out)
 {
   extern __shared__ __align__(16) uint8_t lds[];
   {

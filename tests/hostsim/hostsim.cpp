@@ -7,7 +7,6 @@
 // product: the Python package never loads it, and nothing here is reachable
 // from libmj.so.
 #define MJ_HD inline __attribute__((always_inline))
-#define MJ_HD_NOINLINE __attribute__((noinline))
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -188,6 +187,15 @@ uint64_t hs_waits(Sim *h, const uint8_t *hand, const uint16_t *meld, int n_meld)
   uint64_t mw = 0;
   for (int j = 0; j < 4; j++) mw |= (uint64_t)meld[j] << (16 * j);
   return waits_of(&h->L, hw[0], hw[1], hw[2], hw[3], mw, n_meld);
+}
+
+uint64_t hs_tenpai_discards(Sim *h, const uint8_t *hand, const uint16_t *meld, int n_meld)
+{
+  uint32_t hw[4] = {0, 0, 0, 0};
+  for (int k = 0; k < 34; k++) { int su = suit_of(k); hw[su] |= (uint32_t)hand[k] << (3 * rank_of(k, su)); }
+  uint64_t mw = 0;
+  for (int j = 0; j < 4; j++) mw |= (uint64_t)meld[j] << (16 * j);
+  return tenpai_discards_of(&h->L, hw[0], hw[1], hw[2], hw[3], mw, n_meld, true);
 }
 
 }  // extern "C"

@@ -49,6 +49,8 @@ def lib():
         L.hs_eval_hands.argtypes = [vp, C.c_int64, vp, vp]
         L.hs_waits.argtypes = [vp, vp, vp, C.c_int]
         L.hs_waits.restype = C.c_uint64
+        L.hs_tenpai_discards.argtypes = [vp, vp, vp, C.c_int]
+        L.hs_tenpai_discards.restype = C.c_uint64
         _lib = L
     return _lib
 
@@ -127,3 +129,9 @@ class HostSim:
         m = np.zeros(4, dtype=np.uint16)
         m[:len(melds)] = melds
         return int(lib().hs_waits(self._h, _p(h), _p(m), len(melds)))
+
+    def tenpai_discards_of(self, hand, melds=()):
+        h = np.ascontiguousarray(hand, dtype=np.uint8)
+        m = np.zeros(4, dtype=np.uint16)
+        m[:len(melds)] = melds
+        return int(lib().hs_tenpai_discards(self._h, _p(h), _p(m), len(melds)))

@@ -50,3 +50,98 @@ def test_fused_rollout_and_waits():
             n = int(eo["n_meld"][b, seat])
             if int(eo["hand"][b, seat].sum()) == 13 - 3 * n:
                 assert s.waits_of(eo["hand"][b, seat], eo["meld"][b, seat][:n].tolist()) == int(eo["waits"][b, seat])
+
+
+def _near_hands(rng, n):
+    """Seeded 14 - 3m tile hands that sit close to tenpai in every way the waits code distinguishes: complete
+    standard hands with 0-2 tiles swapped, one-suit hands, seven-pairs and thirteen-orphans neighbours, plain
+    random draws; 0-3 melds (chi, pon, open / concealed / added kan)."""
+    yao = [0, 8, 9, 17, 18, 26, 27, 28, 29, 30, 31, 32, 33]
+    out = []
+    while len(out) < n:
+        left = np.full(34, 4, dtype=np.int64)
+        hand = np.zeros(34, dtype=np.int64)
+        melds = []
+        style = int(rng.integers(0, 6))
+        m = int(rng.integers(0, 4)) if style < 3 else 0
+        ok = True
+        for _ in range(m):
+            t = int(rng.integers(1, 6))
+            if t == 1:
+                su, lo = int(rng.integers(0, 3)), int(rng.integers(0, 7))
+                ks = [9 * su + lo + i for i in range(3)]
+                if min(left[ks]) < 1: ok = False; break
+                left[ks] -= 1
+                melds.append(1 | ks[0] << 3 | 3 << 9)
+            else:
+                k, need = int(rng.integers(0, 34)), 3 if t == 2 else 4
+                if left[k] < need: ok = False; break
+                left[k] -= need
+                melds.append(t | k << 3 | (0 if t == 4 else 2 << 9))
+        if not ok:
+            continue
+        size = 14 - 3 * m
+
+        def take(k):
+            if left[k] < 1: return False
+            left[k] -= 1; hand[k] += 1
+            return True
+        if style in (0, 1):                       # sets + pair, then a few tiles swapped
+            one_suit = style == 1 and m == 0
+            su0 = int(rng.integers(0, 3))
+            for _ in range(4 - m):
+                if rng.integers(0, 2) or one_suit:
+                    su, lo = (su0 if one_suit else int(rng.integers(0, 3))), int(rng.integers(0, 7))
+                    ks = [9 * su + lo + i for i in range(3)]
+                else:
+                    ks = [int(rng.integers(0, 34))] * 3
+                ok = ok and all(take(k) for k in ks)
+            kp = 9 * su0 + int(rng.integers(0, 9)) if one_suit else int(rng.integers(0, 34))
+            ok = ok and take(kp) and take(kp)
+            if not ok:
+                continue
+            for _ in range(int(rng.integers(0, 3))):
+                held = np.flatnonzero(hand)
+                d = int(rng.choice(held)); hand[d] -= 1; left[d] += 1
+                a = 9 * su0 + int(rng.integers(0, 9)) if one_suit else int(rng.integers(0, 34))
+                if not take(a): hand[d] += 1; left[d] -= 1
+        elif style == 2:                          # plain random draw
+            wall = np.repeat(np.arange(34), left)
+            for k in rng.permutation(wall)[:size]: hand[k] += 1
+        elif style == 3:                          # seven pairs and neighbours
+            ks = rng.permutation(34)[:7]
+            for k in ks: hand[k] += 2
+            for _ in range(int(rng.integers(0, 3))):
+                d = int(rng.choice(np.flatnonzero(hand))); a = int(rng.integers(0, 34))
+                if hand[a] < 4: hand[d] -= 1; hand[a] += 1
+        elif style == 4:                          # thirteen orphans and neighbours
+            for k in yao: hand[k] += 1
+            hand[int(rng.choice(yao))] += 1
+            for _ in range(int(rng.integers(0, 3))):
+                d = int(rng.choice(np.flatnonzero(hand)))
+                a = int(rng.choice(yao)) if rng.integers(0, 3) else int(rng.integers(0, 34))
+                if hand[a] < 4: hand[d] -= 1; hand[a] += 1
+        else:                                     # 14 tiles of one suit
+            su = int(rng.integers(0, 3))
+            wall = np.repeat(np.arange(9 * su, 9 * su + 9), 4)
+            for k in rng.permutation(wall)[:14]: hand[k] += 1
+        if hand.sum() == size and hand.max() <= 4:
+            out.append((hand.astype(np.uint8), melds))
+    return out
+
+
+def test_waits_and_tenpai_discards_vs_oracle():
+    s = HostSim(1, 0, mjo.RULES_NORED, mjo.MODE_SINGLE)
+    rng = np.random.default_rng(20577)
+    n_tenpai = n_wait = 0
+    for hand, melds in _near_hands(rng, 6000):
+        want = 0
+        for d in np.flatnonzero(hand):
+            g = hand.copy(); g[d] -= 1
+            w = mjo.waits_of(g, melds)
+            assert s.waits_of(g, melds) == w, (hand.tolist(), melds, int(d))
+            n_wait += w != 0
+            if w: want |= 1 << int(d)
+        assert s.tenpai_discards_of(hand, melds) == want, (hand.tolist(), melds)
+        n_tenpai += want != 0
+    assert n_tenpai > 1500 and n_wait > 5000        # the cases are not vacuous
