@@ -517,7 +517,7 @@ MJ_HD void call_options(Ctx &c, int o, int d, int code, Mask2 &m)
     int su = suit_of(k), r = rank_of(k, su);
     uint32_t hw = HW(c, o, su);
     int have = cnt3(hw, r);
-    int total = concealed_total(c, o);
+    int total = 13 - 3 * (int)sw_get(sw, SW_NMELD, 3);      // a seat that is not on turn holds exactly this many
     bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
     int nonred = have - (red_held ? 1 : 0);
     if (total - have > 0) {
@@ -583,42 +583,56 @@ MJ_HD void push_meld(Ctx &c, int s, uint32_t m)
   swf_set(c, s, SW_NMELD, 3, j + 1);
 }
 
-// seat s takes the last discard with action a; returns true for an open kan (replacement draw due)
+// seat s takes the last discard with action a; returns true for an open kan (replacement draw due).
+// The words it touches are read once, changed in registers and written once.
 MJ_HD bool apply_call(Ctx &c, int s, int a)
 {
-  int d = c.g.last_discarder, k = code_kind(c.g.last_discard), cred = code_red(c.g.last_discard);
-  int from_rel = (d - s) & 3;
-  RIVER(c, d, swf(c, d, SW_NRIVER, 6) - 1) = (uint8_t)(c.g.last_discard | 0x80);      // the called tile, marked; no read-back
-  clear_first_and_ippatsu(c);
+  const int d = c.g.last_discarder, k = code_kind(c.g.last_discard), cred = code_red(c.g.last_discard);
+  const int from_rel = (d - s) & 3, su = suit_of(k), r = rank_of(k, su);
+  uint32_t sws[4];
+#pragma unroll
+  for (int t = 0; t < 4; t++) sws[t] = SW(c, t);
+  const uint32_t sw_d = pick4(sws[0], sws[1], sws[2], sws[3], d);
+  uint32_t sw = pick4(sws[0], sws[1], sws[2], sws[3], s);
+  uint32_t hw = HW(c, s, su);
+  uint64_t mw = MELDW(c, s);
+  RIVER(c, d, (int)sw_get(sw_d, SW_NRIVER, 6) - 1) = (uint8_t)(c.g.last_discard | 0x80);      // the called tile, marked
   c.g.cur = (uint8_t)s;
   c.g.drawn = 255;
   c.g.rinshan = 0;
+  const bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
+  int tr = 0;                        // the red five leaves the hand
+  uint32_t gone, meld;               // tiles taken from the hand (3-bit fields), the meld record
+  bool kan = false;
   if (a == A_PON || a == A_PON_RED) {
-    int tr = a == A_PON_RED;
-    remove_tiles(c, s, k, tr ? 1 : 2, tr);
-    push_meld(c, s, m_make(MT_PON, k, from_rel, 0, tr | cred, cred));
+    tr = a == A_PON_RED;
+    gone = 2u << (3 * r);
+    meld = m_make(MT_PON, k, from_rel, 0, tr | cred, cred);
     c.g.kuikae0 = (uint8_t)k; c.g.kuikae1 = 255;
-    return false;
+  } else if (a == A_MINKAN) {
+    tr = red_held ? 1 : 0;
+    gone = 3u << (3 * r);
+    meld = m_make(MT_MINKAN, k, from_rel, 0, tr | cred, cred);
+    kan = true;
+  } else {
+    const int v = a - A_CHI_L, pos = v % 3, lo = r - pos;
+    tr = v >= 3 ? 1 : 0;
+    gone = (0111u << (3 * lo)) & ~(1u << (3 * r));          // one each of the run's ranks except the called one
+    meld = m_make(MT_CHI, k - pos, from_rel, pos, tr | cred, cred);
+    c.g.kuikae0 = (uint8_t)k;
+    c.g.kuikae1 = 255;
+    if (pos == 0 && r + 3 <= 8) c.g.kuikae1 = (uint8_t)(k + 3);
+    if (pos == 2 && r - 3 >= 0) c.g.kuikae1 = (uint8_t)(k - 3);
   }
-  if (a == A_MINKAN) {
-    int tr = has_red(c, s, k) ? 1 : 0;
-    remove_tiles(c, s, k, tr ? 2 : 3, tr);
-    push_meld(c, s, m_make(MT_MINKAN, k, from_rel, 0, tr | cred, cred));
-    return true;
-  }
-  int v = a - A_CHI_L, tr = v >= 3 ? 1 : 0, pos = v % 3, base = k - pos;
-  for (int t = 0; t < 3; t++) {
-    if (t == pos) continue;
-    int kk = base + t, r = (tr && is_five(kk)) ? 1 : 0;
-    remove_tiles(c, s, kk, r ? 0 : 1, r);
-  }
-  push_meld(c, s, m_make(MT_CHI, base, from_rel, pos, tr | cred, cred));
-  int rk = k % 9;
-  c.g.kuikae0 = (uint8_t)k;
-  c.g.kuikae1 = 255;
-  if (pos == 0 && rk + 3 <= 8) c.g.kuikae1 = (uint8_t)(k + 3);
-  if (pos == 2 && rk - 3 >= 0) c.g.kuikae1 = (uint8_t)(k - 3);
-  return false;
+  HW(c, s, su) = hw - gone;
+  if (tr) sw &= ~(1u << su);
+  const int j = (int)sw_get(sw, SW_NMELD, 3);
+  MELDW(c, s) = mw | (uint64_t)meld << (16 * j);
+  sw = sw_set(sw, SW_NMELD, 3, (uint32_t)(j + 1));
+  // any call ends everybody's first turn and ippatsu
+#pragma unroll
+  for (int t = 0; t < 4; t++) SW(c, t) = (t == s ? sw : sws[t]) & ~((1u << SW_IPPATSU) | (1u << SW_FIRST));
+  return kan;
 }
 
 // KAN on the own turn; returns true for a concealed kan, false for a tile added to a pon (which can be robbed)
@@ -649,10 +663,12 @@ MJ_HD bool apply_own_kan(Ctx &c, int k)
 
 MJ_HD int act_of(uint32_t acts, int s) { return (int)(int8_t)(acts >> (8 * s)); }
 
-MJ_HD void mark_passed_ron(Ctx &c)
+// seats (bit set in ron_offered) that were offered a win and let it go are furiten
+MJ_HD void mark_passed_ron(Ctx &c, int ron_offered)
 {
+#pragma unroll
   for (int s = 0; s < 4; s++)
-    if ((c.g.actor_mask >> s & 1) && (MASK(c, s, 1) >> (A_RON - 64) & 1)) mark_furiten(c, s);
+    if (ron_offered >> s & 1) mark_furiten(c, s);
 }
 
 // One step of one environment, as a fixed sequence of stages that every lane walks through in the same order
@@ -676,21 +692,28 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
     c.live_word = c.e.wallw[(int64_t)(c.g.wall_sel * 34 + (c.g.draw_ptr >> 2)) * c.e.n];
     c.live_ptr = c.g.draw_ptr;
   }
-  // stage 0: an action outside the mask ends the game at once
+  // stage 0: an action outside the mask ends the game at once.  The eight mask words are read once, together.
   const int actors = c.g.actor_mask;
+  uint64_t mk0[4], mk1[4];
+#pragma unroll
+  for (int s = 0; s < 4; s++) { mk0[s] = MASK(c, s, 0); mk1[s] = MASK(c, s, 1); }
+  int illegal = 0, ron_offered = 0;
+#pragma unroll
   for (int s = 0; s < 4; s++) {
-    if (!(actors >> s & 1)) continue;
-    int x = act_of(acts, s);
-    bool ok = x >= 0 && x < N_ACTIONS && (MASK(c, s, x >> 6) >> (x & 63) & 1);
-    if (!ok) {
-      c.g.illegal_seat = (uint8_t)s;
-      clear_result(c);
-      c.g.end_type = 9;
-      c.g.terminated = 1;
-      c.g.phase = PH_TERMINAL;
-      clear_masks(c);
-      return;
-    }
+    const int x = act_of(acts, s);
+    const uint64_t w = x < 64 ? mk0[s] : mk1[s];
+    const bool ok = x >= 0 && x < N_ACTIONS && (w >> (x & 63) & 1);
+    if ((actors >> s & 1) && !ok) illegal |= 1 << s;
+    if ((actors >> s & 1) && (mk1[s] >> (A_RON - 64) & 1)) ron_offered |= 1 << s;
+  }
+  if (illegal) {
+    c.g.illegal_seat = (uint8_t)__builtin_ctz((unsigned)illegal);
+    clear_result(c);
+    c.g.end_type = 9;
+    c.g.terminated = 1;
+    c.g.phase = PH_TERMINAL;
+    clear_masks(c);
+    return;
   }
   MJ_TICK(c, 1);
   // stage 1: apply
@@ -721,7 +744,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       if (popc32((uint32_t)ronners) == 3 && (c.R.flags & F_ABORT)) end_abort = 8;
       else if (ronners) { win_mask = ronners; win_loser = d; win_tile = code_kind(c.g.last_discard); }
       else {
-        mark_passed_ron(c);
+        mark_passed_ron(c, ron_offered);
         int caller = -1, call = 0;
         for (int s = 0; s < 4; s++) if ((actors >> s & 1) && act_of(acts, s) >= A_PON && act_of(acts, s) <= A_MINKAN) { caller = s; call = act_of(acts, s); }
         int nx = (d + 1) & 3;
@@ -735,7 +758,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       }
     } else {
       if (ronners) { win_mask = ronners; win_loser = c.g.cur; win_tile = code_kind(c.g.kakan_tile); win_rob = true; }
-      else { mark_passed_ron(c); kan_fin = true; }
+      else { mark_passed_ron(c, ron_offered); kan_fin = true; }
     }
   }
   clear_masks(c);
