@@ -13,6 +13,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
@@ -151,6 +153,24 @@ def main():
             del obs
         except Exception as ex:                                  # reported, never hidden
             extras["obs_error"] = repr(ex)
+        # configs[1]: 2^20 seeded hand evaluations (yaku / han / fu / points), records resident on the device
+        try:
+            from workloads import hands
+            q = hands.generate(1 << 20, mj.QUERY_DTYPE, seed=0)
+            env = mj.MahjongEnv(64, seed=0, flags=mj.RULES_RED, mode=mj.MODE_HALF)
+            dq = torch.from_numpy(q.view(np.uint8).reshape(q.size, -1)).to("cuda:0")
+            dr = torch.empty((q.size, mj.RESULT_DTYPE.itemsize), dtype=torch.uint8, device="cuda:0")
+            for _ in range(3):
+                env.eval_hands_device(dq, dr)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                env.eval_hands_device(dq, dr)
+            torch.cuda.synchronize()
+            extras["hand_evaluations_per_s"] = q.size * 20 / (time.perf_counter() - t0)
+            env.close()
+        except Exception as ex:
+            extras["hands_error"] = repr(ex)
         out["extras"] = extras
 
     if not args.no_cpu:

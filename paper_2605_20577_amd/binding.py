@@ -287,6 +287,13 @@ class MahjongEnv:
             mj_eval_hands(self._h, q.size, dq, dr)
         return dr.cpu().numpy().view(RESULT_DTYPE).copy()
 
+    def eval_hands_device(self, dq, dr):
+        """same, on records already resident on the device: uint8 tensors holding n MjHandQuery / n MjHandResult"""
+        n = dq.numel() // QUERY_DTYPE.itemsize
+        assert dq.is_contiguous() and dr.is_contiguous() and dr.numel() >= n * RESULT_DTYPE.itemsize
+        with self._dev():
+            mj_eval_hands(self._h, n, dq, dr)
+
     @property
     def step_count(self):
         return int(lib().mj_step_count(self._h))

@@ -213,6 +213,11 @@ MJ_HD uint32_t pick4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, int su)
   uint32_t lo = (su & 1) ? a1 : a0, hi = (su & 1) ? a3 : a2;
   return (su & 2) ? hi : lo;
 }
+MJ_HD uint64_t pick4q(uint64_t a0, uint64_t a1, uint64_t a2, uint64_t a3, int su)
+{
+  uint64_t lo = (su & 1) ? a1 : a0, hi = (su & 1) ? a3 : a2;
+  return (su & 2) ? hi : lo;
+}
 MJ_HD int hand_count(const uint32_t h[4], int k) { int su = suit_of(k); return cnt3(pick4(h[0], h[1], h[2], h[3], su), rank_of(k, su)); }
 
 MJ_HD bool suit_valid(const Lut &L, int su, uint32_t w) { return su == 3 ? honors_valid(w) : lut_valid(L, w); }

@@ -508,14 +508,13 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   return ok;
 }
 
-// the calls (pon, open kan, chi) seat o may make on the tile just discarded by d
-MJ_HD void call_options(Ctx &c, int o, int d, int code, Mask2 &m)
+// the calls (pon, open kan, chi) seat o may make on the tile just discarded by d; sw is the seat's control word,
+// hw its counts in the suit of the tile
+MJ_HD void call_options(Ctx &c, int o, int d, int code, uint32_t sw, uint32_t hw, Mask2 &m)
 {
   int k = code_kind(code);
-  uint32_t sw = SW(c, o);
   if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0) {
     int su = suit_of(k), r = rank_of(k, su);
-    uint32_t hw = HW(c, o, su);
     int have = cnt3(hw, r);
     int total = 13 - 3 * (int)sw_get(sw, SW_NMELD, 3);      // a seat that is not on turn holds exactly this many
     bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
@@ -778,15 +777,22 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   MJ_TICK(c, 3);
   // stage 3: responses of the other seats
   if (respond || rob) {
-    int from = respond ? c.g.last_discarder : c.g.cur;
-    int code = respond ? c.g.last_discard : c.g.kakan_tile;
+    const int from = respond ? c.g.last_discarder : c.g.cur;
+    const int code = respond ? c.g.last_discard : c.g.kakan_tile;
+    const int k = code_kind(code), su = suit_of(k);
+    // what the three seats' options depend on, read together
+    uint32_t sws[4], hws[4];
+    uint64_t wts[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) { sws[t] = SW(c, t); hws[t] = HW(c, t, su); wts[t] = WAITS(c, t); }
     int any = 0;
 #pragma unroll 1
     for (int j = 1; j < 4; j++) {            // one copy of the code for the three seats (one evaluation site)
       const int o = (from + j) & 3;
       Mask2 m = {0, 0};
-      if (ron_option(c, o, code_kind(code), rob)) set_action(m, A_RON);
-      if (respond) call_options(c, o, from, code, m);
+      if ((pick4q(wts[0], wts[1], wts[2], wts[3], o) >> k & 1) && ron_option(c, o, k, rob)) set_action(m, A_RON);
+      if (respond)
+        call_options(c, o, from, code, pick4(sws[0], sws[1], sws[2], sws[3], o), pick4(hws[0], hws[1], hws[2], hws[3], o), m);
       if (m.w0 | m.w1) { set_action(m, A_PASS); any |= 1 << o; MASK(c, o, 0) = m.w0; MASK(c, o, 1) = m.w1; }
     }
     if (any) {

@@ -98,6 +98,22 @@ def test_fused_rollout_many_games():
     assert np.array_equal(o.observe(), g.observe())
 
 
+@pytest.mark.parametrize("flags,lpw,seed", [(mjo.RULES_NORED, 32, 3), (mjo.RULES_RED, 64, 4)])
+def test_fused_rollout_large(flags, lpw, seed, monkeypatch):
+    """16,384 games x 1,600 fused steps (more than a full hanchan each, so the rare paths are walked many times: wins of every
+    kind, kans, robbed kans, abortive draws, busts, game ends), every field and the observation against the
+    oracle, which runs as sixteen shards on the host cores"""
+    from tests.engines import oracle_rollout_sharded
+    monkeypatch.setenv("MJ_LPW", str(lpw))
+    B, steps = 16384, 1600
+    g = GpuEngine(B, seed=seed, flags=flags, mode=mjo.MODE_HALF)
+    g.step_random(steps)
+    eo, oo = oracle_rollout_sharded(B, seed, flags, mjo.MODE_HALF, steps)
+    d = diff_records(eo, g.export())
+    assert not d, d[:4]
+    assert np.array_equal(oo, g.observe())
+
+
 @pytest.mark.parametrize("lpw", [16, 32, 64])
 def test_every_lanes_per_wave_variant(lpw, monkeypatch):
     """the step kernels exist in three variants (16 / 32 / 64 environments per wavefront); the library picks one
