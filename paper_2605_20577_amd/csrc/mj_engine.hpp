@@ -827,8 +827,16 @@ MJ_HD int sample_action(uint64_t m0, uint64_t m1, uint32_t seed, uint32_t env_id
   int n0 = popc64(m0);
   uint64_t m = m0; int base = 0;
   if (pick >= n0) { pick -= n0; m = m1; base = 64; }
-  for (int i = 0; i < pick; i++) m &= m - 1;
-  return base + ctz64(m);
+  // position of the pick-th set bit of m by halving (no loop whose length depends on the lane)
+  uint32_t w = (uint32_t)m;
+  int c = popc32(w);
+  if (pick >= c) { pick -= c; w = (uint32_t)(m >> 32); base += 32; }
+#pragma unroll
+  for (int half = 16; half >= 1; half >>= 1) {
+    c = popc32(w & ((1u << half) - 1u));
+    if (pick >= c) { pick -= c; w >>= half; base += half; }
+  }
+  return base;
 }
 
 }  // namespace mj

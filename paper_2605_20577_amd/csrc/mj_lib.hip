@@ -42,7 +42,7 @@ constexpr int kLutBytes = 64;            // the block's copy of the table pointe
 #ifndef MJ_OCC
 #define MJ_OCC 2                         // waves per SIMD the register budget of the stepping kernels is sized for
 #endif
-constexpr int kRefillEvery = 32;         // steps between refills of the walls made ahead of time
+constexpr int kRefillEvery = 64;         // steps between refills of the walls made ahead of time
 
 // A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
 // occupies 2x or 4x as many wavefronts, which lets a SIMD overlap the LDS / memory latency of one wavefront
