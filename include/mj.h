@@ -165,6 +165,13 @@ int mj_observe(const MjHandle *h, uint8_t *d_obs /*[B][4][56][34]*/, void *strea
 int mj_reward(const MjHandle *h, int32_t *d_delta /*[B][4]*/, float *d_reward /*[B][4]*/,
               uint8_t *d_terminated /*[B]*/, void *stream);
 
+/* standings (section 4.2 evaluates agents by their average rank over whole
+ * games): current points per seat and, for a terminated env, each seat's final
+ * rank 0..3 (0 = first; equal points: the lower seat number is ahead).  Ranks of
+ * an env that has not terminated are those of its previous game.  Either
+ * pointer may be NULL. */
+int mj_standings(const MjHandle *h, int32_t *d_score /*[B][4]*/, uint8_t *d_rank /*[B][4]*/, void *stream);
+
 /* auto-reset: every terminated env starts a new game (episode + 1, a new wall
  * with kyoku_serial + 1, start_score points, East-1). */
 int mj_reset_done(MjHandle *h, void *stream);

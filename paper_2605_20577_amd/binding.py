@@ -62,6 +62,7 @@ EXPORTS = {
     "mj_legal_mask": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_observe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_reward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mj_standings": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_reset_done": (C.c_int, [C.c_void_p, C.c_void_p]),
     "mj_sample_random": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_step_random": (C.c_int, [C.c_void_p, C.c_int32, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
@@ -138,6 +139,10 @@ def mj_legal_mask(h, mask):
 
 def mj_observe(h, obs):
     _check(lib().mj_observe(h, _ptr(obs), _stream()))
+
+
+def mj_standings(h, score, rank):
+    _check(lib().mj_standings(h, _ptr(score), _ptr(rank), _stream()))
 
 
 def mj_reward(h, delta, reward, terminated):
@@ -236,6 +241,15 @@ class MahjongEnv:
         with self._dev():
             mj_reward(self._h, d, r, t)
         return d, r, t
+
+    def standings(self):
+        """(points int32 [B,4], final rank uint8 [B,4]: 0 = first, meaningful for terminated games)"""
+        torch = self.torch
+        sc = torch.empty((self.B, 4), dtype=torch.int32, device=self.device)
+        rk = torch.empty((self.B, 4), dtype=torch.uint8, device=self.device)
+        with self._dev():
+            mj_standings(self._h, sc, rk)
+        return sc, rk
 
     def reset_done(self):
         with self._dev():

@@ -495,6 +495,20 @@ __global__ void __launch_bounds__(kAuxBlock) k_reward(void *state, int64_t B, fl
   if (terminated) terminated[b] = g.terminated;
 }
 
+__global__ void __launch_bounds__(kAuxBlock) k_standings(void *state, int64_t B, int32_t *score, uint8_t *rank)
+{
+  int64_t b = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
+  if (b >= B) return;
+  Env e = make_env(state, B, b);
+  if (score) ((int4 *)score)[b] = make_int4(e.score[0], e.score[B], e.score[2 * B], e.score[3 * B]);
+  if (rank) {
+    uint32_t r = 0;
+#pragma unroll
+    for (int s = 0; s < 4; s++) r |= sw_get(e.seatw[s * B], SW_RANK, 2) << (8 * s);
+    ((uint32_t *)rank)[b] = r;
+  }
+}
+
 __global__ void __launch_bounds__(kAuxBlock) k_export(void *state, int64_t B, int64_t lo, int64_t n, MjEnvCanon *out)
 {
   int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
@@ -800,6 +814,14 @@ int mj_reward(const MjHandle *h, int32_t *d_delta, float *d_reward, uint8_t *d_t
   if (!h || ((uintptr_t)d_delta & 15) || ((uintptr_t)d_reward & 15)) return MJ_E_ARG;
   k_reward<<<blocks_for(h->B), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.illegal_penalty, d_delta, d_reward,
                                                                  d_terminated);
+  return check(hipGetLastError());
+}
+
+int mj_standings(const MjHandle *h, int32_t *d_score, uint8_t *d_rank, void *stream)
+{
+  if (!h || ((uintptr_t)d_score & 15) || ((uintptr_t)d_rank & 3)) return MJ_E_ARG;
+  if (h->B == 0) return MJ_OK;
+  k_standings<<<blocks_for(h->B), kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, d_score, d_rank);
   return check(hipGetLastError());
 }
 

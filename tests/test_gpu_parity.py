@@ -201,3 +201,58 @@ def test_hand_microbatch_full_size():
     # edge cases: empty batch, ragged tail
     assert g.eval_hands(q[:0]).size == 0
     assert g.eval_hands(q[:257]).tobytes() == ro[:257].tobytes()
+
+
+def test_standings_match_the_records():
+    B = 600
+    o = mjo.Oracle(B, 5, mjo.RULES_RED, mjo.MODE_EAST)
+    g = GpuEngine(B, seed=5, flags=mjo.RULES_RED, mode=mjo.MODE_EAST)
+    o.step_random(700, auto_reset=False); g.step_random(700, auto_reset=False)
+    eo = o.export()
+    assert eo["terminated"].sum() > B // 2                       # most east games are over by now
+    score, rank = g.env.standings()
+    assert np.array_equal(score.cpu().numpy(), eo["score"])
+    assert np.array_equal(rank.cpu().numpy(), eo["final_rank"])
+
+
+def _oracle_play(o, policies, n_games):
+    """tests' restatement of arena.play on the oracle, in numpy"""
+    B = o.B
+    rank_count = np.zeros((4, 4), dtype=np.int64)
+    done = steps = 0
+    while done < n_games:
+        words = o.legal_mask().reshape(B, 4, 2)
+        bits = ((words[..., None] >> np.arange(64, dtype=np.uint64)) & np.uint64(1)).astype(bool).reshape(B, 4, 128)[:, :, :85]
+        actions = np.full((B, 4), -1, dtype=np.int8)
+        for s, pol in enumerate(policies):
+            a = pol(bits[:, s])
+            acts = bits[:, s].any(axis=1)
+            actions[acts, s] = a[acts]
+        o.step(actions)
+        steps += 1
+        term = o.reward()[2]
+        idx = np.flatnonzero(term)[: n_games - done]
+        if idx.size:
+            r = o.export()["final_rank"][idx]
+            for s in range(4):
+                rank_count[s] += np.bincount(r[:, s], minlength=4)
+            done += idx.size
+            o.reset_done()
+    return rank_count, steps
+
+
+def test_one_vs_three_evaluation_matches_the_oracle():
+    """section 4.2's protocol (one agent against three fixed opponents, rated by average rank) with two
+    deterministic policies: the harness on the HIP library and the same loop on the oracle see the same games"""
+    from paper_2605_20577_amd import arena
+    B, n_games = 96, 150
+    g = GpuEngine(B, seed=9, flags=mjo.RULES_RED, mode=mjo.MODE_EAST)
+    res = arena.one_vs_three(g.env, arena.highest_legal, arena.lowest_legal, n_games)
+    o = mjo.Oracle(B, 9, mjo.RULES_RED, mjo.MODE_EAST)
+    hi = lambda m: 84 - np.argmax(m[:, ::-1], axis=1)
+    lo = lambda m: np.argmax(m, axis=1)
+    rank_count, steps = _oracle_play(o, [hi, lo, lo, lo], n_games)
+    assert res["games"] == n_games and res["steps"] == steps
+    assert np.array_equal(np.array(res["rank_count"]), rank_count)
+    assert abs(sum(res["mean_rank"]) - 10.0) < 1e-9               # ranks 1..4 are shared out in every game
+    assert not diff_records(o.export(), g.export())
