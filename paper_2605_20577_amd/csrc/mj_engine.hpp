@@ -508,42 +508,51 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   return ok;
 }
 
-// the calls (pon, open kan, chi) seat o may make on the tile just discarded by d; sw is the seat's control word,
-// hw its counts in the suit of the tile
-MJ_HD void call_options(Ctx &c, int o, int d, int code, uint32_t sw, uint32_t hw, Mask2 &m)
+// Responses live in word 1 of a mask (actions 74..84 are its bits 10..20), so a seat's options are one 32-bit value.
+constexpr uint32_t R_BIT(int a) { return 1u << (a - 64); }
+// pon / open kan of kind (su, r) by a seat with control word sw and counts hw in that suit
+MJ_HD uint32_t pon_kan_options(const Ctx &c, int su, int r, uint32_t sw, uint32_t hw)
 {
-  int k = code_kind(code);
+  uint32_t m = 0;
   if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0) {
-    int su = suit_of(k), r = rank_of(k, su);
-    int have = cnt3(hw, r);
-    int total = 13 - 3 * (int)sw_get(sw, SW_NMELD, 3);      // a seat that is not on turn holds exactly this many
-    bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
-    int nonred = have - (red_held ? 1 : 0);
+    const int have = cnt3(hw, r);
+    const int total = 13 - 3 * (int)sw_get(sw, SW_NMELD, 3);      // a seat that is not on turn holds exactly this many
+    const bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
+    const int nonred = have - (red_held ? 1 : 0);
     if (total - have > 0) {
-      if (nonred >= 2) set_action(m, A_PON);
-      if (red_held && nonred >= 1) set_action(m, A_PON_RED);
+      if (nonred >= 2) m |= R_BIT(A_PON);
+      if (red_held && nonred >= 1) m |= R_BIT(A_PON_RED);
     }
-    if (have >= 3 && c.g.n_kan < 4) set_action(m, A_MINKAN);
-    if (o == ((d + 1) & 3) && su < 3) {
-      bool red_in_suit = sw >> su & 1u;
+    if (have >= 3 && c.g.n_kan < 4) m |= R_BIT(A_MINKAN);
+  }
+  return m;
+}
+// chi of rank r of a numbered suit by the next seat
+MJ_HD uint32_t chi_options(const Ctx &c, int su, int r, uint32_t sw, uint32_t hw)
+{
+  uint32_t m = 0;
+  if (!sw_get(sw, SW_RIICHI, 2) && c.g.live_left > 0 && su < 3) {
+    const int have = cnt3(hw, r);
+    const int total = 13 - 3 * (int)sw_get(sw, SW_NMELD, 3);
+    const bool red_in_suit = sw >> su & 1u;
 #pragma unroll
-      for (int pos = 0; pos < 3; pos++) {
-        int lo = r - pos;
-        if (lo < 0 || lo > 6) continue;
-        int ra = pos == 0 ? lo + 1 : lo, rb = pos == 2 ? lo + 1 : lo + 2;       // the two ranks taken from the hand
-        int ca = cnt3(hw, ra), cb = cnt3(hw, rb);
-        if (ca == 0 || cb == 0) continue;
-        int extra = 0;
-        if (pos == 0 && r + 3 <= 8) extra = cnt3(hw, r + 3);
-        if (pos == 2 && r - 3 >= 0) extra = cnt3(hw, r - 3);
-        if (total - 2 - have - extra <= 0) continue;
-        bool five_used = ra == 4 || rb == 4;
-        int na = ca - ((ra == 4 && red_in_suit) ? 1 : 0), nb = cb - ((rb == 4 && red_in_suit) ? 1 : 0);
-        if (na >= 1 && nb >= 1) set_action(m, A_CHI_L + pos);
-        if (five_used && red_in_suit) set_action(m, A_CHI_L_RED + pos);
-      }
+    for (int pos = 0; pos < 3; pos++) {
+      int lo = r - pos;
+      if (lo < 0 || lo > 6) continue;
+      int ra = pos == 0 ? lo + 1 : lo, rb = pos == 2 ? lo + 1 : lo + 2;       // the two ranks taken from the hand
+      int ca = cnt3(hw, ra), cb = cnt3(hw, rb);
+      if (ca == 0 || cb == 0) continue;
+      int extra = 0;
+      if (pos == 0 && r + 3 <= 8) extra = cnt3(hw, r + 3);
+      if (pos == 2 && r - 3 >= 0) extra = cnt3(hw, r - 3);
+      if (total - 2 - have - extra <= 0) continue;
+      bool five_used = ra == 4 || rb == 4;
+      int na = ca - ((ra == 4 && red_in_suit) ? 1 : 0), nb = cb - ((rb == 4 && red_in_suit) ? 1 : 0);
+      if (na >= 1 && nb >= 1) m |= R_BIT(A_CHI_L) << pos;
+      if (five_used && red_in_suit) m |= R_BIT(A_CHI_L_RED) << pos;
     }
   }
+  return m;
 }
 
 // seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later
@@ -785,15 +794,33 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
     uint64_t wts[4];
 #pragma unroll
     for (int t = 0; t < 4; t++) { sws[t] = SW(c, t); hws[t] = HW(c, t, su); wts[t] = WAITS(c, t); }
-    int any = 0;
-#pragma unroll 1
-    for (int j = 1; j < 4; j++) {            // one copy of the code for the three seats (one evaluation site)
+    const int r = rank_of(k, su);
+    // pon / kan and "the tile is one of my waits" for each seat in place (no selection by seat number), ...
+    uint32_t opt[4], hit = 0;
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      const bool other = t != from;
+      opt[t] = (respond && other) ? pon_kan_options(c, su, r, sws[t], hws[t]) : 0u;
+      if (other && (wts[t] >> k & 1)) hit |= 1u << t;
+    }
+    // ... chi once, for the next seat, ...
+    if (respond) {
+      const int nx = (from + 1) & 3;
+      const uint32_t copt = chi_options(c, su, r, pick4(sws[0], sws[1], sws[2], sws[3], nx), pick4(hws[0], hws[1], hws[2], hws[3], nx));
+#pragma unroll
+      for (int t = 0; t < 4; t++) if (t == nx) opt[t] |= copt;
+    }
+    // ... and the wins: one evaluation site in a loop over the (rare) seats that wait on the tile, in turn order
+    uint32_t ron = 0;
+    for (int j = 1; j < 4 && hit; j++) {
       const int o = (from + j) & 3;
-      Mask2 m = {0, 0};
-      if ((pick4q(wts[0], wts[1], wts[2], wts[3], o) >> k & 1) && ron_option(c, o, k, rob)) set_action(m, A_RON);
-      if (respond)
-        call_options(c, o, from, code, pick4(sws[0], sws[1], sws[2], sws[3], o), pick4(hws[0], hws[1], hws[2], hws[3], o), m);
-      if (m.w0 | m.w1) { set_action(m, A_PASS); any |= 1 << o; MASK(c, o, 0) = m.w0; MASK(c, o, 1) = m.w1; }
+      if ((hit >> o & 1) && ron_option(c, o, k, rob)) ron |= 1u << o;
+    }
+    int any = 0;
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      if (ron >> t & 1) opt[t] |= R_BIT(A_RON);
+      if (opt[t]) { any |= 1 << t; MASK(c, t, 1) = opt[t] | R_BIT(A_PASS); }      // word 0 is clear already
     }
     if (any) {
       c.g.phase = respond ? PH_RESPOND : PH_RESPOND_KAKAN;
