@@ -20,7 +20,7 @@ namespace mj {
 
 struct Ctx {
   Env e;
-  const Lut *L;
+  Lut L;               // table pointers, by value (see BlockMem)
   Rules R;
   Glob g;
   uint32_t env_id;
@@ -73,7 +73,7 @@ MJ_HD bool is_red_id(const Ctx &c, int id) { return (c.R.flags & F_RED) && (id =
 
 MJ_HD void refresh_waits(Ctx &c, int s)
 {
-  WAITS(c, s) = waits_of(c.L, HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3), MELDW(c, s), swf(c, s, SW_NMELD, 3));
+  WAITS(c, s) = waits_of(&c.L, HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3), MELDW(c, s), swf(c, s, SW_NMELD, 3));
 }
 MJ_HD int take_tile(Ctx &c, int s, int id)
 {
@@ -133,7 +133,7 @@ MJ_HD void eval_seat(Ctx &c, int s, int w, bool tsumo, bool chankan, HandOut &ou
   if (chankan && code_red(c.g.kakan_tile)) aka++;
   q.n_aka = aka;
   q.kuitan = (c.R.flags & F_KUITAN) ? 1 : 0;
-  eval_hand(c.L, q, out);
+  eval_hand(&c.L, q, out);
 }
 
 MJ_HD bool furiten(Ctx &c, int s)
@@ -195,7 +195,7 @@ MJ_HD void turn_mask(Ctx &c)
   for (int j = 0; j < n_meld; j++) if (m_type(meld_at(mw, j)) != MT_ANKAN) menzen = false;
   const bool may_riichi = !c.g.riichi_pending && !riichi && drawn_k >= 0 && menzen && SCORE(c, s) >= 1000 && c.g.live_left >= 4;
   uint64_t td = 0;
-  if (!riichi) td = tenpai_discards_of(c.L, h[0], h[1], h[2], h[3], mw, n_meld, may_riichi || c.g.riichi_pending);
+  if (!riichi) td = tenpai_discards_of(&c.L, h[0], h[1], h[2], h[3], mw, n_meld, may_riichi || c.g.riichi_pending);
   TD(c) = (td & TD_UNKNOWN) ? 0 : td | TD_VALID;        // the set itself is only searched for when the mask needs it
   MJ_TICK(c, 14);
   if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
@@ -213,7 +213,7 @@ MJ_HD void turn_mask(Ctx &c)
       const int su = suit_of(drawn_k);
       const uint32_t four = 4u << (3 * rank_of(drawn_k, su));
       const uint64_t mw2 = mw | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
-      if (waits_of(c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
+      if (waits_of(&c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
                    h[3] - (su == 3 ? four : 0u), mw2, n_meld + 1) == waits)
         set_action(m, A_KAN + drawn_k);
     }

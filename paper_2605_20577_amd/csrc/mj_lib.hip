@@ -38,7 +38,6 @@ struct DevTables {
   int probe_bytes;                       // multiple of 16
 };
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
-constexpr int kLutBytes = 64;            // the block's copy of the table pointers
 #ifndef MJ_OCC
 #define MJ_OCC 2                         // waves per SIMD the register budget of the stepping kernels is sized for
 #endif
@@ -52,12 +51,12 @@ constexpr int kRefillEvery = 64;         // steps between refills of the walls m
 __host__ __device__ inline int envs_per_block(int lpw) { return (kBlock / 64) * lpw; }
 __host__ __device__ inline size_t step_lds_bytes(int probe_bytes, int lpw)
 {
-  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * (kHotBytesPerEnv + 136) + kLutBytes;
+  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * (kHotBytesPerEnv + 136);
 }
 
-static_assert(sizeof(Lut) <= kLutBytes, "table pointer block");
 struct BlockMem {
-  const Lut *L;                          // in LDS
+  Lut L;                                 // table pointers: the probe tables in LDS, the records in HBM.  Held by value
+                                         // (in registers) so that the probes compile to LDS reads, not flat loads.
   uint64_t *hq;                          // [kHotU64][envs per block]
   uint32_t *hw;                          // [kHotU32][envs per block]
   uint8_t *col;                          // this lane's column of the [136][envs per block] shuffle area
@@ -78,14 +77,10 @@ __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds
   m.lane_on = (threadIdx.x & 63) < LPW;
   m.hq = (uint64_t *)(lds + T.probe_bytes);
   m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)m.epb * 8 * kHotU64);
-  Lut *L = (Lut *)(lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv);
-  if (threadIdx.x == 0) {
-    L->rowid = lds;
-    L->bitmap = (const uint32_t *)(lds + kRowIdBytes);
-    L->base = T.base; L->rowrank = T.rowrank; L->keyinfo = T.keyinfo; L->recs = T.recs;
-  }
-  m.L = L;
-  m.col = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + kLutBytes + m.idx;
+  m.L.rowid = lds;
+  m.L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
+  m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.keyinfo = T.keyinfo; m.L.recs = T.recs;
+  m.col = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + m.idx;
   __syncthreads();
   return m;
 }
@@ -194,7 +189,7 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_
       const int j = (lane - dealer) & 3;
       const uint32_t h0 = pick4(hw[0][0], hw[1][0], hw[2][0], hw[3][0], j), h1 = pick4(hw[0][1], hw[1][1], hw[2][1], hw[3][1], j);
       const uint32_t h2 = pick4(hw[0][2], hw[1][2], hw[2][2], hw[3][2], j), h3 = pick4(hw[0][3], hw[1][3], hw[2][3], hw[3][3], j);
-      wt = waits_of(c.L, h0, h1, h2, h3, 0, 0);
+      wt = waits_of(&c.L, h0, h1, h2, h3, 0, 0);
     }
     const uint32_t wt_lo = (uint32_t)wt, wt_hi = (uint32_t)(wt >> 32);
     uint64_t w4[4];
@@ -264,7 +259,7 @@ __device__ __forceinline__ void refill_next_wall(Ctx &c, uint8_t *col, int strid
     const uint32_t h2 = (uint32_t)(lo >> 54) | ((uint32_t)hi & 0x3FFFFu) << 9, h3 = (uint32_t)(hi >> 18);
     c.e.nexth[(int64_t)(4 * j) * c.e.n] = h0; c.e.nexth[(int64_t)(4 * j + 1) * c.e.n] = h1;
     c.e.nexth[(int64_t)(4 * j + 2) * c.e.n] = h2; c.e.nexth[(int64_t)(4 * j + 3) * c.e.n] = h3;
-    c.e.nextwaits[(int64_t)j * c.e.n] = waits_of(c.L, h0, h1, h2, h3, 0, 0);
+    c.e.nextwaits[(int64_t)j * c.e.n] = waits_of(&c.L, h0, h1, h2, h3, 0, 0);
   }
   c.e.nextred[0] = reds;
   c.e.nserial[0] = target_serial;
@@ -534,13 +529,10 @@ __global__ void __launch_bounds__(kAuxBlock, MJ_OCC) k_eval_hands(DevTables T, i
     for (int j = threadIdx.x; j < T.probe_bytes / 16; j += blockDim.x) dst[j] = src[j];
     __syncthreads();
   }
-  __shared__ Lut Ls;
-  if (threadIdx.x == 0) {
-    Ls.rowid = lds; Ls.bitmap = (const uint32_t *)(lds + kRowIdBytes);
-    Ls.base = T.base; Ls.rowrank = T.rowrank; Ls.keyinfo = T.keyinfo; Ls.recs = T.recs;
-  }
-  __syncthreads();
-  const Lut *L = &Ls;
+  Lut Lv;
+  Lv.rowid = lds; Lv.bitmap = (const uint32_t *)(lds + kRowIdBytes);
+  Lv.base = T.base; Lv.rowrank = T.rowrank; Lv.keyinfo = T.keyinfo; Lv.recs = T.recs;
+  const Lut *L = &Lv;
   int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (i >= n) return;
   const uint32_t *qw = (const uint32_t *)(in + i);

@@ -30,7 +30,7 @@ static Ctx ctx_of(Sim *h, int64_t b)
 {
   Ctx c;
   c.e = make_env(h->state.data(), h->B, b);
-  c.L = &h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
+  c.L = h->L; c.R = h->R; c.env_id = h->R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   return c;
 }
