@@ -18,6 +18,14 @@ namespace mj {
 #define MJ_TICK(c, i) ((void)0)
 #endif
 
+// pins a per-lane value in a vector register at this point (otherwise the compiler turns bit tests of it back into
+// booleans that each occupy a scalar register pair for as long as they live)
+#ifdef __HIP_DEVICE_COMPILE__
+#define MJ_KEEP_IN_VGPR(x) asm volatile("" : "+v"(x))
+#else
+#define MJ_KEEP_IN_VGPR(x) ((void)0)
+#endif
+
 struct Ctx {
   Env e;
   Lut L;               // table pointers, by value (see BlockMem)
@@ -726,7 +734,10 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   MJ_TICK(c, 1);
   // stage 1: apply
   int waits_seat = -1, waits_k = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
-  bool respond = false, rob = false, advance = false, kan_fin = false, win_tsumo = false, win_rob = false;
+  // what the later stages have to do, as bits of one per-lane word (six separate booleans would each live in a
+  // scalar register pair across the stages)
+  enum : uint32_t { DO_RESPOND = 1, DO_ROB = 2, DO_ADVANCE = 4, DO_KANFIN = 8, WIN_TSUMO = 16, WIN_ROB = 32 };
+  uint32_t todo = 0;
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
     if (act < A_KAN) {
@@ -734,15 +745,15 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       // a seat in riichi gives back the drawn tile: its waits stay; any other seat's waits follow from the discard
       if (!sw_get(SW(c, s), SW_RIICHI, 2)) { waits_seat = s; waits_k = k; }
       apply_discard(c, s, k, act < A_DISCARD_RED ? 0 : 1);
-      respond = true;
+      todo |= DO_RESPOND;
     } else if (act < A_RIICHI) {
-      if (apply_own_kan(c, act - A_KAN)) kan_fin = true; else rob = true;
+      todo |= apply_own_kan(c, act - A_KAN) ? DO_KANFIN : DO_ROB;
       waits_seat = s;
     } else if (act == A_RIICHI) {
       c.g.riichi_pending = (SW(c, s) >> SW_FIRST & 1) ? 2 : 1;
       c.need_turn = true;
     } else if (act == A_TSUMO) {
-      win_mask = 1 << s; win_tsumo = true; win_tile = code_kind(c.g.drawn);
+      win_mask = 1 << s; todo |= WIN_TSUMO; win_tile = code_kind(c.g.drawn);
     } else end_abort = 4;
   } else {
     int ronners = 0;
@@ -759,14 +770,14 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
         if (caller < 0 && (actors >> nx & 1) && act_of(acts, nx) >= A_CHI_L && act_of(acts, nx) < A_PASS) { caller = nx; call = act_of(acts, nx); }
         end_abort = settle_discard(c);
         if (!end_abort) {
-          if (caller < 0) advance = true;
-          else if (apply_call(c, caller, call)) { waits_seat = caller; kan_fin = true; }
+          if (caller < 0) todo |= DO_ADVANCE;
+          else if (apply_call(c, caller, call)) { waits_seat = caller; todo |= DO_KANFIN; }
           else c.need_turn = true;
         }
       }
     } else {
-      if (ronners) { win_mask = ronners; win_loser = c.g.cur; win_tile = code_kind(c.g.kakan_tile); win_rob = true; }
-      else { mark_passed_ron(c, ron_offered); kan_fin = true; }
+      if (ronners) { win_mask = ronners; win_loser = c.g.cur; win_tile = code_kind(c.g.kakan_tile); todo |= WIN_ROB; }
+      else { mark_passed_ron(c, ron_offered); todo |= DO_KANFIN; }
     }
   }
   clear_masks(c);
@@ -785,7 +796,9 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   }
   MJ_TICK(c, 3);
   // stage 3: responses of the other seats
-  if (respond || rob) {
+  MJ_KEEP_IN_VGPR(todo);
+  if (todo & (DO_RESPOND | DO_ROB)) {
+    const bool respond = todo & DO_RESPOND, rob = todo & DO_ROB;
     const int from = respond ? c.g.last_discarder : c.g.cur;
     const int code = respond ? c.g.last_discard : c.g.kakan_tile;
     const int k = code_kind(code), su = suit_of(k);
@@ -827,20 +840,22 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
       c.g.actor_mask = (uint8_t)any;
     } else if (respond) {
       end_abort = settle_discard(c);
-      if (!end_abort) advance = true;
-    } else kan_fin = true;
+      if (!end_abort) todo |= DO_ADVANCE;
+    } else todo |= DO_KANFIN;
   }
   MJ_TICK(c, 4);
   bool exhaust = false;
-  if (advance && c.g.live_left == 0) { exhaust = true; advance = false; }
+  MJ_KEEP_IN_VGPR(todo);
+  if ((todo & DO_ADVANCE) && c.g.live_left == 0) { exhaust = true; todo &= ~DO_ADVANCE; }
   // stage 4: the kyoku ends
-  if (win_mask) win(c, win_mask, win_tsumo, win_loser, win_tile, win_rob);
+  if (win_mask) win(c, win_mask, (todo & WIN_TSUMO) != 0, win_loser, win_tile, (todo & WIN_ROB) != 0);
   else if (end_abort) abortive_draw(c, end_abort);
   else if (exhaust) exhaustive_draw(c);
   MJ_TICK(c, 5);
   // stage 5: draws
-  if (advance) { draw_live(c, (c.g.last_discarder + 1) & 3); c.need_turn = true; }
-  if (kan_fin) { kan_draw(c); c.need_turn = true; }
+  MJ_KEEP_IN_VGPR(todo);
+  if (todo & DO_ADVANCE) { draw_live(c, (c.g.last_discarder + 1) & 3); c.need_turn = true; }
+  if (todo & DO_KANFIN) { kan_draw(c); c.need_turn = true; }
 }
 
 // uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)
