@@ -404,6 +404,10 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
 #endif
   for (int t = 0; t < n_steps; t++) {
     uint32_t acts = 0;
+    // The stride of the cold arrays is made opaque once per step: otherwise every address "array + k * stride" is
+    // computed before the loop and kept in a register pair for the whole launch (dozens of pairs, many of them
+    // spilled to scratch memory and fetched back one by one on the rare paths that use them).
+    { int64_t stride = c.e.n; asm volatile("" : "+s"(stride)); c.e.n = stride; }
     if (active) {
       if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
         refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
