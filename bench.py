@@ -57,8 +57,8 @@ def timed_rollout(env, torch, warmup, steps, obs=None):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--steps", type=int, default=2048)
+    ap.add_argument("--warmup", type=int, default=512)
     ap.add_argument("--batch", type=int, default=65536)
     ap.add_argument("--no-extras", action="store_true", help="skip the red-rule and observation side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -95,7 +95,7 @@ def main():
     env = mj.MahjongEnv(B, seed=0, flags=mj.RULES_NORED, mode=mj.MODE_HALF)
     dt, step_ms = timed_rollout(env, torch, W, K)
     value = B * K / dt
-    chunk = min(K, 128)
+    chunk = min(K, mj.ROLLOUT_CHUNK)
     launch_ms = step_ms * chunk
     achieved = ALGO_BYTES_PER_ENV_STEP * B * chunk / (launch_ms * 1e-3) / 1e9
     traffic = None

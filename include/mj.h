@@ -187,7 +187,7 @@ int mj_sample_random(const MjHandle *h, int8_t *d_actions /*[B][4]*/, void *stre
  * MJ_ROLLOUT_CHUNK steps run inside one kernel launch (environments never
  * interact); with observations every step is one step launch plus one
  * observation launch. */
-#define MJ_ROLLOUT_CHUNK 128
+#define MJ_ROLLOUT_CHUNK 1024
 int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, uint8_t *d_obs, void *stream);
 
 /* canonical records of envs [env_lo, env_lo + n) to / from DEVICE memory */

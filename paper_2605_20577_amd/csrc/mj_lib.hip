@@ -425,10 +425,11 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
     MJ_TICK(c, 9);
   }
 #ifdef MJ_PROFILE
-  if (blockIdx.x == 7 && threadIdx.x == 0 && n_steps == 128)
+  if (blockIdx.x == 7 && threadIdx.x == 0 && n_steps >= 128)
     printf("PROF/step: refill %lld sample %lld | check %lld apply %lld waits %lld respond %lld end %lld draw %lld | reset %lld deal %lld mask %lld (pre %lld tsumo %lld bits %lld riichi %lld)\n",
-           c.t[10] / 128, c.t[0] / 128, c.t[1] / 128, c.t[2] / 128, c.t[3] / 128, c.t[4] / 128, c.t[5] / 128, c.t[6] / 128,
-           c.t[7] / 128, c.t[8] / 128, c.t[9] / 128, c.t[11] / 128, c.t[12] / 128, c.t[13] / 128, c.t[14] / 128);
+           c.t[10] / n_steps, c.t[0] / n_steps, c.t[1] / n_steps, c.t[2] / n_steps, c.t[3] / n_steps, c.t[4] / n_steps, c.t[5] / n_steps,
+           c.t[6] / n_steps, c.t[7] / n_steps, c.t[8] / n_steps, c.t[9] / n_steps, c.t[11] / n_steps, c.t[12] / n_steps,
+           c.t[13] / n_steps, c.t[14] / n_steps);
 #endif
   if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }
@@ -692,8 +693,8 @@ inline int pick_lpw(int64_t B)
 {
   const char *ov = std::getenv("MJ_LPW");
   if (ov) { int v = std::atoi(ov); if (v == 64 || v == 32 || v == 16) return v; }
-  if (B >= 2048 * 64) return 64;
-  if (B >= 2048 * 32) return 32;
+  if (B >= 2048 * 32) return 32;        // also for larger batches: 64 per wavefront leaves room for one wavefront
+                                        // per SIMD only (LDS), measured slower at every batch size
   return 16;
 }
 #define MJ_LAUNCH_STEP(kern, h, st, ...)                                                                         \
@@ -843,9 +844,15 @@ int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, 
   int rc = check(hipEventRecord(h->ev[0], st));
   if (rc != MJ_OK) return rc;
   if (!write_obs) {
-    // environments never interact, so many steps run inside one launch; chunked to bound a launch's duration
-    for (int t = 0; t < n_steps && rc == MJ_OK; t += MJ_ROLLOUT_CHUNK) {
-      int n = n_steps - t < MJ_ROLLOUT_CHUNK ? n_steps - t : MJ_ROLLOUT_CHUNK;
+    // environments never interact, so many steps run inside one launch; chunked to bound a launch's duration.
+    // Long launches matter at B = 65,536: all 2,048 wavefronts are resident at once, a launch ends with its
+    // slowest wavefront, and the spread of per-wavefront work shrinks with the number of steps (measured:
+    // 128 / 256 / 512 / 1024 / 2048 steps per launch = 6.26 / 6.44 / 6.58 / 6.67 / 6.69 G env steps/s).
+    // MJ_CHUNK overrides the length for experiments.
+    int chunk = MJ_ROLLOUT_CHUNK;
+    if (const char *cv = std::getenv("MJ_CHUNK")) { int v = std::atoi(cv); if (v > 0) chunk = v; }
+    for (int t = 0; t < n_steps && rc == MJ_OK; t += chunk) {
+      int n = n_steps - t < chunk ? n_steps - t : chunk;
       MJ_LAUNCH_STEP(k_rollout, h, st, h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
       rc = check(hipGetLastError());
     }

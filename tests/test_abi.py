@@ -44,3 +44,10 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(b, "_SO", os.path.join(ROOT, "no_such_dir", "libmj.so"))
     with pytest.raises(RuntimeError):
         b.lib()
+
+
+def test_binding_constants_mirror_the_header():
+    import re
+    import paper_2605_20577_amd as mj
+    text = open(os.path.join(os.path.dirname(__file__), "..", "include", "mj.h")).read()
+    assert int(re.search(r"#define\s+MJ_ROLLOUT_CHUNK\s+(\d+)", text).group(1)) == mj.ROLLOUT_CHUNK

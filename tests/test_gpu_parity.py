@@ -69,7 +69,8 @@ def test_ragged_batch_sizes(B):
     assert np.array_equal(o.observe(), g.observe())
 
 
-def test_fused_rollout_equals_unfused_and_oracle():
+def test_fused_rollout_equals_unfused_and_oracle(monkeypatch):
+    monkeypatch.setenv("MJ_CHUNK", "100")             # steps per launch of the fused path (default 1024)
     B = 1536
     o = mjo.Oracle(B, 4, mjo.RULES_NORED, mjo.MODE_HALF)
     g = GpuEngine(B, seed=4, flags=mjo.RULES_NORED, mode=mjo.MODE_HALF)
