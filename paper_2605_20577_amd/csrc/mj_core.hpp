@@ -57,8 +57,8 @@ struct Rules {
   uint32_t seed;
 };
 
-// the per-suit pattern table: probe part (LDS) and record part (global memory).  The out-of-line functions
-// receive a pointer to this struct (the kernels keep one copy per block in LDS).
+// the per-suit pattern table: probe part (LDS) and record part (global memory).  The kernels hold this struct by
+// value (in registers): after inlining, the probes then compile to LDS reads instead of generic-address loads.
 struct Lut {
   const uint8_t *rowid;      // [3125] row of a prefix
   const uint32_t *bitmap;    // [rows][20] valid suffixes of a row

@@ -116,7 +116,7 @@ __device__ __forceinline__ void store_hot(const BlockMem &m, void *state, int64_
 //   - the wall lives in ONE vector register, four tile ids per lane in lanes 0..33; the 135 swaps of the
 //     Fisher-Yates pass are readlane / select pairs on it (no memory in the loop);
 //   - lanes 0..33 store their word of the wall to HBM, the 4 x 13 tiles are accumulated into sixteen packed
-//     hand words with scalar arithmetic, lanes 0..3 compute the waits of the four hands with one call;
+//     hand words with scalar arithmetic, lanes 0..3 compute the waits of the four hands side by side;
 //   - the owner lane writes the results into its state and takes the dealer's first draw.
 __device__ __forceinline__ uint32_t set_byte(uint32_t w, int pos, uint32_t v) { return (w & ~(255u << (8 * pos))) | v << (8 * pos); }
 
