@@ -579,6 +579,7 @@ __global__ void __launch_bounds__(kAuxBlock, MJ_OCC) k_eval_hands(DevTables T, i
 //  3. all lanes expand bits to bytes, 16 bytes per store, consecutive lanes on consecutive addresses.
 constexpr int kObsEnvs = 32;             // 49 KB of LDS per block; 16 per block reached 3.9 TB/s, 32 reach 5.2 TB/s
 constexpr int kObsBits = 56 * 34;                 // 1904
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kObsWords = 60;                     // u32 words per (env, viewer), 1920 bits
 
 __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, uint32_t rule_flags, uint8_t *obs)
@@ -627,20 +628,19 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
     __syncthreads();
     // 7616 bytes per env = 476 stores of 16 bytes; 16 bytes = 16 bits of the string
     const int per_env = 4 * kObsBits / 16;
-    uint4 *dst = (uint4 *)(obs + (size_t)base * 4 * kObsBits);
+    u32x4 *dst = (u32x4 *)(obs + (size_t)base * 4 * kObsBits);
     for (int i = tid; i < nenv * per_env; i += kAuxBlock) {
       int el = i / per_env, j = i - el * per_env;          // j-th 16-byte group of env el
       int me = j / (kObsBits / 16), q = j - me * (kObsBits / 16);
       uint32_t word = bits[el][me][q >> 1];
       uint32_t v = (q & 1) ? word >> 16 : word & 0xFFFFu;
-      uint4 o;
+      u32x4 o;
       o.x = ((v & 0xFu) * 0x00204081u) & 0x01010101u;
       o.y = (((v >> 4) & 0xFu) * 0x00204081u) & 0x01010101u;
       o.z = (((v >> 8) & 0xFu) * 0x00204081u) & 0x01010101u;
       o.w = (((v >> 12) & 0xFu) * 0x00204081u) & 0x01010101u;
-      // streaming stores: the tensor is written once and not read back by this kernel (+30 % over plain stores)
-      __builtin_nontemporal_store(o.x, &dst[i].x); __builtin_nontemporal_store(o.y, &dst[i].y);
-      __builtin_nontemporal_store(o.z, &dst[i].z); __builtin_nontemporal_store(o.w, &dst[i].w);
+      // one 16-byte streaming store: the tensor is written once and not read back by this kernel
+      __builtin_nontemporal_store(o, &dst[i]);
     }
     __syncthreads();
   }
