@@ -203,8 +203,11 @@ int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandR
  * dealt again from it, without shuffling: hands, first draw, masks. */
 int mj_deal_from_wall(MjHandle *h, int64_t b, const uint8_t *d_wall /*[136]*/, void *stream);
 
-/* steps taken since mj_init */
+/* steps taken since mj_init, and its setter: the counter keys the random
+ * policy, so a run resumed from mj_export / mj_import records continues the
+ * same trajectory once the counter is restored as well (checkpoint / resume). */
 uint64_t mj_step_count(const MjHandle *h);
+int mj_set_step_count(MjHandle *h, uint64_t steps);
 /* timing aid for benchmarks: average duration in milliseconds of the step
  * kernels launched by the last mj_step_random call, measured with HIP events
  * on `stream`; synchronises the stream.  < 0 if nothing was recorded. */

@@ -72,6 +72,7 @@ EXPORTS = {
     "mj_eval_hands": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_deal_from_wall": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
     "mj_step_count": (C.c_uint64, [C.c_void_p]),
+    "mj_set_step_count": (C.c_int, [C.c_void_p, C.c_uint64]),
     "mj_last_step_kernel_ms": (C.c_float, [C.c_void_p]),
     "mj_destroy": (C.c_int, [C.c_void_p]),
 }
@@ -192,6 +193,7 @@ class MahjongEnv:
         self.B = int(B)
         self.device = torch.device(device)
         self.rules = MjRules(flags, env_id_base, start_score, illegal_penalty, mode)
+        self._seed = int(seed)
         with torch.cuda.device(self.device):
             self.state = torch.empty(mj_state_bytes(B, self.rules), dtype=torch.uint8, device=self.device)
             self.scratch = torch.empty(mj_scratch_bytes(B, self.rules), dtype=torch.uint8, device=self.device)
@@ -283,6 +285,25 @@ class MahjongEnv:
         with self._dev():
             mj_import(self._h, lo, e.size, buf)
             torch.cuda.current_stream().synchronize()
+
+    def save(self, path):
+        """checkpoint: the canonical records of every game, the step counter and the construction arguments
+        (numpy .npz).  restore() of it continues the same trajectory, random policy included."""
+        seed = int(self._seed)
+        np.savez_compressed(path, records=self.export(), step_count=np.uint64(self.step_count), B=np.int64(self.B),
+                            seed=np.uint64(seed), flags=np.uint32(self.rules.flags), mode=np.uint8(self.rules.mode),
+                            env_id_base=np.uint32(self.rules.env_id_base), start_score=np.int32(self.rules.start_score),
+                            illegal_penalty=np.float32(self.rules.illegal_penalty))
+
+    @classmethod
+    def restore(cls, path, device="cuda:0"):
+        z = np.load(path, allow_pickle=False)
+        env = cls(int(z["B"]), seed=int(z["seed"]), flags=int(z["flags"]), mode=int(z["mode"]),
+                  start_score=int(z["start_score"]), illegal_penalty=float(z["illegal_penalty"]),
+                  env_id_base=int(z["env_id_base"]), device=device)
+        env.import_(z["records"])
+        _check(lib().mj_set_step_count(env._h, int(z["step_count"])))
+        return env
 
     def deal_from_wall(self, b, wall):
         torch = self.torch

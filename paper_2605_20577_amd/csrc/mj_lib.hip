@@ -905,6 +905,12 @@ int mj_deal_from_wall(MjHandle *h, int64_t b, const uint8_t *d_wall, void *strea
 }
 
 uint64_t mj_step_count(const MjHandle *h) { return h ? h->step : 0; }
+int mj_set_step_count(MjHandle *h, uint64_t steps)
+{
+  if (!h) return MJ_E_ARG;
+  h->step = steps;
+  return MJ_OK;
+}
 
 float mj_last_step_kernel_ms(MjHandle *h)
 {

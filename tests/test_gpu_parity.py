@@ -257,3 +257,24 @@ def test_one_vs_three_evaluation_matches_the_oracle():
     assert np.array_equal(np.array(res["rank_count"]), rank_count)
     assert abs(sum(res["mean_rank"]) - 10.0) < 1e-9               # ranks 1..4 are shared out in every game
     assert not diff_records(o.export(), g.export())
+
+
+def test_checkpoint_and_resume(tmp_path):
+    """records + step counter saved after 300 steps and restored into a fresh library instance continue exactly
+    like the run that was never interrupted (and like the oracle)"""
+    import paper_2605_20577_amd as mj
+    B = 500
+    g = GpuEngine(B, seed=31, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    g.step_random(300)
+    path = str(tmp_path / "ckpt.npz")
+    g.env.save(path)
+    g.step_random(400)
+    r = mj.MahjongEnv.restore(path)
+    assert r.step_count == 300
+    r.step_random(400)
+    assert not diff_records(g.export(), r.export())
+    o = mjo.Oracle(B, 31, mjo.RULES_RED, mjo.MODE_HALF)
+    o.step_random(700)
+    assert not diff_records(o.export(), r.export())
+    assert np.array_equal(o.observe(), r.observe().cpu().numpy())
+    r.close()
