@@ -179,6 +179,72 @@ uint64_t mjo_waits_of(const uint8_t hand[34], const uint16_t meld[4], int n_meld
   return w;
 }
 
+/* ------------------------------------------------------------ shanten */
+
+/* Shanten number (paper section 3.2 lists it among the scalar properties of
+ * the observation): how many tile exchanges a hand is away from tenpai, -1 for
+ * a complete hand.  The usual formula on blocks, written as an exhaustive
+ * search: with `need` = 4 - n_meld sets still to be found among the concealed
+ * tiles, m complete sets (triplet or run), t partial sets (pair, two adjacent,
+ * two with a gap) taken from disjoint tiles with m + t <= need, and p = 1 when
+ * a pair is set aside as the head, the standard form is
+ *     2 * need - (2 m + t) - p,
+ * minimised over every way of choosing head, sets and partial sets; seven
+ * pairs (6 - pairs + missing kinds) and thirteen orphans (13 - kinds - pair)
+ * compete when there is no meld.  Tile availability is not considered (a
+ * partial set that waits on a tile the hand already holds four times still
+ * counts), as in the customary definition. */
+static void sh_search(uint8_t *c, int i, int m, int t, int need, int *best)
+{
+  while (i < 34 && c[i] == 0) i++;
+  if (i == 34) {
+    int tt = t < need - m ? t : need - m;
+    if (2 * m + tt > *best) *best = 2 * m + tt;
+    return;
+  }
+  int suited = i < 27, r = i % 9;
+  if (m < need) {
+    if (c[i] >= 3) { c[i] -= 3; sh_search(c, i, m + 1, t, need, best); c[i] += 3; }
+    if (suited && r <= 6 && c[i + 1] && c[i + 2]) {
+      c[i]--; c[i + 1]--; c[i + 2]--; sh_search(c, i, m + 1, t, need, best); c[i]++; c[i + 1]++; c[i + 2]++;
+    }
+  }
+  if (c[i] >= 2) { c[i] -= 2; sh_search(c, i, m, t + 1, need, best); c[i] += 2; }
+  if (suited && r <= 7 && c[i + 1]) { c[i]--; c[i + 1]--; sh_search(c, i, m, t + 1, need, best); c[i]++; c[i + 1]++; }
+  if (suited && r <= 6 && c[i + 2]) { c[i]--; c[i + 2]--; sh_search(c, i, m, t + 1, need, best); c[i]++; c[i + 2]++; }
+  c[i]--; sh_search(c, i, m, t, need, best); c[i]++;          /* this tile belongs to nothing */
+}
+
+int mjo_shanten(const uint8_t hand[34], int n_meld)
+{
+  uint8_t c[34];
+  memcpy(c, hand, 34);
+  int need = 4 - n_meld, best = 0;
+  sh_search(c, 0, 0, 0, need, &best);
+  int sh = 2 * need - best;                                    /* no head set aside */
+  for (int k = 0; k < 34; k++) {
+    if (c[k] < 2) continue;
+    c[k] -= 2;
+    best = 0;
+    sh_search(c, 0, 0, 0, need, &best);
+    c[k] += 2;
+    if (2 * need - best - 1 < sh) sh = 2 * need - best - 1;
+  }
+  if (n_meld == 0) {
+    int pairs = 0, kinds = 0, yao = 0, yao_pair = 0;
+    for (int k = 0; k < 34; k++) {
+      if (c[k] >= 1) kinds++;
+      if (c[k] >= 2) pairs++;
+      if (is_yaochu(k)) { if (c[k] >= 1) yao++; if (c[k] >= 2) yao_pair = 1; }
+    }
+    int chiitoi = 6 - pairs + (kinds < 7 ? 7 - kinds : 0);
+    int kokushi = 13 - yao - yao_pair;
+    if (chiitoi < sh) sh = chiitoi;
+    if (kokushi < sh) sh = kokushi;
+  }
+  return sh;
+}
+
 /* ------------------------------------------------------------ evaluation */
 
 enum { S_RUN = 0, S_TRIPLET = 1, S_KAN = 2 };

@@ -118,6 +118,7 @@ void mjo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t ou
 void mjo_shuffle_wall(uint32_t seed, uint32_t env_id, uint32_t kyoku_serial, uint8_t wall[136]);
 int  mjo_is_complete(const uint8_t hand[34], int n_meld);
 uint64_t mjo_waits_of(const uint8_t hand[34], const uint16_t meld[4], int n_meld);
+int  mjo_shanten(const uint8_t hand[34], int n_meld);   /* -1 complete, 0 tenpai, ... (section 3.2, observation scalars) */
 void mjo_eval_hand(const MjoHandQuery *q, MjoHandResult *r);
 
 /* environment API (host pointers everywhere) */

@@ -78,6 +78,8 @@ def lib():
         L.mjo_is_complete.argtypes = [vp, C.c_int]
         L.mjo_waits_of.argtypes = [vp, vp, C.c_int]
         L.mjo_waits_of.restype = u64
+        L.mjo_shanten.argtypes = [vp, C.c_int]
+        L.mjo_shanten.restype = C.c_int
         L.mjo_eval_hand.argtypes = [vp, vp]
         L.mjo_create.argtypes = [C.POINTER(vp), i64, u64, C.POINTER(Rules)]
         L.mjo_step.argtypes = [vp, vp]
@@ -128,6 +130,11 @@ def waits_of(hand, melds=()):
     m = np.zeros(4, dtype=np.uint16)
     m[:len(melds)] = melds
     return int(lib().mjo_waits_of(_p(h), _p(m), len(melds)))
+
+
+def shanten(hand, n_meld=0):
+    h = np.ascontiguousarray(hand, dtype=np.uint8)
+    return int(lib().mjo_shanten(_p(h), n_meld))
 
 
 def eval_hands(queries):
