@@ -122,6 +122,29 @@ typedef struct MjHandResult {
   uint8_t  pad_[4];
 } MjHandResult;
 
+/* Token observation of one (environment, viewer) pair, 224 bytes (section
+ * 3.2, "Observation Space": a structured observation for sequence models --
+ * hand indices, the public history of discards and calls, scalar properties
+ * such as the shanten number and the scores -- ego-centric; the field layout is
+ * this library's).  Seats are relative to the viewer: 0 self, 1 next, 2 across,
+ * 3 previous.  A tile token is its kind 0..33, or 34 / 35 / 36 for the red
+ * 5m / 5p / 5s; 255 pads.  A river entry is token | called_away << 7.  Meld
+ * words are those of MjEnvCanon (unused slots 0). */
+typedef struct MjTokenObs {
+  uint8_t  hand[14];        /* own concealed tiles, ascending kind, the red five before the plain fives */
+  uint8_t  n_hand;
+  int8_t   shanten;         /* of the own hand: -1 complete, 0 tenpai, .. 6 (customary block formula, tile
+                               availability not considered; melds count as sets) */
+  uint8_t  drawn;           /* the tile the viewer has just drawn, 255 otherwise */
+  uint8_t  phase, cur, last_discarder, last_discard;    /* cur: the seat to move in phase TURN, else 255 */
+  uint8_t  kyoku, honba, kyotaku, dealer, live_left, n_dora;
+  uint8_t  dora[5];         /* revealed indicators */
+  uint8_t  n_meld[4], n_river[4], riichi[4], riichi_idx[4];
+  int32_t  score[4];
+  uint16_t meld[4][4];
+  uint8_t  river[4][32];
+} MjTokenObs;
+
 typedef struct MjHandle MjHandle;   /* host object: B, seed, rules, step counter, pointers into the caller's buffers */
 
 const char *mj_strerror(int code);
@@ -158,6 +181,10 @@ int mj_legal_mask(const MjHandle *h, uint64_t *d_mask /*[B][4][2]*/, void *strea
 /* observation (section 3.2, ego-centric; this library's plane layout):
  * d_obs[b][seat][56][34], bytes 0/1, seen from `seat`. */
 int mj_observe(const MjHandle *h, uint8_t *d_obs /*[B][4][56][34]*/, void *stream);
+
+/* token observation (section 3.2, see MjTokenObs): d_out[b][seat], seen from
+ * `seat`.  d_out must be 16-byte aligned. */
+int mj_observe_tokens(const MjHandle *h, MjTokenObs *d_out /*[B][4]*/, void *stream);
 
 /* rewards of the last step: point change per seat, optional float view
  * (points / 1000, or the illegal-action penalty for the offending seat,

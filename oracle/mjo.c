@@ -1294,6 +1294,51 @@ uint64_t mjo_step_count(const MjoHandle *h) { return h->step; }
 void mjo_destroy(MjoHandle *h) { if (h) { free(h->env); free(h); } }
 size_t mjo_sizeof_env(void) { return sizeof(E); }
 
+/* Token observation (see MjoTokenObs). */
+static uint8_t tile_token(int kind, int red) { return (uint8_t)(red ? 34 + kind / 9 : kind); }
+int mjo_observe_tokens(const MjoHandle *h, MjoTokenObs *out)
+{
+  for (int64_t b = 0; b < h->B; b++) {
+    const E *e = &h->env[b];
+    for (int me = 0; me < 4; me++) {
+      MjoTokenObs *o = &out[b * 4 + me];
+      memset(o, 255, sizeof *o);
+      int n = 0;
+      for (int k = 0; k < 34; k++) {
+        int cnt = e->hand[me][k];
+        int red = (k % 9 == 4 && k < 27 && (e->hand_red[me] >> (k / 9) & 1)) ? 1 : 0;
+        if (red) { o->hand[n++] = tile_token(k, 1); cnt--; }
+        for (int i = 0; i < cnt; i++) o->hand[n++] = tile_token(k, 0);
+      }
+      o->n_hand = (uint8_t)n;
+      o->shanten = (int8_t)mjo_shanten(e->hand[me], e->n_meld[me]);
+      o->drawn = (e->phase == MJO_TURN && e->cur == me && e->drawn != 255) ? tile_token(e->drawn & 63, e->drawn >> 6 & 1) : 255;
+      o->phase = e->phase;
+      o->cur = e->phase == MJO_TURN ? (uint8_t)((e->cur - me) & 3) : 255;
+      o->last_discarder = e->last_discarder == 255 ? 255 : (uint8_t)((e->last_discarder - me) & 3);
+      o->last_discard = e->last_discard == 255 ? 255 : tile_token(e->last_discard & 63, e->last_discard >> 6 & 1);
+      o->kyoku = e->kyoku; o->honba = e->honba; o->kyotaku = e->kyotaku;
+      o->dealer = (uint8_t)((dealer_of(e) - me) & 3);
+      o->live_left = e->live_left; o->n_dora = e->n_dora;
+      for (int i = 0; i < 5; i++)
+        o->dora[i] = i < e->n_dora ? tile_token(e->wall[126 + i] >> 2, is_red_id(h, e->wall[126 + i])) : 255;
+      for (int rel = 0; rel < 4; rel++) {
+        int s = (me + rel) & 3;
+        o->n_meld[rel] = e->n_meld[s]; o->n_river[rel] = e->n_river[s];
+        o->riichi[rel] = e->riichi[s]; o->riichi_idx[rel] = e->riichi_idx[s];
+        o->score[rel] = e->score[s];
+        for (int j = 0; j < 4; j++) o->meld[rel][j] = j < e->n_meld[s] ? e->meld[s][j] : 0;
+        for (int i = 0; i < 32; i++) {
+          if (i >= e->n_river[s]) { o->river[rel][i] = 255; continue; }
+          int t = e->river[s][i];
+          o->river[rel][i] = (uint8_t)(tile_token(t & 63, t >> 6 & 1) | (t & 0x80));
+        }
+      }
+    }
+  }
+  return 0;
+}
+
 /* Observation, one stack of 56 planes over the 34 kinds per seat, entries 0/1,
  * seen from that seat (rel 0 self, 1 next, 2 across, 3 previous). */
 int mjo_observe(const MjoHandle *h, uint8_t *obs)

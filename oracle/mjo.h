@@ -114,6 +114,27 @@ typedef struct MjoHandResult {
 typedef struct MjoHandle MjoHandle;
 
 /* pins / building blocks exposed for the tests */
+/* Token observation of one (environment, viewer) pair, 224 bytes (paper
+ * section 3.2: a structured observation for sequence models -- hand indices,
+ * the public history of discards and calls, scalar properties such as the
+ * shanten number and the scores -- ego-centric).  Seats are relative to the
+ * viewer: 0 self, 1 next, 2 across, 3 previous.  A tile token is its kind
+ * 0..33, or 34 / 35 / 36 for the red 5m / 5p / 5s; 255 pads.  A river entry is
+ * token | called_away << 7.  Meld words are those of MjoEnv. */
+typedef struct MjoTokenObs {
+  uint8_t  hand[14];      /* own concealed tiles, ascending kind, the red five before the plain fives */
+  uint8_t  n_hand;
+  int8_t   shanten;       /* of the own hand: -1 complete, 0 tenpai, .. 6 */
+  uint8_t  drawn;         /* the tile the viewer has just drawn, 255 otherwise */
+  uint8_t  phase, cur, last_discarder, last_discard;   /* relative seats (255 none), token */
+  uint8_t  kyoku, honba, kyotaku, dealer, live_left, n_dora;
+  uint8_t  dora[5];       /* revealed indicators */
+  uint8_t  n_meld[4], n_river[4], riichi[4], riichi_idx[4];
+  int32_t  score[4];
+  uint16_t meld[4][4];
+  uint8_t  river[4][32];
+} MjoTokenObs;
+
 void mjo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 void mjo_shuffle_wall(uint32_t seed, uint32_t env_id, uint32_t kyoku_serial, uint8_t wall[136]);
 int  mjo_is_complete(const uint8_t hand[34], int n_meld);
@@ -135,6 +156,7 @@ int  mjo_export(const MjoHandle *h, int64_t env_lo, int64_t n, MjoEnv *out);
 int  mjo_import(MjoHandle *h, int64_t env_lo, int64_t n, const MjoEnv *in);
 /* replace env b's wall by the given permutation and deal the current kyoku again from it */
 int  mjo_deal_from_wall(MjoHandle *h, int64_t b, const uint8_t wall[136]);
+int  mjo_observe_tokens(const MjoHandle *h, MjoTokenObs *out /*[B][4]*/);
 uint64_t mjo_step_count(const MjoHandle *h);
 void mjo_destroy(MjoHandle *h);
 size_t mjo_sizeof_env(void);

@@ -48,6 +48,14 @@ RESULT_DTYPE = np.dtype([
     ("shape_ok", "u1"), ("yaku_ok", "u1"), ("n_dora", "u1"), ("n_ura", "u1"), ("n_aka", "u1"),
     ("pad_", "u1", (4,)),
 ])
+TOKEN_DTYPE = np.dtype([
+    ("hand", "u1", (14,)), ("n_hand", "u1"), ("shanten", "i1"), ("drawn", "u1"), ("phase", "u1"), ("cur", "u1"),
+    ("last_discarder", "u1"), ("last_discard", "u1"), ("kyoku", "u1"), ("honba", "u1"), ("kyotaku", "u1"),
+    ("dealer", "u1"), ("live_left", "u1"), ("n_dora", "u1"), ("dora", "u1", (5,)), ("n_meld", "u1", (4,)),
+    ("n_river", "u1", (4,)), ("riichi", "u1", (4,)), ("riichi_idx", "u1", (4,)), ("score", "<i4", (4,)),
+    ("meld", "<u2", (4, 4)), ("river", "u1", (4, 32)),
+])
+assert TOKEN_DTYPE.itemsize == 224
 
 
 class Rules(C.Structure):
@@ -85,6 +93,7 @@ def lib():
         L.mjo_step.argtypes = [vp, vp]
         L.mjo_legal_mask.argtypes = [vp, vp]
         L.mjo_observe.argtypes = [vp, vp]
+        L.mjo_observe_tokens.argtypes = [vp, vp]
         L.mjo_reward.argtypes = [vp, vp, vp, vp]
         L.mjo_reset_done.argtypes = [vp]
         L.mjo_sample_random.argtypes = [vp, vp]
@@ -186,6 +195,11 @@ class Oracle:
     def observe(self):
         o = np.zeros((self.B, 4, 56, 34), dtype=np.uint8)
         lib().mjo_observe(self._h, _p(o))
+        return o
+
+    def observe_tokens(self):
+        o = np.zeros((self.B, 4), dtype=TOKEN_DTYPE)
+        lib().mjo_observe_tokens(self._h, _p(o))
         return o
 
     def reward(self):

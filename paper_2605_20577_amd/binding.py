@@ -44,7 +44,15 @@ RESULT_DTYPE = np.dtype([
     ("shape_ok", "u1"), ("yaku_ok", "u1"), ("n_dora", "u1"), ("n_ura", "u1"), ("n_aka", "u1"),
     ("pad_", "u1", (4,)),
 ])
+TOKEN_DTYPE = np.dtype([        # MjTokenObs
+    ("hand", "u1", (14,)), ("n_hand", "u1"), ("shanten", "i1"), ("drawn", "u1"), ("phase", "u1"), ("cur", "u1"),
+    ("last_discarder", "u1"), ("last_discard", "u1"), ("kyoku", "u1"), ("honba", "u1"), ("kyotaku", "u1"),
+    ("dealer", "u1"), ("live_left", "u1"), ("n_dora", "u1"), ("dora", "u1", (5,)), ("n_meld", "u1", (4,)),
+    ("n_river", "u1", (4,)), ("riichi", "u1", (4,)), ("riichi_idx", "u1", (4,)), ("score", "<i4", (4,)),
+    ("meld", "<u2", (4, 4)), ("river", "u1", (4, 32)),
+])
 assert ENV_DTYPE.itemsize == 744 and QUERY_DTYPE.itemsize == 64 and RESULT_DTYPE.itemsize == 24
+assert TOKEN_DTYPE.itemsize == 224
 
 
 class MjRules(C.Structure):
@@ -62,6 +70,7 @@ EXPORTS = {
     "mj_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_legal_mask": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_observe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mj_observe_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_reward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_standings": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_reset_done": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -141,6 +150,10 @@ def mj_legal_mask(h, mask):
 
 def mj_observe(h, obs):
     _check(lib().mj_observe(h, _ptr(obs), _stream()))
+
+
+def mj_observe_tokens(h, out):
+    _check(lib().mj_observe_tokens(h, _ptr(out), _stream()))
 
 
 def mj_standings(h, score, rank):
@@ -234,6 +247,15 @@ class MahjongEnv:
         o = out if out is not None else torch.empty((self.B, 4, 56, 34), dtype=torch.uint8, device=self.device)
         with self._dev():
             mj_observe(self._h, o)
+        return o
+
+    def observe_tokens(self, out=None):
+        """token observation: uint8 tensor [B, 4, 224], one MjTokenObs per (game, viewer); view it on the host as
+        TOKEN_DTYPE, or slice the byte fields on the device"""
+        torch = self.torch
+        o = out if out is not None else torch.empty((self.B, 4, TOKEN_DTYPE.itemsize), dtype=torch.uint8, device=self.device)
+        with self._dev():
+            mj_observe_tokens(self._h, o)
         return o
 
     def reward(self):

@@ -212,4 +212,57 @@ MJ_HD uint64_t obs_plane(int p, int me, const uint64_t *S, uint32_t own_red, con
   return cur == me ? (G[OG_MISC] >> 8) : 0;
 }
 
+// ------------------------------------------------------- token observation
+MJ_HD uint8_t tile_token(int kind, int red) { return (uint8_t)(red ? 34 + kind / 9 : kind); }
+// the record of viewer `me` (see MjTokenObs); every field of the record is written
+MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, const uint32_t *sh_suit, const uint32_t *sh_honor,
+                     MjTokenObs &o)
+{
+  const int64_t n = e.n;
+  const uint32_t swm = e.seatw[me * n];
+  uint32_t h[4];
+  for (int su = 0; su < 4; su++) h[su] = e.hand[(me * 4 + su) * n];
+  int cnt = 0;
+  for (int su = 0; su < 4; su++) {
+    const int nr = su == 3 ? 7 : 9;
+    for (int r = 0; r < nr; r++) {
+      int c = cnt3(h[su], r);
+      const int k = (su == 3 ? 27 : 9 * su) + r;
+      if (su < 3 && r == 4 && (swm >> su & 1u) && c > 0) { if (cnt < 14) o.hand[cnt] = tile_token(k, 1); cnt++; c--; }
+      for (int i = 0; i < c; i++) { if (cnt < 14) o.hand[cnt] = tile_token(k, 0); cnt++; }
+    }
+  }
+  for (int i = cnt; i < 14; i++) o.hand[i] = 255;
+  o.n_hand = (uint8_t)cnt;
+  o.shanten = (int8_t)shanten_of(sh_suit, sh_honor, h[0], h[1], h[2], h[3], (int)sw_get(swm, SW_NMELD, 3));
+  o.drawn = (g.phase == PH_TURN && g.cur == me && g.drawn != 255) ? tile_token(code_kind(g.drawn), code_red(g.drawn)) : 255;
+  o.phase = g.phase;
+  o.cur = g.phase == PH_TURN ? (uint8_t)((g.cur - me) & 3) : 255;
+  o.last_discarder = g.last_discarder == 255 ? 255 : (uint8_t)((g.last_discarder - me) & 3);
+  o.last_discard = g.last_discard == 255 ? 255 : tile_token(code_kind(g.last_discard), code_red(g.last_discard));
+  o.kyoku = g.kyoku; o.honba = g.honba; o.kyotaku = g.kyotaku;
+  o.dealer = (uint8_t)(((g.kyoku & 3) - me) & 3);
+  o.live_left = g.live_left; o.n_dora = g.n_dora;
+  for (int i = 0; i < 5; i++) {
+    const int id = wall_at(e, g.wall_sel, 126 + i);
+    const bool red = (rule_flags & F_RED) && (id == 16 || id == 52 || id == 88);
+    o.dora[i] = i < g.n_dora ? tile_token(id >> 2, red) : 255;
+  }
+  for (int rel = 0; rel < 4; rel++) {
+    const int s = (me + rel) & 3;
+    const uint32_t sw = e.seatw[s * n];
+    const int nm = (int)sw_get(sw, SW_NMELD, 3), nriv = (int)sw_get(sw, SW_NRIVER, 6);
+    o.n_meld[rel] = (uint8_t)nm; o.n_river[rel] = (uint8_t)nriv;
+    o.riichi[rel] = (uint8_t)sw_get(sw, SW_RIICHI, 2); o.riichi_idx[rel] = (uint8_t)sw_get(sw, SW_RIDX, 8);
+    o.score[rel] = e.score[s * n];
+    const uint64_t mw = e.meld[s * n];
+    for (int j = 0; j < 4; j++) o.meld[rel][j] = j < nm ? (uint16_t)(mw >> (16 * j)) : (uint16_t)0;
+    for (int i = 0; i < 32; i++) {
+      if (i >= nriv) { o.river[rel][i] = 255; continue; }
+      const int t = e.river[(s * 32 + i) * n];
+      o.river[rel][i] = (uint8_t)(tile_token(t & 63, t >> 6 & 1) | (t & 0x80));
+    }
+  }
+}
+
 }  // namespace mj

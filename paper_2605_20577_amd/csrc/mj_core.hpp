@@ -499,6 +499,83 @@ MJ_HD uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint3
   return out;
 }
 
+// ------------------------------------------------------------------ shanten
+// Shanten number of a concealed hand with n_meld melds (paper section 3.2, observation scalars): -1 complete,
+// 0 tenpai, ...  Standard form: 2 * need - max(2 m + min(t, need - m)) - head with need = 4 - n_meld, m sets and
+// t partial sets summed over the four suits; each suit contributes, for every m, its largest t from the block
+// tables of mj_tables.hpp (sh_suit for the numbered suits, sh_honor for the honors), with the head in at most one
+// suit.  Seven pairs and thirteen orphans compete when there is no meld.
+struct ShFront { int v[5]; };
+MJ_HD ShFront sh_front(uint32_t e, int head)
+{
+  ShFront f;
+#pragma unroll
+  for (int m = 0; m < 5; m++) { int x = (int)(e >> (15 * head + 3 * m)) & 7; f.v[m] = x == 7 ? -64 : x; }
+  return f;
+}
+MJ_HD ShFront sh_join(const ShFront &a, const ShFront &b)     // sets and partial sets of two disjoint groups of tiles
+{
+  ShFront c;
+#pragma unroll
+  for (int m = 0; m < 5; m++) {
+    int best = -64;
+#pragma unroll
+    for (int i = 0; i <= m; i++) { int x = a.v[i] + b.v[m - i]; best = x > best ? x : best; }
+    c.v[m] = best;
+  }
+  return c;
+}
+MJ_HD ShFront sh_max(const ShFront &a, const ShFront &b)
+{
+  ShFront c;
+#pragma unroll
+  for (int m = 0; m < 5; m++) c.v[m] = a.v[m] > b.v[m] ? a.v[m] : b.v[m];
+  return c;
+}
+MJ_HD int sh_value(const ShFront &f, int need)                // max of 2 m + min(t, need - m) over m <= need
+{
+  int best = -64;
+#pragma unroll
+  for (int m = 0; m < 5; m++) {
+    if (m > need || f.v[m] < 0) continue;
+    int t = f.v[m] < need - m ? f.v[m] : need - m;
+    best = 2 * m + t > best ? 2 * m + t : best;
+  }
+  return best;
+}
+MJ_HD int shanten_of(const uint32_t *sh_suit, const uint32_t *sh_honor, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3,
+                     int n_meld)
+{
+  const uint32_t hkey = (uint32_t)cnt3(h3, 0) + 5u * cnt3(h3, 1) + 25u * cnt3(h3, 2) + 125u * cnt3(h3, 3) + 625u * cnt3(h3, 4) +
+                        3125u * cnt3(h3, 5) + 15625u * cnt3(h3, 6);
+  const uint32_t e0 = sh_suit[prefix5(h0) + 3125u * suffix5(h0)], e1 = sh_suit[prefix5(h1) + 3125u * suffix5(h1)];
+  const uint32_t e2 = sh_suit[prefix5(h2) + 3125u * suffix5(h2)], e3 = sh_honor[hkey];
+  const int need = 4 - n_meld;
+  const ShFront n0 = sh_front(e0, 0), n1 = sh_front(e1, 0), n2 = sh_front(e2, 0), n3 = sh_front(e3, 0);
+  const ShFront g0 = sh_front(e0, 1), g1 = sh_front(e1, 1), g2 = sh_front(e2, 1), g3 = sh_front(e3, 1);
+  const ShFront n01 = sh_join(n0, n1), n23 = sh_join(n2, n3);
+  const ShFront g01 = sh_max(sh_join(g0, n1), sh_join(n0, g1)), g23 = sh_max(sh_join(g2, n3), sh_join(n2, g3));
+  int sh = 2 * need - sh_value(sh_join(n01, n23), need);
+  const int with_head = sh_value(sh_max(sh_join(g01, n23), sh_join(n01, g23)), need);
+  if (with_head >= 0 && 2 * need - with_head - 1 < sh) sh = 2 * need - with_head - 1;
+  if (n_meld == 0) {
+    const uint32_t h[4] = {h0, h1, h2, h3};
+    int pairs = kinds_held_twice(h), kinds = 0, yao = 0, yao_pair = 0;
+#pragma unroll
+    for (int su = 0; su < 4; su++) {
+      const uint32_t nz = fields_nonzero(h[su]), two = ((h[su] >> 1) | (h[su] >> 2)) & O111;
+      const uint32_t ym = su == 3 ? O111 : (1u | 1u << 24);     // the yaochu ranks of this suit
+      kinds += popc32(nz);
+      yao += popc32(nz & ym);
+      if (two & ym) yao_pair = 1;
+    }
+    const int chiitoi = 6 - pairs + (kinds < 7 ? 7 - kinds : 0), kokushi = 13 - yao - yao_pair;
+    sh = chiitoi < sh ? chiitoi : sh;
+    sh = kokushi < sh ? kokushi : sh;
+  }
+  return sh;
+}
+
 // --------------------------------------------------------------- evaluation
 struct HandIn {
   uint32_t h[4];        // concealed, winning tile included

@@ -22,6 +22,7 @@
 
 using namespace mj;
 
+static_assert(sizeof(MjTokenObs) == 224, "token record");
 static_assert(sizeof(MjEnvCanon) == 744, "canonical record layout");
 static_assert(sizeof(MjHandQuery) == 64 && sizeof(MjHandResult) == 24, "hand records");
 static_assert(sizeof(Glob) == 28, "control bytes");
@@ -646,6 +647,31 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
   }
 }
 
+// Token observation: one lane per (environment, viewer) builds its 224-byte record in LDS (byte and word fields
+// written in place), then the block copies its 256 records out with consecutive lanes on consecutive 16 bytes.
+constexpr int kTokEnvs = kAuxBlock / 4;           // 64 environments per block
+__global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64_t B, uint32_t rule_flags, const uint32_t *sh_suit,
+                                                           const uint32_t *sh_honor, MjTokenObs *out)
+{
+  __shared__ __align__(16) MjTokenObs rec[kAuxBlock];
+  const int tid = threadIdx.x;
+  const int64_t base = (int64_t)blockIdx.x * kTokEnvs;
+  const int nenv = (int)((B - base) < kTokEnvs ? (B - base) : kTokEnvs);
+  if (tid < 4 * nenv) {
+    // lanes of a wavefront take consecutive environments of one viewer, so that state reads are coalesced
+    const int me = tid / nenv, el = tid - me * nenv;
+    Env e = make_env(state, B, base + el);
+    Glob g;
+    load_glob(e, g);
+    token_obs(e, g, me, rule_flags, sh_suit, sh_honor, rec[el * 4 + me]);
+  }
+  __syncthreads();
+  const u32x4 *src = (const u32x4 *)rec;
+  u32x4 *dst = (u32x4 *)(out + base * 4);
+  const int n16 = nenv * 4 * (int)(sizeof(MjTokenObs) / 16);
+  for (int i = tid; i < n16; i += kAuxBlock) __builtin_nontemporal_store(src[i], &dst[i]);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ host side
@@ -656,6 +682,7 @@ struct MjHandle {
   uint64_t step;
   void *d_state, *d_scratch;
   DevTables T;
+  const uint32_t *sh_suit, *sh_honor;    // block tables of the shanten number (device)
   size_t lds_bytes, probe_bytes;
   int lpw;
   hipEvent_t ev[2];
@@ -670,8 +697,18 @@ const mjt::SuitTables &tables()
   static const mjt::SuitTables t = mjt::build();
   return t;
 }
+const std::vector<uint32_t> &sh_suit_table()
+{
+  static const std::vector<uint32_t> t = mjt::build_shanten_table(9, true);
+  return t;
+}
+const std::vector<uint32_t> &sh_honor_table()
+{
+  static const std::vector<uint32_t> t = mjt::build_shanten_table(7, false);
+  return t;
+}
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-struct ScratchLayout { size_t probe, base, rowrank, keyinfo, recs, total, probe_bytes; };
+struct ScratchLayout { size_t probe, base, rowrank, keyinfo, recs, sh_suit, sh_honor, total, probe_bytes; };
 ScratchLayout scratch_layout()
 {
   const mjt::SuitTables &t = tables();
@@ -682,7 +719,9 @@ ScratchLayout scratch_layout()
   s.rowrank = align256(s.base + t.base.size() * 2);
   s.keyinfo = align256(s.rowrank + t.rowrank.size() * 2);
   s.recs = align256(s.keyinfo + t.keyinfo.size() * 4);
-  s.total = align256(s.recs + t.recs.size() * 4);
+  s.sh_suit = align256(s.recs + t.recs.size() * 4);
+  s.sh_honor = align256(s.sh_suit + sh_suit_table().size() * 4);
+  s.total = align256(s.sh_honor + sh_honor_table().size() * 4);
   return s;
 }
 size_t scratch_bytes_impl() { return scratch_layout().total; }
@@ -763,6 +802,8 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   std::memcpy(img.data() + sl.rowrank, t.rowrank.data(), t.rowrank.size() * 2);
   std::memcpy(img.data() + sl.keyinfo, t.keyinfo.data(), t.keyinfo.size() * 4);
   std::memcpy(img.data() + sl.recs, t.recs.data(), t.recs.size() * 4);
+  std::memcpy(img.data() + sl.sh_suit, sh_suit_table().data(), sh_suit_table().size() * 4);
+  std::memcpy(img.data() + sl.sh_honor, sh_honor_table().data(), sh_honor_table().size() * 4);
   int rc = check(hipMemcpyAsync(d_scratch, img.data(), sl.total, hipMemcpyHostToDevice, st));
   if (rc == MJ_OK) rc = check(hipStreamSynchronize(st));       // the host image goes away
   char *sc = (char *)d_scratch;
@@ -772,6 +813,8 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   h->T.keyinfo = (const uint32_t *)(sc + sl.keyinfo);
   h->T.recs = (const uint32_t *)(sc + sl.recs);
   h->T.probe_bytes = (int)sl.probe_bytes;
+  h->sh_suit = (const uint32_t *)(sc + sl.sh_suit);
+  h->sh_honor = (const uint32_t *)(sc + sl.sh_honor);
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[0]));
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[1]));
   if (rc != MJ_OK) { delete h; return rc; }
@@ -803,6 +846,14 @@ int mj_observe(const MjHandle *h, uint8_t *d_obs, void *stream)
   int64_t groups = (h->B + kObsEnvs - 1) / kObsEnvs;
   unsigned grid = (unsigned)(groups < 65536 ? groups : 65536);
   k_observe<<<grid, kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, d_obs);
+  return check(hipGetLastError());
+}
+
+int mj_observe_tokens(const MjHandle *h, MjTokenObs *d_out, void *stream)
+{
+  if (!h || !d_out || ((uintptr_t)d_out & 15)) return MJ_E_ARG;
+  const unsigned grid = (unsigned)((h->B + kTokEnvs - 1) / kTokEnvs);
+  k_observe_tokens<<<grid, kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, h->sh_suit, h->sh_honor, d_out);
   return check(hipGetLastError());
 }
 

@@ -133,4 +133,62 @@ inline SuitTables build()
   return t;
 }
 
+// ---------------------------------------------------------------- shanten
+// Block statistics of one suit for the shanten number (paper section 3.2 lists the shanten number among the
+// observation's scalars; section 3.1, item 2 is the idea of a per-suit table).  For a pattern of counts and a number
+// m = 0..4 of complete sets (triplets, runs) taken from it, the entry gives the largest number of partial sets
+// (pair, two adjacent, two with a gap; capped at 4) that the remaining tiles still hold, once without and once
+// with one pair set aside as the head: ten 3-bit fields, 7 = "m sets are not possible" (bits 0..14 without head,
+// 15..29 with).  The key is the base-5 number of the counts, prefix5 + 3125 * suffix5 for a numbered suit
+// (1,953,125 entries), seven digits for the honors (78,125 entries, no runs).  Filled by dynamic programming over
+// the lowest occupied rank: every block that starts there, or the tile belongs to nothing.
+struct Frontier { int8_t n[5], h[5]; };
+inline uint32_t pack_frontier(const Frontier &f)
+{
+  uint32_t v = 0;
+  for (int m = 0; m < 5; m++) {
+    v |= (f.n[m] < 0 ? 7u : (uint32_t)f.n[m]) << (3 * m);
+    v |= (f.h[m] < 0 ? 7u : (uint32_t)f.h[m]) << (15 + 3 * m);
+  }
+  return v;
+}
+inline std::vector<uint32_t> build_shanten_table(int n_ranks, bool runs)
+{
+  int pw[10];
+  pw[0] = 1;
+  for (int r = 1; r <= n_ranks; r++) pw[r] = pw[r - 1] * 5;
+  const int N = pw[n_ranks];
+  std::vector<Frontier> F((size_t)N);
+  for (int m = 0; m < 5; m++) { F[0].n[m] = m == 0 ? 0 : -1; F[0].h[m] = -1; }
+  std::vector<uint32_t> out((size_t)N);
+  out[0] = pack_frontier(F[0]);
+  for (int key = 1; key < N; key++) {
+    int c[11] = {0};
+    for (int r = 0, k = key; r < n_ranks; r++, k /= 5) c[r] = k % 5;
+    int i = 0;
+    while (c[i] == 0) i++;
+    Frontier f;
+    for (int m = 0; m < 5; m++) f.n[m] = f.h[m] = -1;
+    auto relax = [&f](const Frontier &g, int dm, int dt) {
+      for (int m = 0; m + dm < 5; m++) {
+        if (g.n[m] >= 0) f.n[m + dm] = std::max<int8_t>(f.n[m + dm], (int8_t)std::min(g.n[m] + dt, 4));
+        if (g.h[m] >= 0) f.h[m + dm] = std::max<int8_t>(f.h[m + dm], (int8_t)std::min(g.h[m] + dt, 4));
+      }
+    };
+    if (c[i] >= 3) relax(F[key - 3 * pw[i]], 1, 0);
+    if (runs && i + 2 < n_ranks && c[i + 1] && c[i + 2]) relax(F[key - pw[i] - pw[i + 1] - pw[i + 2]], 1, 0);
+    if (c[i] >= 2) relax(F[key - 2 * pw[i]], 0, 1);
+    if (runs && i + 1 < n_ranks && c[i + 1]) relax(F[key - pw[i] - pw[i + 1]], 0, 1);
+    if (runs && i + 2 < n_ranks && c[i + 2]) relax(F[key - pw[i] - pw[i + 2]], 0, 1);
+    relax(F[key - pw[i]], 0, 0);
+    if (c[i] >= 2) {                                            // the pair at rank i is the head
+      const Frontier &g = F[key - 2 * pw[i]];
+      for (int m = 0; m < 5; m++) if (g.n[m] >= 0) f.h[m] = std::max(f.h[m], g.n[m]);
+    }
+    F[key] = f;
+    out[key] = pack_frontier(f);
+  }
+  return out;
+}
+
 }  // namespace mjt

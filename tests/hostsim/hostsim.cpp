@@ -152,6 +152,24 @@ void hs_observe(Sim *h, uint8_t *obs)
       }
   }
 }
+void hs_observe_tokens(Sim *h, MjTokenObs *out)
+{
+  static const std::vector<uint32_t> sh_suit = mjt::build_shanten_table(9, true), sh_honor = mjt::build_shanten_table(7, false);
+  for (int64_t b = 0; b < h->B; b++) {
+    Env e = make_env(h->state.data(), h->B, b);
+    Glob g;
+    load_glob(e, g);
+    for (int me = 0; me < 4; me++) token_obs(e, g, me, h->R.flags, sh_suit.data(), sh_honor.data(), out[b * 4 + me]);
+  }
+}
+int hs_shanten(Sim *h, const uint8_t *hand, int n_meld)
+{
+  (void)h;
+  static const std::vector<uint32_t> sh_suit = mjt::build_shanten_table(9, true), sh_honor = mjt::build_shanten_table(7, false);
+  uint32_t hw[4] = {0, 0, 0, 0};
+  for (int k = 0; k < 34; k++) { int su = suit_of(k); hw[su] |= (uint32_t)hand[k] << (3 * rank_of(k, su)); }
+  return shanten_of(sh_suit.data(), sh_honor.data(), hw[0], hw[1], hw[2], hw[3], n_meld);
+}
 void hs_eval_hands(Sim *h, int64_t n, const MjHandQuery *in, MjHandResult *out)
 {
   for (int64_t i = 0; i < n; i++) {

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libhostsim.so")
 _CSRC = os.path.join(_HERE, "..", "..", "paper_2605_20577_amd", "csrc")
 
-from oracle.mjo import ENV_DTYPE, QUERY_DTYPE, RESULT_DTYPE, Rules  # record layouts are the same by contract
+from oracle.mjo import ENV_DTYPE, QUERY_DTYPE, RESULT_DTYPE, TOKEN_DTYPE, Rules  # record layouts are the same by contract
 
 
 def build(force=False):
@@ -45,6 +45,9 @@ def lib():
         L.hs_export.argtypes = [vp, C.c_int64, C.c_int64, vp]
         L.hs_import.argtypes = [vp, C.c_int64, C.c_int64, vp]
         L.hs_observe.argtypes = [vp, vp]
+        L.hs_observe_tokens.argtypes = [vp, vp]
+        L.hs_shanten.argtypes = [vp, vp, C.c_int]
+        L.hs_shanten.restype = C.c_int
         L.hs_deal_from_wall.argtypes = [vp, C.c_int64, vp]
         L.hs_eval_hands.argtypes = [vp, C.c_int64, vp, vp]
         L.hs_waits.argtypes = [vp, vp, vp, C.c_int]
@@ -123,6 +126,15 @@ class HostSim:
         r = np.zeros(q.shape, dtype=RESULT_DTYPE)
         lib().hs_eval_hands(self._h, q.size, _p(q), _p(r))
         return r
+
+    def observe_tokens(self):
+        o = np.zeros((self.B, 4), dtype=TOKEN_DTYPE)
+        lib().hs_observe_tokens(self._h, _p(o))
+        return o
+
+    def shanten(self, hand, n_meld=0):
+        h = np.ascontiguousarray(hand, dtype=np.uint8)
+        return int(lib().hs_shanten(self._h, _p(h), n_meld))
 
     def waits_of(self, hand, melds=()):
         h = np.ascontiguousarray(hand, dtype=np.uint8)

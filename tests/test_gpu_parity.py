@@ -278,3 +278,22 @@ def test_checkpoint_and_resume(tmp_path):
     assert not diff_records(o.export(), r.export())
     assert np.array_equal(o.observe(), r.observe().cpu().numpy())
     r.close()
+
+
+@pytest.mark.parametrize("B,flags,mode", [(1, mjo.RULES_RED, mjo.MODE_HALF), (257, mjo.RULES_NORED, mjo.MODE_EAST),
+                                          (3000, mjo.RULES_RED, mjo.MODE_HALF)])
+def test_token_observation(B, flags, mode):
+    """the token observation (hand tokens, shanten number, rivers, melds, scalars) of every viewer against the
+    oracle's, along a rollout"""
+    o = mjo.Oracle(B, 17, flags, mode)
+    g = GpuEngine(B, seed=17, flags=flags, mode=mode)
+    shanten_seen = set()
+    for n in (0, 1, 40, 150, 400, 409):
+        o.step_random(n); g.step_random(n)
+        want = o.observe_tokens()
+        got = g.env.observe_tokens().cpu().numpy().reshape(B, 4, -1).view(mjo.TOKEN_DTYPE).reshape(B, 4)
+        for name in want.dtype.names:
+            assert np.array_equal(want[name], got[name]), (n, name)
+        shanten_seen |= set(np.unique(want["shanten"]).tolist())
+    if B >= 3000:
+        assert {-1, 0, 1, 2, 3, 4, 5} <= shanten_seen

@@ -145,3 +145,33 @@ def test_waits_and_tenpai_discards_vs_oracle():
         assert s.tenpai_discards_of(hand, melds) == want, (hand.tolist(), melds)
         n_tenpai += want != 0
     assert n_tenpai > 1500 and n_wait > 5000        # the cases are not vacuous
+
+
+def test_shanten_tables_vs_oracle():
+    """the kernels' table-driven shanten number against the oracle's exhaustive search: random hands of every size,
+    one- and two-suit hands (where the per-suit statistics are stressed), the seeded near-tenpai hands"""
+    s = HostSim(1, 0, mjo.RULES_NORED, mjo.MODE_SINGLE)
+    rng = np.random.default_rng(99)
+    wall = np.repeat(np.arange(34), 4)
+    seen = set()
+    for m in (0, 1, 2, 3, 4):
+        for size in (13 - 3 * m, 14 - 3 * m):
+            for suits in (None, (0,), (1, 2), (2, 3)):
+                w = wall if suits is None else np.repeat(np.concatenate([np.arange(9 * u, 9 * u + (7 if u == 3 else 9)) for u in suits]), 4)
+                for _ in range(150):
+                    h = np.bincount(rng.permutation(w)[:size], minlength=34).astype(np.uint8)
+                    want = mjo.shanten(h, m)
+                    assert s.shanten(h, m) == want, (h.tolist(), m)
+                    seen.add(want)
+    for hand, melds in _near_hands(rng, 1500):
+        assert s.shanten(hand, len(melds)) == mjo.shanten(hand, len(melds)), (hand.tolist(), len(melds))
+    assert set(range(-1, 7)) <= seen
+
+
+def test_token_observation_trace():
+    o, s = mjo.Oracle(24, 3, mjo.RULES_RED, mjo.MODE_HALF), HostSim(24, 3, mjo.RULES_RED, mjo.MODE_HALF)
+    for _ in range(40):
+        o.step_random(13); s.step_random(13)
+        a, b = o.observe_tokens(), s.observe_tokens()
+        for name in a.dtype.names:
+            assert np.array_equal(a[name], b[name]), name
