@@ -19,6 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+TOKEN_BYTES_PER_ENV = 4 * 224      # token observation written per game (4 viewers)
 # Algorithmic HBM bytes of one env step of the fused path ("Algorithmic bytes"): the state fields a
 # step has to read and write when nothing is cached between steps, outputs included.
 ALGO_BYTES_PER_ENV_STEP = 512
@@ -64,6 +65,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only-obs", action="store_true",
                     help="only the configs[4] side run (B = 2^20, red rules, observation written every step), 30 steps")
+    ap.add_argument("--only-tokens", action="store_true",
+                    help="only the token observation of B = 2^20 games (red rules, after 60 steps), 30 launches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB three times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -85,6 +88,20 @@ def main():
         print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30, "launches": 3}))
         return
 
+    if args.only_tokens:
+        Bo = 1 << 20
+        env = mj.MahjongEnv(Bo, seed=0, flags=mj.RULES_RED, mode=mj.MODE_HALF)
+        env.step_random(60)
+        tok = env.observe_tokens()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(30):
+            env.observe_tokens(tok)
+        torch.cuda.synchronize()
+        dtk = (time.perf_counter() - t0) / 30
+        print(json.dumps({"tok_B": Bo, "token_observation_envs_per_s": Bo / dtk,
+                          "token_observation_kernel_GBps": TOKEN_BYTES_PER_ENV * Bo / dtk / 1e9}))
+        return
     if args.only_obs:
         Bo = 1 << 20
         env = mj.MahjongEnv(Bo, seed=0, flags=mj.RULES_RED, mode=mj.MODE_HALF)
@@ -149,6 +166,17 @@ def main():
                 env.observe(obs)
             torch.cuda.synchronize()
             extras["observe_kernel_GBps"] = OBS_BYTES_PER_ENV * Bo * 20 / (time.perf_counter() - t0) / 1e9
+            # the token observation of the same batch: 4 x 224 B per game, shanten number included
+            tok = env.observe_tokens()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(20):
+                env.observe_tokens(tok)
+            torch.cuda.synchronize()
+            dtk = (time.perf_counter() - t0) / 20
+            extras["token_observation_envs_per_s"] = Bo / dtk
+            extras["token_observation_kernel_GBps"] = TOKEN_BYTES_PER_ENV * Bo / dtk / 1e9
+            del tok
             env.close()
             del obs
         except Exception as ex:                                  # reported, never hidden

@@ -213,10 +213,13 @@ MJ_HD uint64_t obs_plane(int p, int me, const uint64_t *S, uint32_t own_red, con
 }
 
 // ------------------------------------------------------- token observation
+// The record of a viewer (see MjTokenObs) is put together from four pieces, so that the kernel can compute what the
+// four viewers of a game share only once: the viewer's own hand, the game's scalars, the seats' public words
+// rotated to the viewer, and the rivers (token bytes by absolute seat, picked by relative seat on the way out).
 MJ_HD uint8_t tile_token(int kind, int red) { return (uint8_t)(red ? 34 + kind / 9 : kind); }
-// the record of viewer `me` (see MjTokenObs); every field of the record is written
-MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, const uint32_t *sh_suit, const uint32_t *sh_honor,
-                     MjTokenObs &o)
+MJ_HD uint8_t river_token(int t) { return (uint8_t)(tile_token(t & 63, t >> 6 & 1) | (t & 0x80)); }
+// own hand: tokens in ascending order (the red five first among the fives) and the shanten number
+MJ_HD void tok_own(const Env &e, int me, const uint32_t *sh_suit, const uint32_t *sh_honor, MjTokenObs &o)
 {
   const int64_t n = e.n;
   const uint32_t swm = e.seatw[me * n];
@@ -235,6 +238,10 @@ MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, c
   for (int i = cnt; i < 14; i++) o.hand[i] = 255;
   o.n_hand = (uint8_t)cnt;
   o.shanten = (int8_t)shanten_of(sh_suit, sh_honor, h[0], h[1], h[2], h[3], (int)sw_get(swm, SW_NMELD, 3));
+}
+// the game's scalars as the viewer sees them
+MJ_HD void tok_env(const Env &e, const Glob &g, int me, uint32_t rule_flags, MjTokenObs &o)
+{
   o.drawn = (g.phase == PH_TURN && g.cur == me && g.drawn != 255) ? tile_token(code_kind(g.drawn), code_red(g.drawn)) : 255;
   o.phase = g.phase;
   o.cur = g.phase == PH_TURN ? (uint8_t)((g.cur - me) & 3) : 255;
@@ -248,21 +255,41 @@ MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, c
     const bool red = (rule_flags & F_RED) && (id == 16 || id == 52 || id == 88);
     o.dora[i] = i < g.n_dora ? tile_token(id >> 2, red) : 255;
   }
+}
+// the four seats' public words (control word, points, melds; by absolute seat) rotated to the viewer
+MJ_HD void tok_seats(const uint32_t sw[4], const int32_t score[4], const uint64_t meld[4], int me, MjTokenObs &o)
+{
   for (int rel = 0; rel < 4; rel++) {
     const int s = (me + rel) & 3;
-    const uint32_t sw = e.seatw[s * n];
-    const int nm = (int)sw_get(sw, SW_NMELD, 3), nriv = (int)sw_get(sw, SW_NRIVER, 6);
-    o.n_meld[rel] = (uint8_t)nm; o.n_river[rel] = (uint8_t)nriv;
-    o.riichi[rel] = (uint8_t)sw_get(sw, SW_RIICHI, 2); o.riichi_idx[rel] = (uint8_t)sw_get(sw, SW_RIDX, 8);
-    o.score[rel] = e.score[s * n];
-    const uint64_t mw = e.meld[s * n];
-    for (int j = 0; j < 4; j++) o.meld[rel][j] = j < nm ? (uint16_t)(mw >> (16 * j)) : (uint16_t)0;
-    for (int i = 0; i < 32; i++) {
-      if (i >= nriv) { o.river[rel][i] = 255; continue; }
-      const int t = e.river[(s * 32 + i) * n];
-      o.river[rel][i] = (uint8_t)(tile_token(t & 63, t >> 6 & 1) | (t & 0x80));
-    }
+    const int nm = (int)sw_get(sw[s], SW_NMELD, 3);
+    o.n_meld[rel] = (uint8_t)nm; o.n_river[rel] = (uint8_t)sw_get(sw[s], SW_NRIVER, 6);
+    o.riichi[rel] = (uint8_t)sw_get(sw[s], SW_RIICHI, 2); o.riichi_idx[rel] = (uint8_t)sw_get(sw[s], SW_RIDX, 8);
+    o.score[rel] = score[s];
+    for (int j = 0; j < 4; j++) o.meld[rel][j] = j < nm ? (uint16_t)(meld[s] >> (16 * j)) : (uint16_t)0;
   }
+}
+// one seat's river as 32 token bytes
+MJ_HD void tok_river(const Env &e, int s, uint8_t out[32])
+{
+  const int nriv = (int)sw_get(e.seatw[s * e.n], SW_NRIVER, 6);
+  uint8_t t[32];
+#pragma unroll
+  for (int i = 0; i < 32; i++) t[i] = e.river[(int64_t)(s * 32 + i) * e.n];      // all 32 loads in flight together
+#pragma unroll
+  for (int i = 0; i < 32; i++) out[i] = i < nriv ? river_token(t[i]) : (uint8_t)255;
+}
+// the whole record of viewer `me` (the plain composition; every field of the record is written)
+MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, const uint32_t *sh_suit, const uint32_t *sh_honor,
+                     MjTokenObs &o)
+{
+  uint32_t sw[4];
+  int32_t score[4];
+  uint64_t meld[4];
+  for (int s = 0; s < 4; s++) { sw[s] = e.seatw[s * e.n]; score[s] = e.score[s * e.n]; meld[s] = e.meld[s * e.n]; }
+  tok_own(e, me, sh_suit, sh_honor, o);
+  tok_env(e, g, me, rule_flags, o);
+  tok_seats(sw, score, meld, me, o);
+  for (int rel = 0; rel < 4; rel++) tok_river(e, (me + rel) & 3, o.river[rel]);
 }
 
 }  // namespace mj

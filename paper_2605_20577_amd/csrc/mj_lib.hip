@@ -12,6 +12,7 @@
 // with all lanes.
 #include <hip/hip_runtime.h>
 #include <cstdio>
+#include <cstddef>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -647,29 +648,58 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
   }
 }
 
-// Token observation: one lane per (environment, viewer) builds its 224-byte record in LDS (byte and word fields
-// written in place), then the block copies its 256 records out with consecutive lanes on consecutive 16 bytes.
+// Token observation.  One lane per (environment, seat).  What the four viewers of a game share is computed once:
+// lane (env, s) turns seat s's river into token bytes and publishes the seat's control word, points and melds in
+// LDS; then, as viewer s, it writes the first 96 bytes of its record (own hand, shanten number, scalars, the seats'
+// words rotated to it) into LDS.  The block then streams the records out, consecutive lanes on consecutive
+// 16 bytes: six chunks from the record head, eight from the four rivers picked by relative seat.
 constexpr int kTokEnvs = kAuxBlock / 4;           // 64 environments per block
+constexpr int kTokHead = 96;                      // bytes of MjTokenObs before river[][]
+constexpr int kTokHeadStride = 100, kTokRivStride = 36;   // LDS strides: an odd number of words, so that the lanes of a
+                                                          // wavefront (consecutive environments) fall into different banks
+static_assert(offsetof(MjTokenObs, river) == kTokHead && sizeof(MjTokenObs) == kTokHead + 128, "token record layout");
 __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64_t B, uint32_t rule_flags, const uint32_t *sh_suit,
                                                            const uint32_t *sh_honor, MjTokenObs *out)
 {
-  __shared__ __align__(16) MjTokenObs rec[kAuxBlock];
+  __shared__ __align__(4) uint8_t head[4][kTokEnvs][kTokHeadStride];       // [viewer][env]
+  __shared__ __align__(4) uint8_t riv[4][kTokEnvs][kTokRivStride];         // [seat][env]
+  __shared__ uint32_t p_sw[4][kTokEnvs];
+  __shared__ int32_t p_score[4][kTokEnvs];
+  __shared__ uint64_t p_meld[4][kTokEnvs];
   const int tid = threadIdx.x;
   const int64_t base = (int64_t)blockIdx.x * kTokEnvs;
   const int nenv = (int)((B - base) < kTokEnvs ? (B - base) : kTokEnvs);
-  if (tid < 4 * nenv) {
-    // lanes of a wavefront take consecutive environments of one viewer, so that state reads are coalesced
-    const int me = tid / nenv, el = tid - me * nenv;
-    Env e = make_env(state, B, base + el);
+  // lanes of a wavefront take consecutive environments of one seat, so that state reads are coalesced
+  const int s = tid / nenv, el = tid - s * nenv;
+  const bool on = tid < 4 * nenv;
+  Env e = make_env(state, B, base + (on ? el : 0));
+  // MjTokenObs is used as a view of the record head only: nothing below touches river[][]
+  MjTokenObs &o = *(MjTokenObs *)head[on ? s : 0][on ? el : 0];
+  if (on) {
+    tok_river(e, s, riv[s][el]);
+    p_sw[s][el] = e.seatw[s * B]; p_score[s][el] = e.score[s * B]; p_meld[s][el] = e.meld[s * B];
     Glob g;
     load_glob(e, g);
-    token_obs(e, g, me, rule_flags, sh_suit, sh_honor, rec[el * 4 + me]);
+    tok_own(e, s, sh_suit, sh_honor, o);
+    tok_env(e, g, s, rule_flags, o);
   }
   __syncthreads();
-  const u32x4 *src = (const u32x4 *)rec;
-  u32x4 *dst = (u32x4 *)(out + base * 4);
-  const int n16 = nenv * 4 * (int)(sizeof(MjTokenObs) / 16);
-  for (int i = tid; i < n16; i += kAuxBlock) __builtin_nontemporal_store(src[i], &dst[i]);
+  if (on) {
+    const uint32_t sw[4] = {p_sw[0][el], p_sw[1][el], p_sw[2][el], p_sw[3][el]};
+    const int32_t sc[4] = {p_score[0][el], p_score[1][el], p_score[2][el], p_score[3][el]};
+    const uint64_t ml[4] = {p_meld[0][el], p_meld[1][el], p_meld[2][el], p_meld[3][el]};
+    tok_seats(sw, sc, ml, s, o);
+  }
+  __syncthreads();
+  // out: consecutive lanes on consecutive words; 24 words from the record head, 32 from the rivers by relative seat
+  uint32_t *dst = (uint32_t *)(out + base * 4);
+  constexpr int kRecWords = (int)(sizeof(MjTokenObs) / 4), kHeadWords = kTokHead / 4;
+  for (int i = tid; i < nenv * 4 * kRecWords; i += kAuxBlock) {
+    const int rec = i / kRecWords, c = i - rec * kRecWords, env = rec >> 2, me = rec & 3;
+    const uint32_t *src = c < kHeadWords ? (const uint32_t *)head[me][env] + c
+                                         : (const uint32_t *)riv[(me + ((c - kHeadWords) >> 3)) & 3][env] + ((c - kHeadWords) & 7);
+    __builtin_nontemporal_store(*src, &dst[i]);
+  }
 }
 
 }  // namespace
