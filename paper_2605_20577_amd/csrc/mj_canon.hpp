@@ -216,7 +216,7 @@ MJ_HD uint64_t obs_plane(int p, int me, const uint64_t *S, uint32_t own_red, con
 // The record of a viewer (see MjTokenObs) is put together from four pieces, so that the kernel can compute what the
 // four viewers of a game share only once: the viewer's own hand, the game's scalars, the seats' public words
 // rotated to the viewer, and the rivers (token bytes by absolute seat, picked by relative seat on the way out).
-MJ_HD uint8_t tile_token(int kind, int red) { return (uint8_t)(red ? 34 + kind / 9 : kind); }
+MJ_HD uint8_t tile_token(int kind, int red) { return (uint8_t)(red ? 34 + (kind >= 9) + (kind >= 18) : kind); }
 MJ_HD uint8_t river_token(int t) { return (uint8_t)(tile_token(t & 63, t >> 6 & 1) | (t & 0x80)); }
 // own hand: tokens in ascending order (the red five first among the fives) and the shanten number
 MJ_HD void tok_own(const Env &e, int me, const uint32_t *sh_suit, const uint32_t *sh_honor, MjTokenObs &o)

@@ -691,14 +691,20 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
     tok_seats(sw, sc, ml, s, o);
   }
   __syncthreads();
-  // out: consecutive lanes on consecutive words; 24 words from the record head, 32 from the rivers by relative seat
-  uint32_t *dst = (uint32_t *)(out + base * 4);
+  // out: lane c < 56 of a wavefront owns word c of every record the wavefront writes (one record per iteration, 224
+  // consecutive bytes), so the source is a fixed offset plus a stride: 24 words from the record head, 32 from the
+  // rivers picked by relative seat
   constexpr int kRecWords = (int)(sizeof(MjTokenObs) / 4), kHeadWords = kTokHead / 4;
-  for (int i = tid; i < nenv * 4 * kRecWords; i += kAuxBlock) {
-    const int rec = i / kRecWords, c = i - rec * kRecWords, env = rec >> 2, me = rec & 3;
-    const uint32_t *src = c < kHeadWords ? (const uint32_t *)head[me][env] + c
-                                         : (const uint32_t *)riv[(me + ((c - kHeadWords) >> 3)) & 3][env] + ((c - kHeadWords) & 7);
-    __builtin_nontemporal_store(*src, &dst[i]);
+  const int c = tid & 63, wave = tid >> 6;
+  if (c < kRecWords) {
+    uint32_t *dst = (uint32_t *)(out + base * 4) + c;
+    const bool in_head = c < kHeadWords;
+    const int rel = (c - kHeadWords) >> 3, w = (c - kHeadWords) & 7;
+    for (int rec = wave; rec < nenv * 4; rec += kAuxBlock / 64) {
+      const int env = rec >> 2, me = rec & 3;
+      const uint32_t *src = in_head ? (const uint32_t *)head[me][env] + c : (const uint32_t *)riv[(me + rel) & 3][env] + w;
+      __builtin_nontemporal_store(*src, dst + (size_t)rec * kRecWords);
+    }
   }
 }
 
