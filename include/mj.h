@@ -41,6 +41,10 @@ extern "C" {
 #define MJ_F_ABORT    2u     /* abortive draws */
 #define MJ_F_KUITAN   4u     /* open tanyao */
 #define MJ_F_MULTIRON 8u     /* reserved, multiple ron is always on */
+#define MJ_F_ENDGAME 16u     /* end of game by points (east / half): the last regular kyoku ends the game only if
+                                somebody has 30,000; otherwise at most one more round is played, ending after any
+                                kyoku that leaves somebody at 30,000; a dealer who repeats in the last regular
+                                kyoku or later ends the game when alone in the lead with 30,000 */
 #define MJ_RULES_NORED (MJ_F_KUITAN | MJ_F_MULTIRON)
 #define MJ_RULES_RED   (MJ_F_RED | MJ_F_ABORT | MJ_F_KUITAN | MJ_F_MULTIRON)
 

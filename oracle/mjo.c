@@ -792,7 +792,20 @@ static void finish_kyoku(MjoHandle *h, int64_t b, int renchan, int honba_up)
   int last = h->rules.mode == 0 ? 0 : h->rules.mode == 1 ? 3 : 7;
   int over = h->rules.mode == 0;
   for (int s = 0; s < 4; s++) if (e->score[s] < 0) over = 1;
-  if (!renchan && e->kyoku == last) over = 1;
+  if ((h->rules.flags & MJO_F_ENDGAME) && h->rules.mode != 0) {
+    /* End of game by points (the paper's rule set follows Tenhou, section 3.2; this is this library's reading of
+     * that site's ending rules): the last regular kyoku ends the game only if somebody has 30,000; otherwise play
+     * goes on for at most one more round, ending after any kyoku that leaves somebody at 30,000; a dealer who
+     * repeats in the last regular kyoku or later ends the game when alone in the lead with 30,000. */
+    int dealer = dealer_of(e), limit = last + 4, lead = 1;
+    int32_t top = e->score[0];
+    for (int s = 1; s < 4; s++) if (e->score[s] > top) top = e->score[s];
+    for (int s = 0; s < 4; s++) if (s != dealer && e->score[s] >= e->score[dealer]) lead = 0;
+    if (e->kyoku >= last) {
+      if (!renchan) { if (top >= 30000 || e->kyoku == limit) over = 1; }
+      else if ((lead && e->score[dealer] >= 30000) || (e->kyoku > last && top >= 30000)) over = 1;
+    }
+  } else if (!renchan && e->kyoku == last) over = 1;
   if (honba_up) { if (e->honba < 255) e->honba++; } else e->honba = 0;
   if (!renchan && !over) e->kyoku++;
   if (over) {

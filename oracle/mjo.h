@@ -36,6 +36,7 @@ extern "C" {
 #define MJO_F_ABORT    2u   /* abortive draws */
 #define MJO_F_KUITAN   4u   /* open tanyao */
 #define MJO_F_MULTIRON 8u   /* reserved: multiple ron is always on */
+#define MJO_F_ENDGAME 16u   /* end of game by points: 30,000 to finish, one extra round, the leading dealer may stop */
 
 typedef struct MjoRules {
   uint32_t flags;

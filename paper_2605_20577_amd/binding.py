@@ -7,7 +7,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libmj.so")
 
-F_RED, F_ABORT, F_KUITAN, F_MULTIRON = 1, 2, 4, 8
+F_RED, F_ABORT, F_KUITAN, F_MULTIRON, F_ENDGAME = 1, 2, 4, 8, 16
 RULES_NORED = F_KUITAN | F_MULTIRON
 RULES_RED = F_RED | F_ABORT | F_KUITAN | F_MULTIRON
 MODE_SINGLE, MODE_EAST, MODE_HALF = 0, 1, 2

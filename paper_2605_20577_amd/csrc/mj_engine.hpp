@@ -372,8 +372,23 @@ MJ_HD void finish_kyoku(Ctx &c, bool renchan, bool honba_up)
 {
   int last = c.R.mode == 0 ? 0 : c.R.mode == 1 ? 3 : 7;
   bool over = c.R.mode == 0;
-  for (int s = 0; s < 4; s++) if (SCORE(c, s) < 0) over = true;
-  if (!renchan && c.g.kyoku == last) over = true;
+  const int32_t sc0[4] = {SCORE(c, 0), SCORE(c, 1), SCORE(c, 2), SCORE(c, 3)};
+  for (int s = 0; s < 4; s++) if (sc0[s] < 0) over = true;
+  if ((c.R.flags & F_ENDGAME) && c.R.mode != 0) {
+    // end of game by points: see MJ_F_ENDGAME
+    const int dealer = dealer_of(c), limit = last + 4;
+    const int32_t sd = pick4((uint32_t)sc0[0], (uint32_t)sc0[1], (uint32_t)sc0[2], (uint32_t)sc0[3], dealer);
+    int32_t top = sc0[0];
+    bool lead = true;
+    for (int s = 0; s < 4; s++) {
+      top = sc0[s] > top ? sc0[s] : top;
+      if (s != dealer && sc0[s] >= sd) lead = false;
+    }
+    if (c.g.kyoku >= last) {
+      if (!renchan) { if (top >= 30000 || c.g.kyoku == limit) over = true; }
+      else if ((lead && sd >= 30000) || (c.g.kyoku > last && top >= 30000)) over = true;
+    }
+  } else if (!renchan && c.g.kyoku == last) over = true;
   if (honba_up) { if (c.g.honba < 255) c.g.honba++; } else c.g.honba = 0;
   if (!renchan && !over) c.g.kyoku++;
   if (over) {

@@ -222,3 +222,65 @@ def test_bust_ends_the_game(engine):
     e = act(o, 0, {1: A_RON})
     assert e["score"].tolist() == [-500, 50500, 25000, 25000] and e["terminated"] == 1 and e["kyoku"] == 0
     assert e["final_rank"].tolist() == [3, 0, 1, 2]
+
+
+def _south4(o, scores, dealer_hand, winner_hand=TENPAI):
+    """South 4 (the dealer is seat 3), given points; seat 3 opens by discarding 5p, which completes seat 0's hand
+    (pinfu + tanyao, 2,000 from a non-dealer... paid by the dealer here)"""
+    e = o.export()
+    e["kyoku"][0] = 7
+    e["score"][0] = scores
+    o.import_(e)
+    o.deal_from_wall(0, build_wall([winner_hand, J1, J2, dealer_hand], draws="1m", dora="1z", dealer=3))
+
+
+def test_end_of_game_by_points(engine):
+    """MJ_F_ENDGAME: 30,000 to finish, otherwise one more round; the leading dealer who repeats may stop"""
+    F = mjo.RULES_NORED | mjo.F_ENDGAME
+    # nobody reaches 30,000 in South 4: the game goes on into West 1 (without the flag it ends)
+    for flags, over in ((F, 0), (mjo.RULES_NORED, 1)):
+        o = engine(flags=flags, mode=mjo.MODE_HALF)
+        _south4(o, [26000, 25000, 25000, 24000], "5p " + J3[1:])
+        act(o, 0, {3: kind("5p")})
+        e = act(o, 0, {0: A_RON})
+        assert e["score"].tolist() == [28000, 25000, 25000, 22000] and e["terminated"] == over
+        assert e["kyoku"] == (7 if over else 8)
+    # somebody reaches 30,000 in South 4: over
+    o = engine(flags=F, mode=mjo.MODE_HALF)
+    _south4(o, [28000, 25000, 25000, 22000], "5p " + J3[1:])
+    act(o, 0, {3: kind("5p")})
+    e = act(o, 0, {0: A_RON})
+    assert e["score"].tolist() == [30000, 25000, 25000, 20000] and e["terminated"] == 1
+    assert e["final_rank"].tolist() == [0, 1, 2, 3]
+    # extra round, sudden death: West 2 (kyoku 9, dealer seat 1); seat 0 wins from seat 1 and passes 30,000
+    o = engine(flags=F, mode=mjo.MODE_HALF)
+    e = o.export(); e["kyoku"][0] = 9; e["score"][0] = [28500, 24500, 23500, 23500]; o.import_(e)
+    o.deal_from_wall(0, build_wall([TENPAI, "5p " + J1[1:], J2, J3], draws="1m", dora="1z", dealer=1))
+    act(o, 0, {1: kind("5p")})
+    e = act(o, 0, {0: A_RON})
+    assert e["score"][0] == 30500 and e["terminated"] == 1
+    # the extra round is the last: West 4 (kyoku 11, dealer seat 3) ends the game whatever the points
+    o = engine(flags=F, mode=mjo.MODE_HALF)
+    e = o.export(); e["kyoku"][0] = 11; e["score"][0] = [25000, 25000, 25000, 25000]; o.import_(e)
+    o.deal_from_wall(0, build_wall([TENPAI, J1, J2, "5p " + J3[1:]], draws="1m", dora="1z", dealer=3))
+    act(o, 0, {3: kind("5p")})
+    e = act(o, 0, {0: A_RON})
+    assert e["score"][0] == 27000 and e["terminated"] == 1
+    # the dealer wins South 4 and is alone in the lead with 30,000: the game ends; without the flag the dealer repeats
+    for flags, over in ((F, 1), (mjo.RULES_NORED, 0)):
+        o = engine(flags=flags, mode=mjo.MODE_HALF)
+        e = o.export(); e["kyoku"][0] = 7; e["score"][0] = [24000, 24000, 24000, 28000]; o.import_(e)
+        o.deal_from_wall(0, build_wall(["5p " + J1[1:], J2, J3, TENPAI], draws="1m 9s", dora="1z", dealer=3))
+        act(o, 0, {3: kind("1m")})                               # the dealer draws 1m and lets it go
+        act(o, 0, {0: kind("5p")})                               # seat 0 draws 9s and discards 5p
+        e = act(o, 0, {3: A_RON})                                # dealer: pinfu + tanyao = 2,900
+        assert e["score"].tolist() == [21100, 24000, 24000, 30900] and e["terminated"] == over
+        assert e["kyoku"] == 7 and e["honba"] == 1
+    # the dealer wins South 4 but is not in the lead: play goes on with the dealer repeating
+    o = engine(flags=F, mode=mjo.MODE_HALF)
+    e = o.export(); e["kyoku"][0] = 7; e["score"][0] = [14000, 35000, 24000, 27000]; o.import_(e)
+    o.deal_from_wall(0, build_wall(["5p " + J1[1:], J2, J3, TENPAI], draws="1m 9s", dora="1z", dealer=3))
+    act(o, 0, {3: kind("1m")})
+    act(o, 0, {0: kind("5p")})
+    e = act(o, 0, {3: A_RON})
+    assert e["score"].tolist() == [11100, 35000, 24000, 29900] and e["terminated"] == 0 and e["kyoku"] == 7
