@@ -709,7 +709,9 @@ MJ_HD void mark_passed_ron(Ctx &c, int ron_offered)
 //   5 draw (live wall or replacement tile)
 // then, outside: deal when need_deal is set, and step_finish() for the mask of the seat to move.
 // `acts` packs the four seats' actions as signed bytes (seat s in byte s).
-MJ_HD void step_env(Ctx &c, uint32_t acts)
+// `sampled_ron` >= 0 says that the actions were drawn from the masks by the library's own sampler (they are legal by
+// construction, so stage 0 is skipped) and carries the seats whose mask offered a win.
+MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
 {
   c.need_deal = false;
   c.need_turn = false;
@@ -725,17 +727,20 @@ MJ_HD void step_env(Ctx &c, uint32_t acts)
   }
   // stage 0: an action outside the mask ends the game at once.  The eight mask words are read once, together.
   const int actors = c.g.actor_mask;
-  uint64_t mk0[4], mk1[4];
+  int illegal = 0, ron_offered = sampled_ron;
+  if (sampled_ron < 0) {
+    uint64_t mk0[4], mk1[4];
 #pragma unroll
-  for (int s = 0; s < 4; s++) { mk0[s] = MASK(c, s, 0); mk1[s] = MASK(c, s, 1); }
-  int illegal = 0, ron_offered = 0;
+    for (int s = 0; s < 4; s++) { mk0[s] = MASK(c, s, 0); mk1[s] = MASK(c, s, 1); }
+    ron_offered = 0;
 #pragma unroll
-  for (int s = 0; s < 4; s++) {
-    const int x = act_of(acts, s);
-    const uint64_t w = x < 64 ? mk0[s] : mk1[s];
-    const bool ok = x >= 0 && x < N_ACTIONS && (w >> (x & 63) & 1);
-    if ((actors >> s & 1) && !ok) illegal |= 1 << s;
-    if ((actors >> s & 1) && (mk1[s] >> (A_RON - 64) & 1)) ron_offered |= 1 << s;
+    for (int s = 0; s < 4; s++) {
+      const int x = act_of(acts, s);
+      const uint64_t w = x < 64 ? mk0[s] : mk1[s];
+      const bool ok = x >= 0 && x < N_ACTIONS && (w >> (x & 63) & 1);
+      if ((actors >> s & 1) && !ok) illegal |= 1 << s;
+      if ((actors >> s & 1) && (mk1[s] >> (A_RON - 64) & 1)) ron_offered |= 1 << s;
+    }
   }
   if (illegal) {
     c.g.illegal_seat = (uint8_t)__builtin_ctz((unsigned)illegal);

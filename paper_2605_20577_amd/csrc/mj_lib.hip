@@ -375,13 +375,18 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B,
 }
 
 // the random policy for every acting seat of the lane's environment, packed as four signed bytes
-__device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step)
+// (also notes, in ron_offered, the seats whose mask offers a win: the step needs that and skips its own look at the
+// masks when the actions come from here)
+__device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step, int &ron_offered)
 {
   uint32_t acts = 0xFFFFFFFFu, am = c.g.actor_mask;
+  ron_offered = 0;
   while (am) {
     int s = __builtin_ctz(am);
     am &= am - 1;
-    int a = sample_action(MASK(c, s, 0), MASK(c, s, 1), c.R.seed, c.env_id, step, s);
+    const uint64_t m0 = MASK(c, s, 0), m1 = MASK(c, s, 1);
+    if (m1 >> (A_RON - 64) & 1) ron_offered |= 1 << s;
+    int a = sample_action(m0, m1, c.R.seed, c.env_id, step, s);
     acts = (acts & ~(0xFFu << (8 * s))) | ((uint32_t)(uint8_t)(int8_t)a << (8 * s));
   }
   return acts;
@@ -414,9 +419,10 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
       if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
         refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
       MJ_TICK(c, 10);
-      acts = sample_actors(c, step0 + t);
+      int ron_offered;
+      acts = sample_actors(c, step0 + t, ron_offered);
       MJ_TICK(c, 0);
-      step_env(c, acts);
+      step_env(c, acts, ron_offered);
       MJ_TICK(c, 6);
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }

@@ -51,9 +51,9 @@ static uint32_t pack4(const int a[4])
 {
   return (uint32_t)(uint8_t)a[0] | (uint32_t)(uint8_t)a[1] << 8 | (uint32_t)(uint8_t)a[2] << 16 | (uint32_t)(uint8_t)a[3] << 24;
 }
-static void step_and_deal(Ctx &c, const int a[4])
+static void step_and_deal(Ctx &c, const int a[4], int sampled_ron = -1)
 {
-  step_env(c, pack4(a));
+  step_env(c, pack4(a), sampled_ron);
   if (c.need_deal) deal(c, true);
   step_finish(c);
 }
@@ -111,9 +111,12 @@ void hs_step_random(Sim *h, int n, int auto_reset)
     Ctx c = ctx_of(h, b);
     load_glob(c.e, c.g);
     for (int t = 0; t < n; t++) {
-      int a[4];
-      for (int s = 0; s < 4; s++) a[s] = sample_action(MASK(c, s, 0), MASK(c, s, 1), h->R.seed, c.env_id, h->step + t, s);
-      step_and_deal(c, a);
+      int a[4], ron_offered = 0;                  // as the fused kernel does it: sampled actions skip the legality check
+      for (int s = 0; s < 4; s++) {
+        a[s] = sample_action(MASK(c, s, 0), MASK(c, s, 1), h->R.seed, c.env_id, h->step + t, s);
+        if ((c.g.actor_mask >> s & 1) && (MASK(c, s, 1) >> (A_RON - 64) & 1)) ron_offered |= 1 << s;
+      }
+      step_and_deal(c, a, ron_offered);
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }
     store_glob(c.e, c.g);
