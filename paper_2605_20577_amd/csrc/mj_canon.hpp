@@ -15,7 +15,7 @@ MJ_HD void export_env(const Env &e, MjEnvCanon &o)
   for (int s = 0; s < 4; s++) {
     uint32_t sw = e.seatw[s * n];
     o.discarded_kinds[s] = e.dk[s * n];
-    o.waits[s] = e.waits[s * n];
+    o.waits[s] = e.waits[s * n] & K_ALL;                    // without the facts that ride in the upper bits
     o.mask[s][0] = e.mask[(2 * s) * n]; o.mask[s][1] = e.mask[(2 * s + 1) * n];
     o.yaku[s] = e.yaku[s * n];
     o.score[s] = e.score[s * n]; o.delta[s] = e.delta[s * n]; o.gain[s] = e.gain[s * n];

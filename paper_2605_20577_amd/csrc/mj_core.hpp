@@ -42,6 +42,11 @@ enum { MT_CHI = 1, MT_PON = 2, MT_MINKAN = 3, MT_ANKAN = 4, MT_KAKAN = 5 };
 constexpr uint64_t K_TERMINALS = 0x4060301ull;                       // kinds 0,8,9,17,18,26
 constexpr uint64_t K_HONORS = 0x7Full << 27;
 constexpr uint64_t K_YAOCHU = K_TERMINALS | K_HONORS;
+// "Facts" of a hand, kept next to the caches that depend on it so that a hand which changed in one suit costs one
+// table probe instead of four: tile count mod 3 of suit s in bits 2s..2s+1, "suit s is a valid pattern" in bit 8+s.
+// They ride in bits 40..51 of a waits word (W_FACTS_VALID set) and of the tenpai-discards word (TD_FACTS set).
+constexpr int FACTS_SHIFT = 40;
+constexpr uint64_t W_FACTS_VALID = 1ull << 52, TD_FACTS = 1ull << 52;
 constexpr uint64_t TD_UNKNOWN = 1ull << 62;     // tenpai_discards_of without the search: "some discard may keep tenpai"
 constexpr uint64_t TD_VALID = 1ull << 63;       // Env::tdisc holds the tenpai-keeping discards of the hand as it is now
 constexpr uint64_t K_WINDS = 0xFull << 27;
@@ -327,19 +332,12 @@ MJ_HD uint64_t own4_mask(const uint32_t h[4], uint64_t meldw, int n_meld)
   return (uint64_t)squeeze9((o0 >> 2) & O111) | (uint64_t)squeeze9((o1 >> 2) & O111) << 9 |
          (uint64_t)squeeze9((o2 >> 2) & O111) << 18 | (uint64_t)squeeze9((o3 >> 2) & O111) << 27;
 }
-// cheap necessary conditions for the two special forms: kinds held at least twice; tiles that are neither terminals nor honors
+// cheap necessary condition for seven pairs: kinds held at least twice
 MJ_HD int kinds_held_twice(const uint32_t h[4])
 {
   int n = 0;
 #pragma unroll
   for (int su = 0; su < 4; su++) n += popc32(((h[su] >> 1) | (h[su] >> 2)) & O111);
-  return n;
-}
-MJ_HD int simple_tiles(const uint32_t h[4])
-{
-  int n = 0;
-#pragma unroll
-  for (int su = 0; su < 3; su++) n += tiles_in(h[su] & ~(7u | 7u << 24));
   return n;
 }
 struct SpecialCounts { int c1, c2, c3, c4, yao_tiles, total; };
@@ -363,11 +361,38 @@ MJ_HD uint64_t kinds_where(const uint32_t h[4], int v)     // 34-bit mask of kin
   return m;
 }
 
-// Waits of a (13 - 3*n_meld)-tile hand: kinds whose addition completes it and
-// of which the seat owns fewer than four.
-MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
+// at most `limit` (0 or 1) tiles that are neither terminals nor honors (no counting: masks only)
+MJ_HD bool few_simples(const uint32_t h[4], int limit)
 {
-  const Lut &L = *Lp;
+  const uint32_t inner = ~(7u | 7u << 24);
+  const uint32_t a = h[0] & inner, b = h[1] & inner, c = h[2] & inner;
+  if (limit == 0) return (a | b | c) == 0;
+  const int kinds = popc32(fields_nonzero(a)) + popc32(fields_nonzero(b)) + popc32(fields_nonzero(c));
+  return kinds <= 1 && ((a | b | c) & (O111 * 6u)) == 0;          // one kind at most, held once
+}
+MJ_HD uint32_t hand_facts(const Lut &L, const uint32_t h[4])     // four probes
+{
+  uint32_t f = 0;
+#pragma unroll
+  for (int s = 0; s < 4; s++) {
+    f |= (uint32_t)(tiles_in(h[s]) % 3) << (2 * s);
+    if (suit_valid(L, s, h[s])) f |= 1u << (8 + s);
+  }
+  return f;
+}
+MJ_HD uint32_t facts_update(const Lut &L, uint32_t f, int su, uint32_t hw)      // suit su changed to hw: one probe
+{
+  const uint32_t rem = (uint32_t)(tiles_in(hw) % 3);
+  const bool v = su == 3 ? honors_valid(hw) : lut_valid(L, hw);
+  return (f & ~(3u << (2 * su)) & ~(1u << (8 + su))) | rem << (2 * su) | (v ? 1u << (8 + su) : 0u);
+}
+
+// Waits of a (13 - 3*n_meld)-tile hand: kinds whose addition completes it and of which the seat owns fewer than
+// four, in bits 0..33; the hand's facts ride along in bits 40..52 (see above).  waits_from_facts takes the facts as
+// given, waits_of looks them up.
+MJ_HD uint64_t waits_from_facts(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld,
+                                uint32_t facts)
+{
   MJ_STAT(n_waits);
   const uint32_t h[4] = {h0, h1, h2, h3};
   uint64_t w = 0;
@@ -375,10 +400,10 @@ MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, ui
   uint32_t bad = 0, nonzero = 0;
 #pragma unroll
   for (int s = 0; s < 4; s++) {
-    const int rem = tiles_in(h[s]) % 3;
+    const int rem = (int)(facts >> (2 * s) & 3u);
     r1 += rem == 1; r2 += rem == 2;
     if (rem != 0) nonzero |= 1u << s;
-    if (rem == 1 || !suit_valid(L, s, h[s])) bad |= 1u << s;
+    if (rem == 1 || !(facts >> (8 + s) & 1u)) bad |= 1u << s;
   }
   // standard form: the suit that takes the tile has remainder 1 (it then holds the pair) or is one of two
   // suits with remainder 2; every other suit must already be valid.  With remainder pattern (1,0,0,0) the
@@ -392,7 +417,7 @@ MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, ui
       w |= (uint64_t)suit_addmask(Lp, s, pick4(h0, h1, h2, h3, s)) << (9 * s);
     }
   }
-  if (n_meld == 0 && (kinds_held_twice(h) == 6 || simple_tiles(h) == 0)) {
+  if (n_meld == 0 && (kinds_held_twice(h) == 6 || few_simples(h, 0))) {
     SpecialCounts c = special_counts(h);
     if (c.c2 == 6 && c.c1 == 1 && c.c3 == 0 && c.c4 == 0) w |= kinds_where(h, 1);      // seven pairs
     if (c.yao_tiles == c.total && c.c3 == 0 && c.c4 == 0) {                            // thirteen orphans
@@ -401,7 +426,12 @@ MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, ui
     }
   }
   if (w) w &= ~own4_mask(h, meldw, n_meld);
-  return w;
+  return w | (uint64_t)facts << FACTS_SHIFT | W_FACTS_VALID;
+}
+MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld)
+{
+  const uint32_t h[4] = {h0, h1, h2, h3};
+  return waits_from_facts(Lp, h0, h1, h2, h3, meldw, n_meld, hand_facts(*Lp, h));
 }
 
 // Kinds whose discard leaves the 14 - 3*n_meld tiles of a hand tenpai (non-empty waits_of).  Per suit, three
@@ -411,23 +441,23 @@ MJ_HD uint64_t waits_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, ui
 // candidate, and that case needs the three other suits to be valid already.
 // With exact == false only the cheap necessary conditions are tested: the result is 0 (no discard keeps tenpai)
 // or TD_UNKNOWN.
-MJ_HD uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
-                                           int n_meld, bool exact)
+MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw,
+                                          int n_meld, bool exact, uint32_t facts)
 {
   const Lut &L = *Lp;
   MJ_STAT(n_tenpai);
   const uint32_t h[4] = {h0, h1, h2, h3};
-  uint32_t remp = 0, valid = 0;
+  const uint32_t remp = facts & 0xFFu;
+  uint32_t valid = 0;
   int t1 = 0, t2 = 0;
 #pragma unroll
   for (int s = 0; s < 4; s++) {
-    const int r = tiles_in(h[s]) % 3;
-    remp |= (uint32_t)r << (2 * s);
+    const int r = (int)(remp >> (2 * s) & 3u);
     t1 += r == 1; t2 += r == 2;
-    if (r != 1 && suit_valid(L, s, h[s])) valid |= 1u << s;
+    if (r != 1 && (facts >> (8 + s) & 1u)) valid |= 1u << s;
   }
   uint64_t out = 0;
-  const bool special = n_meld == 0 && (kinds_held_twice(h) >= 6 || simple_tiles(h) <= 1);
+  const bool special = n_meld == 0 && (kinds_held_twice(h) >= 6 || few_simples(h, 1));
   const bool standard = popc32(~valid & 15u) <= 2;      // a discard and a draw touch at most two suits
   if (!exact) return (standard || special) ? TD_UNKNOWN : 0;
   if (standard) {                       // rare: the search proper
@@ -497,6 +527,13 @@ MJ_HD uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint3
     }
   }
   return out;
+}
+
+MJ_HD uint64_t tenpai_discards_of(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, uint64_t meldw, int n_meld,
+                                  bool exact)
+{
+  const uint32_t h[4] = {h0, h1, h2, h3};
+  return tenpai_discards_from_facts(Lp, h0, h1, h2, h3, meldw, n_meld, exact, hand_facts(*Lp, h));
 }
 
 // ------------------------------------------------------------------ shanten

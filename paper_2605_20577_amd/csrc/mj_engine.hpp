@@ -192,7 +192,7 @@ MJ_HD void turn_mask(Ctx &c)
   const int drawn_k = c.g.drawn == 255 ? -1 : code_kind(c.g.drawn);
   const uint32_t sw = SW(c, s);
   const uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
-  const uint64_t mw = MELDW(c, s), waits = WAITS(c, s);
+  const uint64_t mw = MELDW(c, s), wfull = WAITS(c, s), waits = wfull & K_ALL;
   const int riichi = (int)sw_get(sw, SW_RIICHI, 2), n_meld = (int)sw_get(sw, SW_NMELD, 3);
   MJ_TICK(c, 11);
 
@@ -202,9 +202,18 @@ MJ_HD void turn_mask(Ctx &c)
   bool menzen = true;
   for (int j = 0; j < n_meld; j++) if (m_type(meld_at(mw, j)) != MT_ANKAN) menzen = false;
   const bool may_riichi = !c.g.riichi_pending && !riichi && drawn_k >= 0 && menzen && SCORE(c, s) >= 1000 && c.g.live_left >= 4;
-  uint64_t td = 0;
-  if (!riichi) td = tenpai_discards_of(&c.L, h[0], h[1], h[2], h[3], mw, n_meld, may_riichi || c.g.riichi_pending);
-  TD(c) = (td & TD_UNKNOWN) ? 0 : td | TD_VALID;        // the set itself is only searched for when the mask needs it
+  // The hand differs from the 13 - 3m tiles whose facts sit in the waits word by the tile drawn, or by the tiles a
+  // call took (all of the called tile's suit): one probe brings the facts up to date.
+  const int changed = drawn_k >= 0 ? drawn_k : (c.g.kuikae0 != 255 ? (int)c.g.kuikae0 : -1);
+  uint32_t facts;
+  if ((wfull & W_FACTS_VALID) && changed >= 0) {
+    const int cs = suit_of(changed);
+    facts = facts_update(c.L, (uint32_t)(wfull >> FACTS_SHIFT) & 0xFFFu, cs, pick4(h[0], h[1], h[2], h[3], cs));
+  } else facts = hand_facts(c.L, h);
+  const bool exact = !riichi && (may_riichi || c.g.riichi_pending);        // the set itself is only searched for when
+  uint64_t td = 0;                                                         // the mask needs it
+  if (exact) td = tenpai_discards_from_facts(&c.L, h[0], h[1], h[2], h[3], mw, n_meld, true, facts);
+  TD(c) = (exact || riichi ? td | TD_VALID : 0) | (uint64_t)facts << FACTS_SHIFT | TD_FACTS;
   MJ_TICK(c, 14);
   if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
     HandOut r;
@@ -221,8 +230,8 @@ MJ_HD void turn_mask(Ctx &c)
       const int su = suit_of(drawn_k);
       const uint32_t four = 4u << (3 * rank_of(drawn_k, su));
       const uint64_t mw2 = mw | (uint64_t)m_make(MT_ANKAN, drawn_k, 0, 0, 0, 0) << (16 * n_meld);
-      if (waits_of(&c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
-                   h[3] - (su == 3 ? four : 0u), mw2, n_meld + 1) == waits)
+      if ((waits_of(&c.L, h[0] - (su == 0 ? four : 0u), h[1] - (su == 1 ? four : 0u), h[2] - (su == 2 ? four : 0u),
+                   h[3] - (su == 3 ? four : 0u), mw2, n_meld + 1) & K_ALL) == waits)
         set_action(m, A_KAN + drawn_k);
     }
   } else {
@@ -456,7 +465,7 @@ MJ_HD void exhaustive_draw(Ctx &c)
   clear_result(c);
   c.g.end_type = 3;
   int T = 0;
-  for (int s = 0; s < 4; s++) if (WAITS(c, s) != 0 || swf(c, s, SW_RIICHI, 2)) T |= 1 << s;
+  for (int s = 0; s < 4; s++) if ((WAITS(c, s) & K_ALL) != 0 || swf(c, s, SW_RIICHI, 2)) T |= 1 << s;
   c.g.tenpai_mask = (uint8_t)T;
   int n = popc32((uint32_t)T);
   if (n >= 1 && n <= 3) {
@@ -804,15 +813,17 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   MJ_TICK(c, 2);
   // stage 2: the seat whose concealed hand is back to 13 - 3 * melds tiles gets its waits refreshed
   if (waits_seat >= 0) {
-    bool search = true;
-    if (waits_k >= 0) {                    // a discard: the cache made with the turn's mask says whether any wait is left
-      const uint64_t td = TD(c);
-      if (td & TD_VALID) {
-        search = td >> waits_k & 1;
-        if (!search) WAITS(c, waits_seat) = 0;
-      }
-    }
-    if (search) refresh_waits(c, waits_seat);
+    const uint64_t td = TD(c);
+    if (waits_k >= 0 && (td & TD_FACTS)) {
+      // a discard: the facts of the 14-tile hand came with the turn's mask, the discard changed one suit; the set of
+      // tenpai-keeping discards, when it was searched for, says at once whether any wait is left
+      const int cs = suit_of(waits_k);
+      const uint32_t facts = facts_update(c.L, (uint32_t)(td >> FACTS_SHIFT) & 0xFFFu, cs, HW(c, waits_seat, cs));
+      if ((td & TD_VALID) && !(td >> waits_k & 1)) WAITS(c, waits_seat) = (uint64_t)facts << FACTS_SHIFT | W_FACTS_VALID;
+      else
+        WAITS(c, waits_seat) = waits_from_facts(&c.L, HW(c, waits_seat, 0), HW(c, waits_seat, 1), HW(c, waits_seat, 2),
+                                                HW(c, waits_seat, 3), MELDW(c, waits_seat), swf(c, waits_seat, SW_NMELD, 3), facts);
+    } else refresh_waits(c, waits_seat);
   }
   MJ_TICK(c, 3);
   // stage 3: responses of the other seats

@@ -159,7 +159,9 @@ inline std::vector<uint32_t> build_shanten_table(int n_ranks, bool runs)
   for (int r = 1; r <= n_ranks; r++) pw[r] = pw[r - 1] * 5;
   const int N = pw[n_ranks];
   std::vector<Frontier> F((size_t)N);
-  for (int m = 0; m < 5; m++) { F[0].n[m] = m == 0 ? 0 : -1; F[0].h[m] = -1; }
+  Frontier empty;
+  for (int m = 0; m < 5; m++) { empty.n[m] = m == 0 ? 0 : -1; empty.h[m] = -1; }
+  F[0] = empty;
   std::vector<uint32_t> out((size_t)N);
   out[0] = pack_frontier(F[0]);
   for (int key = 1; key < N; key++) {

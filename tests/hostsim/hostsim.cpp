@@ -207,7 +207,7 @@ uint64_t hs_waits(Sim *h, const uint8_t *hand, const uint16_t *meld, int n_meld)
   for (int k = 0; k < 34; k++) { int su = suit_of(k); hw[su] |= (uint32_t)hand[k] << (3 * rank_of(k, su)); }
   uint64_t mw = 0;
   for (int j = 0; j < 4; j++) mw |= (uint64_t)meld[j] << (16 * j);
-  return waits_of(&h->L, hw[0], hw[1], hw[2], hw[3], mw, n_meld);
+  return waits_of(&h->L, hw[0], hw[1], hw[2], hw[3], mw, n_meld) & K_ALL;
 }
 
 uint64_t hs_tenpai_discards(Sim *h, const uint8_t *hand, const uint16_t *meld, int n_meld)
