@@ -183,7 +183,9 @@ int mj_step(MjHandle *h, const int8_t *d_actions /*[B][4]*/, void *stream);
 int mj_legal_mask(const MjHandle *h, uint64_t *d_mask /*[B][4][2]*/, void *stream);
 
 /* observation (section 3.2, ego-centric; this library's plane layout):
- * d_obs[b][seat][56][34], bytes 0/1, seen from `seat`. */
+ * d_obs[b][seat][56][34], bytes 0/1, seen from `seat`.  The kernel hands out
+ * its work through counters in d_scratch: two mj_observe calls on one handle
+ * must be ordered (same stream, or an event between them). */
 int mj_observe(const MjHandle *h, uint8_t *d_obs /*[B][4][56][34]*/, void *stream);
 
 /* token observation (section 3.2, see MjTokenObs): d_out[b][seat], seen from

@@ -581,24 +581,33 @@ __global__ void __launch_bounds__(kAuxBlock, MJ_OCC) k_eval_hands(DevTables T, i
   out[i] = r;
 }
 
-// Observation writer.  A block takes kObsEnvs environments at a time:
+// Observation writer.  Blocks stay resident and take groups of kObsEnvs environments in order from a device counter
+// (ctr[0]; ctr[1] counts the blocks that have left, and the last one sets both back to zero), so launches of one
+// handle must not overlap.  For each group:
 //  1. 4 lanes per env build the per-seat masks, then one lane per env the env masks (LDS);
 //  2. one lane per (env, viewer) concatenates the 56 planes of 34 bits into a 1904-bit string (LDS);
 //  3. all lanes expand bits to bytes, 16 bytes per store, consecutive lanes on consecutive addresses.
-constexpr int kObsEnvs = 32;             // 49 KB of LDS per block; 16 per block reached 3.9 TB/s, 32 reach 5.2 TB/s
+constexpr int kObsEnvs = 32;             // 49 KB of LDS per block; 16 per group reached 3.9 TB/s, 32 reach 5.2 TB/s
 constexpr int kObsBits = 56 * 34;                 // 1904
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kObsWords = 60;                     // u32 words per (env, viewer), 1920 bits
 
-__global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, uint32_t rule_flags, uint8_t *obs)
+__global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, uint32_t rule_flags, uint8_t *obs, unsigned *ctr)
 {
   __shared__ uint64_t S[kObsEnvs][4][OB_SEAT_WORDS];
   __shared__ uint64_t G[kObsEnvs][OG_WORDS];
   __shared__ uint64_t R[kObsEnvs][4];
   __shared__ uint32_t own_red[kObsEnvs][4];
   __shared__ uint32_t bits[kObsEnvs][4][kObsWords];
+  __shared__ unsigned next_group;
   const int tid = threadIdx.x;
-  for (int64_t base = (int64_t)blockIdx.x * kObsEnvs; base < B; base += (int64_t)gridDim.x * kObsEnvs) {
+  const int64_t n_groups = (B + kObsEnvs - 1) / kObsEnvs;
+  for (;;) {
+    if (tid == 0) next_group = atomicAdd(&ctr[0], 1u);
+    __syncthreads();
+    const int64_t grp = next_group;           // the barrier at the end of the round keeps it until every lane has read it
+    if (grp >= n_groups) break;
+    const int64_t base = grp * kObsEnvs;
     int nenv = (int)((B - base) < kObsEnvs ? (B - base) : kObsEnvs);
     if (tid < 4 * nenv) {
       int el = tid >> 2, s = tid & 3;
@@ -652,6 +661,8 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
     }
     __syncthreads();
   }
+  // the last block to leave rearms both counters for the next launch
+  if (tid == 0 && atomicAdd(&ctr[1], 1u) == gridDim.x - 1) { atomicExch(&ctr[0], 0u); atomicExch(&ctr[1], 0u); }
 }
 
 // Token observation.  One lane per (environment, seat).  What the four viewers of a game share is computed once:
@@ -725,6 +736,8 @@ struct MjHandle {
   void *d_state, *d_scratch;
   DevTables T;
   const uint32_t *sh_suit, *sh_honor;    // block tables of the shanten number (device)
+  unsigned *obs_ctr;                     // work counters of the observation writer (device, zero between launches)
+  int n_cu;
   size_t lds_bytes, probe_bytes;
   int lpw;
   hipEvent_t ev[2];
@@ -750,7 +763,7 @@ const std::vector<uint32_t> &sh_honor_table()
   return t;
 }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-struct ScratchLayout { size_t probe, base, rowrank, keyinfo, recs, sh_suit, sh_honor, total, probe_bytes; };
+struct ScratchLayout { size_t probe, base, rowrank, keyinfo, recs, sh_suit, sh_honor, counters, total, probe_bytes; };
 ScratchLayout scratch_layout()
 {
   const mjt::SuitTables &t = tables();
@@ -763,7 +776,8 @@ ScratchLayout scratch_layout()
   s.recs = align256(s.keyinfo + t.keyinfo.size() * 4);
   s.sh_suit = align256(s.recs + t.recs.size() * 4);
   s.sh_honor = align256(s.sh_suit + sh_suit_table().size() * 4);
-  s.total = align256(s.sh_honor + sh_honor_table().size() * 4);
+  s.counters = align256(s.sh_honor + sh_honor_table().size() * 4);
+  s.total = s.counters + 256;
   return s;
 }
 size_t scratch_bytes_impl() { return scratch_layout().total; }
@@ -830,7 +844,8 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   if (t.rowid.size() != (size_t)kRowIdBytes || (sl.probe_bytes & 15)) { delete h; return MJ_E_UNSUPPORTED; }
   int dev = 0, lds_max = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) { delete h; return MJ_E_HIP; }
+      hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+      hipDeviceGetAttribute(&h->n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || h->n_cu <= 0) { delete h; return MJ_E_HIP; }
   h->lpw = pick_lpw(B);
   h->lds_bytes = step_lds_bytes((int)sl.probe_bytes, 64);
   h->probe_bytes = sl.probe_bytes;
@@ -857,6 +872,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   h->T.probe_bytes = (int)sl.probe_bytes;
   h->sh_suit = (const uint32_t *)(sc + sl.sh_suit);
   h->sh_honor = (const uint32_t *)(sc + sl.sh_honor);
+  h->obs_ctr = (unsigned *)(sc + sl.counters);
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[0]));
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[1]));
   if (rc != MJ_OK) { delete h; return rc; }
@@ -886,8 +902,12 @@ int mj_observe(const MjHandle *h, uint8_t *d_obs, void *stream)
 {
   if (!h || !d_obs || ((uintptr_t)d_obs & 15)) return MJ_E_ARG;
   int64_t groups = (h->B + kObsEnvs - 1) / kObsEnvs;
-  unsigned grid = (unsigned)(groups < 65536 ? groups : 65536);
-  k_observe<<<grid, kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, d_obs);
+  // three blocks fit a compute unit (LDS); they take the groups of 32 games in order from a counter, so that the
+  // blocks in flight write one compact, advancing window of the tensor (measured: 5.8 TB/s against 5.3 TB/s with
+  // one block per group in launch order)
+  const int64_t resident = (int64_t)h->n_cu * 3;
+  unsigned grid = (unsigned)(groups < resident ? groups : resident);
+  k_observe<<<grid, kAuxBlock, 0, (hipStream_t)stream>>>(h->d_state, h->B, h->R.flags, d_obs, h->obs_ctr);
   return check(hipGetLastError());
 }
 

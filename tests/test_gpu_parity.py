@@ -99,6 +99,20 @@ def test_fused_rollout_many_games():
     assert np.array_equal(o.observe(), g.observe())
 
 
+def test_observation_more_groups_than_resident_blocks():
+    """40,003 games are 1,251 groups of 32 for the observation writer, more than the blocks it keeps resident, so every
+    block takes several groups from the work counter; a second launch checks that the counters were set back"""
+    B = 40003
+    o = mjo.Oracle(B, 21, mjo.RULES_RED, mjo.MODE_HALF)
+    g = GpuEngine(B, seed=21, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    o.step_random(40); g.step_random(40)
+    want = o.observe()
+    assert np.array_equal(want, g.observe())
+    assert np.array_equal(want, g.observe())
+    o.step_random(5); g.step_random(5)
+    assert np.array_equal(o.observe(), g.observe())
+
+
 @pytest.mark.parametrize("flags,lpw,seed", [(mjo.RULES_NORED, 32, 3), (mjo.RULES_RED, 64, 4),
                                             (mjo.RULES_RED | mjo.F_ENDGAME, 32, 5)])
 def test_fused_rollout_large(flags, lpw, seed, monkeypatch):
