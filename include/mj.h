@@ -45,6 +45,16 @@ extern "C" {
                                 somebody has 30,000; otherwise at most one more round is played, ending after any
                                 kyoku that leaves somebody at 30,000; a dealer who repeats in the last regular
                                 kyoku or later ends the game when alone in the lead with 30,000 */
+#define MJ_F_KANDORA_LATE 32u /* the indicator of an open kan or of a tile added to a pon is turned when the seat
+                                discards (before the discard is answered) or declares another kan, so a win on the
+                                replacement tile does not count it; a concealed kan still turns it at once.
+                                Off: every kan turns its indicator at once */
+#define MJ_F_NAGASHI 64u      /* at an exhaustive draw a seat whose river holds terminals and honors only, none of
+                                them claimed, is paid as for a self-drawn mangan (no counter bonus, deposits stay,
+                                no payments for tenpai); end_type 10, winners = the seats paid.  Off: no such payment */
+#define MJ_F_ANKAN_ROB 128u   /* a hand waiting as thirteen orphans may win on the tile of a concealed kan: the offer
+                                uses phase 2 like an added kan, kakan_tile carries bit 7 (0x80) then, and a pass lets
+                                the kan go on.  Off: a concealed kan can not be robbed */
 #define MJ_RULES_NORED (MJ_F_KUITAN | MJ_F_MULTIRON)
 #define MJ_RULES_RED   (MJ_F_RED | MJ_F_ABORT | MJ_F_KUITAN | MJ_F_MULTIRON)
 
@@ -102,7 +112,8 @@ typedef struct MjEnvCanon {
            last_discard, last_discarder, kakan_tile, kuikae[2],
            first_wind, same_wind_cnt, illegal_seat;
   uint8_t  end_type, winners, loser, tenpai_mask;
-  uint8_t  pad_[2];
+  uint8_t  dora_pending;         /* kan indicators not turned yet (MJ_F_KANDORA_LATE) */
+  uint8_t  pad_[1];
 } MjEnvCanon;
 
 /* one hand to evaluate (64 bytes) and its value (24 bytes) */

@@ -745,7 +745,7 @@ static void deal(MjoHandle *h, int64_t b, int reshuffle)
   memset(e->furiten_riichi, 0, 4);
   memset(e->kan_by, 0, 4);
   memset(e->discarded_kinds, 0, sizeof e->discarded_kinds);
-  e->draw_ptr = 52; e->n_kan = 0; e->live_left = 70; e->n_dora = 1;
+  e->draw_ptr = 52; e->n_kan = 0; e->live_left = 70; e->n_dora = 1; e->dora_pending = 0;
   e->drawn = 255; e->riichi_pending = 0; e->rinshan = 0;
   e->last_discard = 255; e->last_discarder = 255; e->kakan_tile = 255;
   e->kuikae[0] = e->kuikae[1] = 255;
@@ -874,7 +874,30 @@ static void exhaustive_draw(MjoHandle *h, int64_t b)
   int T = 0, n = 0;
   for (int s = 0; s < 4; s++) if (e->waits[s] || e->riichi[s]) { T |= 1 << s; n++; }
   e->tenpai_mask = (uint8_t)T;
-  if (n >= 1 && n <= 3) {
+  /* Reading (the paper names the rule set, section 3.2, not this detail), with MJO_F_NAGASHI: a seat whose river
+   * holds terminals and honors only, none of them claimed by another seat, is paid as for a self-drawn mangan
+   * (4000 from or to the dealer, 2000 between the others), without counter bonus; deposits stay on the table.
+   * Several seats can qualify; the payments for tenpai are not made then.  The dealer still repeats when tenpai
+   * and the counter goes up, as after any exhaustive draw.  end_type 10, winners = the seats paid. */
+  int N = 0;
+  if (h->rules.flags & MJO_F_NAGASHI)
+    for (int s = 0; s < 4; s++) {
+      int ok = e->n_river[s] > 0;
+      for (int i = 0; i < e->n_river[s]; i++)
+        if (!is_yaochu(e->river[s][i] & 63) || (e->river[s][i] & 0x80)) ok = 0;
+      if (ok) N |= 1 << s;
+    }
+  if (N) {
+    int dealer = dealer_of(e);
+    e->end_type = 10;
+    e->winners = (uint8_t)N;
+    for (int w = 0; w < 4; w++) if (N >> w & 1)
+      for (int o = 0; o < 4; o++) if (o != w) {
+        int32_t pay = (w == dealer || o == dealer) ? 4000 : 2000;
+        e->score[o] -= pay; e->delta[o] -= pay;
+        e->score[w] += pay; e->delta[w] += pay; e->gain[w] += pay;
+      }
+  } else if (n >= 1 && n <= 3) {
     int32_t give = 3000 / (4 - n), get = 3000 / n;
     for (int s = 0; s < 4; s++) {
       int32_t x = (T >> s & 1) ? get : -give;
@@ -901,13 +924,25 @@ static void advance(MjoHandle *h, int64_t b)
   turn_mask(h, e);
 }
 
-/* the replacement draw that completes any kan */
-static void finish_kan(MjoHandle *h, int64_t b)
+/* indicators of earlier open / added kans that wait to be turned are turned now */
+static void turn_pending_indicators(E *e)
+{
+  e->n_dora = (uint8_t)(e->n_dora + e->dora_pending);
+  e->dora_pending = 0;
+}
+
+/* the replacement draw that completes any kan; `open` = a kan from a discard or a tile added to a pon */
+static void finish_kan(MjoHandle *h, int64_t b, int open)
 {
   E *e = &h->env[b];
   int s = e->cur;
   e->kan_by[s]++;
-  e->n_dora++;                            /* reading: the new indicator is shown at once for every kan type */
+  /* Reading (the paper names the rule set, section 3.2, not this detail): by default the new indicator is shown at
+   * once for every kan type.  With MJO_F_KANDORA_LATE only a concealed kan shows it at once; after an open or
+   * added kan it is turned when the seat discards (before anyone answers that discard) or declares another kan,
+   * so a win on the replacement tile does not count it. */
+  if ((h->rules.flags & MJO_F_KANDORA_LATE) && open) e->dora_pending++;
+  else e->n_dora++;
   int id = e->wall[122 + e->n_kan];
   e->n_kan++;
   e->live_left--;
@@ -997,6 +1032,7 @@ static void response_options(const MjoHandle *h, E *e, int o, int d, int code, u
 static void discard(MjoHandle *h, int64_t b, int s, int k, int red)
 {
   E *e = &h->env[b];
+  turn_pending_indicators(e);
   e->hand[s][k]--;
   if (red) e->hand_red[s] &= (uint8_t)~(1 << (k / 9));
   e->river[s][e->n_river[s]++] = (uint8_t)(k | red << 6);
@@ -1061,7 +1097,7 @@ static void do_call(MjoHandle *h, int64_t b, int s, int a)
     remove_from_hand(e, s, k, tr ? 2 : 3, tr);
     e->meld[s][j] = m_make(M_MINKAN, k, from_rel, 0, tr || cred, cred);
     refresh_waits(e, s);
-    finish_kan(h, b);
+    finish_kan(h, b, 1);
   } else {
     int pos = (a - MJO_A_CHI_L) % 3, tr = a >= MJO_A_CHI_L_RED;
     int base = k - pos;
@@ -1078,19 +1114,60 @@ static void do_call(MjoHandle *h, int64_t b, int s, int a)
   }
 }
 
+/* Seats other than s that can win on kind k of a kan that s has just declared get RON and PASS in m; returns
+ * them as a bit set.  A seat whose hand the tile completes but that may not win on it becomes furiten.
+ * `orphans_only`: only the thirteen orphans count (the tile of a concealed kan, MJO_F_ANKAN_ROB). */
+static int offer_rob(MjoHandle *h, E *e, int s, int k, int orphans_only, uint64_t m[4][2])
+{
+  int any = 0;
+  for (int o = 0; o < 4; o++) if (o != s) {
+    e->hand[o][k]++;
+    int shape = orphans_only ? (e->n_meld[o] == 0 && thirteen_orphans(e->hand[o])) : mjo_is_complete(e->hand[o], e->n_meld[o]);
+    e->hand[o][k]--;
+    if (!shape) continue;
+    int ok = 0;
+    if (!furiten(e, o)) {
+      MjoHandResult r;
+      eval_seat(h, e, o, k, 0, 1, &r);
+      ok = r.yaku_ok;
+    }
+    if (ok) { set_bit(m[o], MJO_A_RON); set_bit(m[o], MJO_A_PASS); any |= 1 << o; }
+    else if (e->riichi[o]) e->furiten_riichi[o] = 1;
+    else e->furiten_temp[o] = 1;
+  }
+  return any;
+}
+
 /* KAN action on the own turn: concealed kan with four in hand, otherwise a
  * tile added to an own pon (which the other seats may rob). */
 static void own_kan(MjoHandle *h, int64_t b, int k)
 {
   E *e = &h->env[b];
   int s = e->cur;
+  turn_pending_indicators(e);
   if (e->hand[s][k] == 4) {
     int tr = is_five(k) && (e->hand_red[s] >> (k / 9) & 1);
     remove_from_hand(e, s, k, tr ? 3 : 4, tr);
     e->meld[s][e->n_meld[s]++] = m_make(M_ANKAN, k, 0, 0, tr, 0);
     e->drawn = 255;
     refresh_waits(e, s);
-    finish_kan(h, b);
+    /* Reading (section 3.2 names the rule set, not this detail), with MJO_F_ANKAN_ROB: a hand that waits for this
+     * tile as thirteen orphans may win on it; the offer uses the phase of the added kan, the tile code carries
+     * bit 7 to tell the two apart, and a pass lets the kan go on. */
+    if ((h->rules.flags & MJO_F_ANKAN_ROB) && is_yaochu(k)) {
+      uint64_t m[4][2];
+      memset(m, 0, sizeof m);
+      int any = offer_rob(h, e, s, k, 1, m);
+      if (any) {
+        e->kakan_tile = (uint8_t)(k | 0x80);
+        clear_masks(e);
+        e->phase = MJO_RESPOND_KAKAN;
+        e->actor_mask = (uint8_t)any;
+        memcpy(e->mask, m, sizeof m);
+        return;
+      }
+    }
+    finish_kan(h, b, 0);
     return;
   }
   int tr = is_five(k) && (e->hand_red[s] >> (k / 9) & 1);
@@ -1105,24 +1182,9 @@ static void own_kan(MjoHandle *h, int64_t b, int k)
   e->kakan_tile = (uint8_t)(k | tr << 6);
   e->drawn = 255;
   refresh_waits(e, s);
-  int any = 0;
   uint64_t m[4][2];
   memset(m, 0, sizeof m);
-  for (int o = 0; o < 4; o++) if (o != s) {
-    e->hand[o][k]++;
-    int shape = mjo_is_complete(e->hand[o], e->n_meld[o]);
-    e->hand[o][k]--;
-    if (!shape) continue;
-    int ok = 0;
-    if (!furiten(e, o)) {
-      MjoHandResult r;
-      eval_seat(h, e, o, k, 0, 1, &r);
-      ok = r.yaku_ok;
-    }
-    if (ok) { set_bit(m[o], MJO_A_RON); set_bit(m[o], MJO_A_PASS); any |= 1 << o; }
-    else if (e->riichi[o]) e->furiten_riichi[o] = 1;
-    else e->furiten_temp[o] = 1;
-  }
+  int any = offer_rob(h, e, s, k, 0, m);
   if (any) {
     clear_masks(e);
     e->phase = MJO_RESPOND_KAKAN;
@@ -1130,7 +1192,7 @@ static void own_kan(MjoHandle *h, int64_t b, int k)
     memcpy(e->mask, m, sizeof m);
     return;
   }
-  finish_kan(h, b);
+  finish_kan(h, b, 1);
 }
 
 static void mark_passed_ron(E *e)
@@ -1186,7 +1248,7 @@ static void step_env(MjoHandle *h, int64_t b, const int8_t a[4])
     for (int s = 0; s < 4; s++) if ((e->actor_mask >> s & 1) && a[s] == MJO_A_RON) ronners |= 1 << s;
     if (ronners) { win(h, b, ronners, 0, e->cur, t_kind(e->kakan_tile), 1); return; }
     mark_passed_ron(e);
-    finish_kan(h, b);
+    finish_kan(h, b, !(e->kakan_tile & 0x80));
   }
 }
 

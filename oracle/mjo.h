@@ -37,6 +37,9 @@ extern "C" {
 #define MJO_F_KUITAN   4u   /* open tanyao */
 #define MJO_F_MULTIRON 8u   /* reserved: multiple ron is always on */
 #define MJO_F_ENDGAME 16u   /* end of game by points: 30,000 to finish, one extra round, the leading dealer may stop */
+#define MJO_F_NAGASHI 64u     /* a river of unclaimed terminals and honors is paid as a mangan at an exhaustive draw */
+#define MJO_F_ANKAN_ROB 128u  /* thirteen orphans may win on the tile of a concealed kan */
+#define MJO_F_KANDORA_LATE 32u /* the indicator of an open or added kan is turned with the next discard or kan, not at once */
 
 typedef struct MjoRules {
   uint32_t flags;
@@ -87,7 +90,8 @@ typedef struct MjoEnv {
            last_discard, last_discarder, kakan_tile, kuikae[2],
            first_wind, same_wind_cnt, illegal_seat;
   uint8_t  end_type, winners, loser, tenpai_mask;
-  uint8_t  pad_[2];
+  uint8_t  dora_pending;  /* kan indicators not turned yet (MJO_F_KANDORA_LATE) */
+  uint8_t  pad_[1];
 } MjoEnv;
 
 /* hand-evaluation query / result (the 2^20-hand micro-batch) */

@@ -7,7 +7,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libmj.so")
 
-F_RED, F_ABORT, F_KUITAN, F_MULTIRON, F_ENDGAME = 1, 2, 4, 8, 16
+F_RED, F_ABORT, F_KUITAN, F_MULTIRON, F_ENDGAME, F_KANDORA_LATE, F_NAGASHI, F_ANKAN_ROB = 1, 2, 4, 8, 16, 32, 64, 128
 RULES_NORED = F_KUITAN | F_MULTIRON
 RULES_RED = F_RED | F_ABORT | F_KUITAN | F_MULTIRON
 MODE_SINGLE, MODE_EAST, MODE_HALF = 0, 1, 2
@@ -32,7 +32,7 @@ ENV_DTYPE = np.dtype([
     ("rinshan", "u1"), ("last_discard", "u1"), ("last_discarder", "u1"), ("kakan_tile", "u1"),
     ("kuikae", "u1", (2,)), ("first_wind", "u1"), ("same_wind_cnt", "u1"), ("illegal_seat", "u1"),
     ("end_type", "u1"), ("winners", "u1"), ("loser", "u1"), ("tenpai_mask", "u1"),
-    ("pad_", "u1", (2,)),
+    ("dora_pending", "u1"), ("pad_", "u1", (1,)),
 ])
 QUERY_DTYPE = np.dtype([
     ("meld", "<u2", (4,)), ("hand", "u1", (34,)), ("n_meld", "u1"), ("win_kind", "u1"), ("flags", "u1"),

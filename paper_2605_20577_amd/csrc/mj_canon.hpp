@@ -51,7 +51,7 @@ MJ_HD void export_env(const Env &e, MjEnvCanon &o)
   o.last_discarder = g.last_discarder; o.kakan_tile = g.kakan_tile; o.kuikae[0] = g.kuikae0; o.kuikae[1] = g.kuikae1;
   o.first_wind = g.first_wind; o.same_wind_cnt = g.same_wind_cnt; o.illegal_seat = g.illegal_seat;
   o.end_type = g.end_type; o.winners = g.winners; o.loser = g.loser; o.tenpai_mask = g.tenpai_mask;
-  o.pad_[0] = o.pad_[1] = 0;
+  o.dora_pending = g.dora_pending; o.pad_[0] = 0;
 }
 
 MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
@@ -98,7 +98,7 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
   g.last_discarder = o.last_discarder; g.kakan_tile = o.kakan_tile; g.kuikae0 = o.kuikae[0]; g.kuikae1 = o.kuikae[1];
   g.first_wind = o.first_wind; g.same_wind_cnt = o.same_wind_cnt; g.illegal_seat = o.illegal_seat;
   g.end_type = o.end_type; g.winners = o.winners; g.loser = o.loser; g.tenpai_mask = o.tenpai_mask;
-  g.wall_sel = 0; g.pad1 = 0;                      // the imported wall goes to buffer 0
+  g.wall_sel = 0; g.dora_pending = o.dora_pending;                      // the imported wall goes to buffer 0
   store_glob(e, g);
 }
 

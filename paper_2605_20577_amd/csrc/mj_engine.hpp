@@ -311,7 +311,7 @@ MJ_HD void deal_reset(Ctx &c)
     MELDW(c, s) = 0;
     DK(c, s) = 0;
   }
-  c.g.n_kan = 0; c.g.n_dora = 1;
+  c.g.n_kan = 0; c.g.n_dora = 1; c.g.dora_pending = 0;
   c.g.riichi_pending = 0; c.g.rinshan = 0;
   c.g.last_discard = 255; c.g.last_discarder = 255; c.g.kakan_tile = 255;
   c.g.kuikae0 = c.g.kuikae1 = 255;
@@ -468,7 +468,35 @@ MJ_HD void exhaustive_draw(Ctx &c)
   for (int s = 0; s < 4; s++) if ((WAITS(c, s) & K_ALL) != 0 || swf(c, s, SW_RIICHI, 2)) T |= 1 << s;
   c.g.tenpai_mask = (uint8_t)T;
   int n = popc32((uint32_t)T);
-  if (n >= 1 && n <= 3) {
+  // MJ_F_NAGASHI: seats that discarded terminals and honors only (the set of discarded kinds says so) and whose
+  // discards nobody took (every open meld names the seat it took from)
+  int N = 0;
+  if (c.R.flags & F_NAGASHI) {
+    for (int s = 0; s < 4; s++) if (!(DK(c, s) & ~K_YAOCHU)) N |= 1 << s;
+    if (N)
+      for (int o = 0; o < 4; o++) {
+        const uint64_t mw = MELDW(c, o);
+        const int nm = swf(c, o, SW_NMELD, 3);
+        for (int j = 0; j < nm; j++) {
+          const uint32_t m = meld_at(mw, j);
+          if (m_type(m) != MT_ANKAN) N &= ~(1 << ((o + (int)(m >> 9 & 3)) & 3));
+        }
+      }
+  }
+  if (N) {
+    const int dealer = dealer_of(c);
+    c.g.end_type = 10;
+    c.g.winners = (uint8_t)N;
+    for (int w = 0; w < 4; w++) if (N >> w & 1) {
+      int32_t got = 0;
+      for (int o = 0; o < 4; o++) if (o != w) {
+        const int32_t pay = (w == dealer || o == dealer) ? 4000 : 2000;
+        credit(c, o, -pay); got += pay;
+      }
+      credit(c, w, got);
+      c.e.gain[(int64_t)w * c.e.n] = got;
+    }
+  } else if (n >= 1 && n <= 3) {
     int32_t get = 3000 / n, give = 3000 / (4 - n);
     for (int s = 0; s < 4; s++) credit(c, s, (T >> s & 1) ? get : -give);
   }
@@ -481,12 +509,21 @@ MJ_HD void abortive_draw(Ctx &c, int type)
   finish_kyoku(c, true, true);
 }
 
-// the replacement draw that completes any kan (the mask follows in step_finish)
-MJ_HD void kan_draw(Ctx &c)
+// indicators of earlier open / added kans that wait to be turned are turned now (see MJ_F_KANDORA_LATE)
+MJ_HD void turn_pending_indicators(Ctx &c)
+{
+  c.g.n_dora = (uint8_t)(c.g.n_dora + c.g.dora_pending);
+  c.g.dora_pending = 0;
+}
+
+// the replacement draw that completes any kan (the mask follows in step_finish); `open` = a kan from a discard or
+// a tile added to a pon, whose indicator waits for the seat's discard when the rules say so
+MJ_HD void kan_draw(Ctx &c, bool open)
 {
   int s = c.g.cur;
   swf_set(c, s, SW_KANBY, 3, swf(c, s, SW_KANBY, 3) + 1);
-  c.g.n_dora++;
+  if ((c.R.flags & F_KANDORA_LATE) && open) c.g.dora_pending++;
+  else c.g.n_dora++;
   int id = WALL(c, 122 + c.g.n_kan);
   c.g.n_kan++;
   c.g.live_left--;
@@ -590,6 +627,7 @@ MJ_HD uint32_t chi_options(const Ctx &c, int su, int r, uint32_t sw, uint32_t hw
 // seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later
 MJ_HD void apply_discard(Ctx &c, int s, int k, int red)
 {
+  turn_pending_indicators(c);
   hand_add(c, s, k, -1);
   uint32_t sw = SW(c, s);
   if (red) sw &= ~(1u << (k / 9));
@@ -681,6 +719,7 @@ MJ_HD bool apply_own_kan(Ctx &c, int k)
   int s = c.g.cur;
   int tr = has_red(c, s, k) ? 1 : 0;
   c.g.drawn = 255;
+  turn_pending_indicators(c);
   if (count_of(c, s, k) == 4) {
     remove_tiles(c, s, k, tr ? 3 : 4, tr);
     push_meld(c, s, m_make(MT_ANKAN, k, 0, 0, tr, 0));
@@ -765,7 +804,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   int waits_seat = -1, waits_k = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
   // what the later stages have to do, as bits of one per-lane word (six separate booleans would each live in a
   // scalar register pair across the stages)
-  enum : uint32_t { DO_RESPOND = 1, DO_ROB = 2, DO_ADVANCE = 4, DO_KANFIN = 8, WIN_TSUMO = 16, WIN_ROB = 32 };
+  enum : uint32_t { DO_RESPOND = 1, DO_ROB = 2, DO_ADVANCE = 4, DO_KANFIN = 8, WIN_TSUMO = 16, WIN_ROB = 32, KAN_CONCEALED = 64 };
   uint32_t todo = 0;
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
@@ -776,7 +815,13 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
       apply_discard(c, s, k, act < A_DISCARD_RED ? 0 : 1);
       todo |= DO_RESPOND;
     } else if (act < A_RIICHI) {
-      todo |= apply_own_kan(c, act - A_KAN) ? DO_KANFIN : DO_ROB;
+      const int kk = act - A_KAN;
+      if (!apply_own_kan(c, kk)) todo |= DO_ROB;
+      else if ((c.R.flags & F_ANKAN_ROB) && (K_YAOCHU >> kk & 1)) {
+        // MJ_F_ANKAN_ROB: the thirteen orphans may win on this tile; the tile code carries bit 7 while that is open
+        c.g.kakan_tile = (uint8_t)(kk | 0x80);
+        todo |= DO_ROB | KAN_CONCEALED;
+      } else todo |= DO_KANFIN | KAN_CONCEALED;
       waits_seat = s;
     } else if (act == A_RIICHI) {
       c.g.riichi_pending = (SW(c, s) >> SW_FIRST & 1) ? 2 : 1;
@@ -806,7 +851,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
       }
     } else {
       if (ronners) { win_mask = ronners; win_loser = c.g.cur; win_tile = code_kind(c.g.kakan_tile); todo |= WIN_ROB; }
-      else { mark_passed_ron(c, ron_offered); todo |= DO_KANFIN; }
+      else { mark_passed_ron(c, ron_offered); todo |= (c.g.kakan_tile & 0x80) ? (DO_KANFIN | KAN_CONCEALED) : DO_KANFIN; }
     }
   }
   clear_masks(c);
@@ -847,6 +892,13 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
       opt[t] = (respond && other) ? pon_kan_options(c, su, r, sws[t], hws[t]) : 0u;
       if (other && (wts[t] >> k & 1)) hit |= 1u << t;
     }
+    // the tile of a concealed kan: only a hand without melds and without simples can wait for it as thirteen orphans
+    // (the declarer holds all four copies, so no ordinary wait of such a hand contains it)
+    if (rob && (todo & KAN_CONCEALED)) {
+#pragma unroll
+      for (int t = 0; t < 4; t++)
+        if (sw_get(sws[t], SW_NMELD, 3) || ((HW(c, t, 0) | HW(c, t, 1) | HW(c, t, 2)) & 0x00FFFFF8u)) hit &= ~(1u << t);
+    }
     // ... chi once, for the next seat, ...
     if (respond) {
       const int nx = (from + 1) & 3;
@@ -886,7 +938,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   // stage 5: draws
   MJ_KEEP_IN_VGPR(todo);
   if (todo & DO_ADVANCE) { draw_live(c, (c.g.last_discarder + 1) & 3); c.need_turn = true; }
-  if (todo & DO_KANFIN) { kan_draw(c); c.need_turn = true; }
+  if (todo & DO_KANFIN) { kan_draw(c, !(todo & KAN_CONCEALED)); c.need_turn = true; }
 }
 
 // uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)

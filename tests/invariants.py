@@ -54,7 +54,8 @@ def check_env(e, flags, start_score=25000, check_waits=True):
     # points conserved
     assert int(e["score"].sum()) + 1000 * int(e["kyotaku"]) == 4 * start_score
     assert int(e["live_left"]) == 70 - (int(e["draw_ptr"]) - 52) - int(e["n_kan"])
-    assert int(e["n_dora"]) == 1 + int(e["n_kan"]) and int(e["n_kan"]) == int(e["kan_by"].sum())
+    assert int(e["n_dora"]) + int(e["dora_pending"]) == 1 + int(e["n_kan"]) and int(e["n_kan"]) == int(e["kan_by"].sum())
+    assert int(e["dora_pending"]) <= (1 if flags & 32 else 0)       # only an open or added kan defers its indicator
     # masks
     am = int(e["actor_mask"])
     if e["terminated"]:

@@ -284,3 +284,137 @@ def test_end_of_game_by_points(engine):
     act(o, 0, {0: kind("5p")})
     e = act(o, 0, {3: A_RON})
     assert e["score"].tolist() == [11100, 35000, 24000, 29900] and e["terminated"] == 0 and e["kyoku"] == 7
+
+
+def test_late_kan_indicator(engine):
+    """MJ_F_KANDORA_LATE: the indicator of an open kan waits for the seat's discard or next kan, so a win on the
+    replacement tile does not count it; a concealed kan turns its indicator at once"""
+    hands = [J1, "111m 34p 456p 22s 678s", J2, J3]
+    wall = build_wall(hands, draws="9s", rinshan="5p", dora="1z 1s")
+    for late in (False, True):
+        o = engine(flags=mjo.RULES_NORED | (mjo.F_KANDORA_LATE if late else 0))
+        o.deal_from_wall(0, wall)
+        e = act(o, 0, {0: kind("1m")})
+        assert bits(e["mask"][1]) == [A_PON, A_MINKAN, A_PASS]
+        e = act(o, 0, {1: A_MINKAN})
+        assert e["n_kan"] == 1 and e["rinshan"] == 1 and e["drawn"] == kind("5p")
+        assert (e["n_dora"], e["dora_pending"]) == ((1, 1) if late else (2, 0))
+        e = act(o, 0, {1: A_TSUMO})
+        # after the kan: 34p+5p 456p 22s 678s; 20 + 2 (tsumo) + 16 (open kan of terminals) = 38 -> 40 fu;
+        # rinshan 1 han, and the pair of 2s is dora only if the second indicator (1s) counts
+        assert e["yaku"][1] == 1 << 12 and e["fu"][1] == 40
+        if late:
+            assert e["han"][1] == 1 and e["r_dora"][1] == 0 and e["delta"].tolist() == [-700, 1500, -400, -400]
+        else:
+            assert e["han"][1] == 3 and e["r_dora"][1] == 2 and e["delta"].tolist() == [-2600, 5200, -1300, -1300]
+    # the discard after an open kan turns the indicator before the discard is answered; so does another kan
+    hands = [J1, "111m 999p 34p 22s 678s", "258m 36p 1479s 4567z", J3]
+    wall = build_wall(hands, draws="9s", rinshan="9p 1s", dora="1z 2z 3z")
+    for second in ("discard", "kan"):
+        o = engine(flags=mjo.RULES_NORED | mjo.F_KANDORA_LATE)
+        o.deal_from_wall(0, wall)
+        act(o, 0, {0: kind("1m")})
+        e = act(o, 0, {1: A_MINKAN})
+        assert (e["n_dora"], e["dora_pending"]) == (1, 1) and A_KAN + kind("9p") in bits(e["mask"][1])
+        if second == "discard":
+            e = act(o, 0, {1: kind("8s")})
+            assert (e["n_dora"], e["dora_pending"], e["n_kan"]) == (2, 0, 1)
+        else:
+            e = act(o, 0, {1: A_KAN + kind("9p")})
+            assert (e["n_dora"], e["dora_pending"], e["n_kan"]) == (3, 0, 2) and e["drawn"] == kind("1s")
+        check_env(e, mjo.RULES_NORED | mjo.F_KANDORA_LATE)
+
+
+def _play_out(o, claims=()):
+    """everybody discards the tile just drawn (after a claim: the lowest legal tile) and passes on every offer, except
+    the (seat, action) pairs in `claims`, which are taken the first time they are offered; returns the final record"""
+    claims = list(claims)
+    for _ in range(400):
+        e = o.export(0, 1)[0]
+        if e["end_type"] != 0:
+            assert not claims, claims
+            return e
+        actors = [s for s in range(4) if int(e["actor_mask"]) >> s & 1]
+        moves = {}
+        for s in actors:
+            legal = bits(e["mask"][s])
+            if e["phase"] == 0:
+                d = int(e["drawn"])
+                moves[s] = d if d != 255 and d in legal else min(a for a in legal if a < 34)
+            else:
+                take = [c for c in claims if c[0] == s and c[1] in legal]
+                if take:
+                    claims.remove(take[0]); moves[s] = take[0][1]
+                else:
+                    moves[s] = A_PASS
+        act(o, 0, moves)
+    raise AssertionError("the kyoku did not end")
+
+
+NAGASHI_X = "5678p 2345678s 12z"            # a fourth hand from tiles the stacked draws leave over
+
+
+def _nagashi_wall(seat, hands, yao="9m 9m 9m 1p 1p 1p 9p 9p 9p 1s 1s 1s 6z 6z 6z 7z 7z 7z"):
+    """live draws: `seat` draws terminals and honors only, the others simples"""
+    yao = yao.split()
+    simples = [t for _ in range(3) for t in "2m 3m 4m 5m 6m 7m 8m 2p 3p 4p 5p 6p 7p 8p 2s 3s 4s 5s 6s 7s 8s".split()]
+    draws = [yao.pop(0) if i % 4 == seat else simples.pop(0) for i in range(70)]
+    return build_wall(hands, draws=" ".join(draws), dora="5z")
+
+
+def test_nagashi_mangan(engine):
+    """MJ_F_NAGASHI: a river of unclaimed terminals and honors is paid as a self-drawn mangan at the exhaustive draw"""
+    F = mjo.RULES_NORED | mjo.F_NAGASHI
+    # the dealer: 4000 from everybody; not tenpai, so the deal passes on and the counter goes up
+    o = engine(flags=F, mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, _nagashi_wall(0, [J1, J2, J3, NAGASHI_X]))
+    e = _play_out(o)
+    assert e["end_type"] == 10 and e["winners"] == 0b0001 and e["tenpai_mask"] == 0
+    assert e["delta"].tolist() == [12000, -4000, -4000, -4000] and e["gain"].tolist() == [12000, 0, 0, 0]
+    assert e["kyoku"] == 1 and e["honba"] == 1 and e["score"].tolist() == [37000, 21000, 21000, 21000]
+    # another seat: 4000 from the dealer, 2000 from the others; without the flag an ordinary exhaustive draw
+    for flags in (F, mjo.RULES_NORED):
+        o = engine(flags=flags, mode=mjo.MODE_HALF)
+        o.deal_from_wall(0, _nagashi_wall(1, [J1, J2, J3, NAGASHI_X]))
+        e = _play_out(o)
+        if flags == F:
+            assert e["end_type"] == 10 and e["winners"] == 0b0010 and e["delta"].tolist() == [-4000, 8000, -2000, -2000]
+        else:
+            assert e["end_type"] == 3 and e["winners"] == 0 and (e["delta"] == 0).all()
+    # one of the discards is claimed: no payment as mangan
+    o = engine(flags=F, mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, _nagashi_wall(0, [J1, J2, "99m 36m 147p 258s 123z", NAGASHI_X],
+                                      yao="9m 9m 1m 1p 1p 1p 9p 9p 9p 1s 1s 1s 6z 6z 6z 7z 7z 7z"))
+    e = _play_out(o, claims=[(2, A_PON)])
+    assert e["end_type"] == 3 and e["winners"] == 0
+
+
+def test_thirteen_orphans_rob_a_concealed_kan(engine):
+    """MJ_F_ANKAN_ROB: only a hand waiting as thirteen orphans may win on the tile of a concealed kan"""
+    hands = ["777z 234m 567p 234s 5s", "119m 19p 19s 123456z", "258m 369p 147s 4566z", J3]
+    wall = build_wall(hands, draws="7z", rinshan="8s", dora="1z 2z")
+    K = A_KAN + kind("7z")
+    for how in ("off", "ron", "pass"):
+        o = engine(flags=mjo.RULES_NORED | (0 if how == "off" else mjo.F_ANKAN_ROB))
+        o.deal_from_wall(0, wall)
+        e = act(o, 0, {0: K})
+        if how == "off":
+            assert e["phase"] == 0 and e["n_kan"] == 1 and e["n_dora"] == 2 and e["drawn"] == kind("8s")
+            continue
+        assert e["phase"] == 2 and e["actor_mask"] == 0b0010 and bits(e["mask"][1]) == [A_RON, A_PASS]
+        assert e["kakan_tile"] == kind("7z") | 0x80 and e["n_kan"] == 0 and int(e["meld"][0][0]) & 7 == 4
+        if how == "ron":
+            e = act(o, 0, {1: A_RON})
+            assert e["end_type"] == 2 and e["loser"] == 0 and e["winners"] == 0b0010 and e["yakuman_units"][1] == 1
+            assert e["delta"].tolist() == [-32000, 32000, 0, 0]
+        else:
+            e = act(o, 0, {1: A_PASS})
+            assert e["phase"] == 0 and e["cur"] == 0 and e["n_kan"] == 1 and e["n_dora"] == 2 and e["rinshan"] == 1
+            assert e["drawn"] == kind("8s") and e["kakan_tile"] == 255 and e["furiten_temp"][1] == 1
+    # an ordinary wait on the tile (78s waiting for 6s / 9s) is no offer
+    hands = ["999s 234m 567p 234p 5m", "147m 258p 36s 12345z", "234m 567m 22p 78s 666z", J3]
+    o = engine(flags=mjo.RULES_NORED | mjo.F_ANKAN_ROB)
+    o.deal_from_wall(0, build_wall(hands, draws="9s", rinshan="1s", dora="1z 2z"))
+    assert o.export()[0]["waits"][2] == (1 << kind("6s")) | (1 << kind("9s"))
+    e = act(o, 0, {0: A_KAN + kind("9s")})
+    assert e["phase"] == 0 and e["n_kan"] == 1 and e["furiten_temp"][2] == 0
