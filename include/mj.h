@@ -55,6 +55,11 @@ extern "C" {
 #define MJ_F_ANKAN_ROB 128u   /* a hand waiting as thirteen orphans may win on the tile of a concealed kan: the offer
                                 uses phase 2 like an added kan, kakan_tile carries bit 7 (0x80) then, and a pass lets
                                 the kan go on.  Off: a concealed kan can not be robbed */
+#define MJ_F_PAO 256u         /* liability: when all three dragon sets (all four wind sets) of a winner are exposed and
+                                the last one exposed was claimed from a discard, that discarder pays the whole of
+                                that yakuman and the counter bonus on a self-draw, and half of it (the discarder of
+                                the winning tile the other half, the counter bonus and any further yakuman) on a
+                                ron off somebody else.  Off: no liability */
 #define MJ_RULES_NORED (MJ_F_KUITAN | MJ_F_MULTIRON)
 #define MJ_RULES_RED   (MJ_F_RED | MJ_F_ABORT | MJ_F_KUITAN | MJ_F_MULTIRON)
 

@@ -830,6 +830,25 @@ static void finish_kyoku(MjoHandle *h, int64_t b, int renchan, int honba_up)
 /* win by the seats in `winners` (bit mask).  tsumo: one winner, everybody
  * pays.  ron: `loser` pays every winner in full, honba included; the sticks
  * go to the winner closest after the loser in turn order. */
+/* MJO_F_PAO: the seat liable for winner s's big three dragons or big four winds, or -1.  Reading (section 3.2
+ * names the rule set, not this detail): all three dragon sets (all four wind sets) are exposed, and the one exposed
+ * last was claimed from a discard; the discarder of that tile is liable.  Melds are stored in the order they were
+ * made, and a pon that later took its fourth tile keeps its place and its source. */
+static int pao_seat(const E *e, int s, uint64_t yaku)
+{
+  int lo, need;
+  if (yaku >> Y_DAISANGEN & 1) { lo = 31; need = 3; }
+  else if (yaku >> Y_DAISUUSHII & 1) { lo = 27; need = 4; }
+  else return -1;
+  int cnt = 0, last = -1;
+  for (int j = 0; j < e->n_meld[s]; j++) {
+    int k = m_kind(e->meld[s][j]);
+    if (m_type(e->meld[s][j]) != M_CHI && k >= lo && k < lo + need) { cnt++; last = j; }
+  }
+  if (cnt != need || m_type(e->meld[s][last]) == M_ANKAN) return -1;
+  return (s + (e->meld[s][last] >> 9 & 3)) & 3;
+}
+
 static void win(MjoHandle *h, int64_t b, int winners, int tsumo, int loser, int w, int chankan)
 {
   E *e = &h->env[b];
@@ -848,7 +867,22 @@ static void win(MjoHandle *h, int64_t b, int winners, int tsumo, int loser, int 
     e->r_dora[s] = r.n_dora; e->r_ura[s] = r.n_ura; e->r_aka[s] = r.n_aka;
     int32_t base = base_points(r.han, r.fu, r.yakuman_units);
     int32_t before = e->score[s];
-    if (tsumo) {
+    int liable = (h->rules.flags & MJO_F_PAO) ? pao_seat(e, s, r.yaku) : -1;
+    if (liable >= 0 && (tsumo || liable != loser)) {
+      /* The liable yakuman is one unit, worth `part` to this winner by ron or by self-draw alike.  Self-draw: the
+       * liable seat pays all of it and the counter bonus; any further yakuman of the hand is paid by all three as
+       * usual.  Ron off somebody else: the two share the liable part evenly, the discarder pays the rest and the
+       * counter bonus.  (Ron off the liable seat itself is an ordinary ron.) */
+      int32_t part = 8000 * (s == dealer ? 6 : 4), rest = 8000 * (r.yakuman_units - 1), bonus = 300 * (int32_t)e->honba;
+      if (tsumo) {
+        pay(e, liable, s, part + bonus);
+        if (rest > 0)
+          for (int o = 0; o < 4; o++) if (o != s) pay(e, o, s, (s == dealer || o == dealer) ? rest * 2 : rest);
+      } else {
+        pay(e, liable, s, part / 2);
+        pay(e, loser, s, part / 2 + rest * (s == dealer ? 6 : 4) + bonus);
+      }
+    } else if (tsumo) {
       for (int o = 0; o < 4; o++) if (o != s) {
         int32_t x = (s == dealer || o == dealer) ? up100(base * 2) : up100(base);
         pay(e, o, s, x + 100 * (int32_t)e->honba);

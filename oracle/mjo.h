@@ -39,6 +39,7 @@ extern "C" {
 #define MJO_F_ENDGAME 16u   /* end of game by points: 30,000 to finish, one extra round, the leading dealer may stop */
 #define MJO_F_NAGASHI 64u     /* a river of unclaimed terminals and honors is paid as a mangan at an exhaustive draw */
 #define MJO_F_ANKAN_ROB 128u  /* thirteen orphans may win on the tile of a concealed kan */
+#define MJO_F_PAO 256u        /* liability for feeding the last exposed set of the three dragons / four winds */
 #define MJO_F_KANDORA_LATE 32u /* the indicator of an open or added kan is turned with the next discard or kan, not at once */
 
 typedef struct MjoRules {

@@ -7,7 +7,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libmj.so")
 
-F_RED, F_ABORT, F_KUITAN, F_MULTIRON, F_ENDGAME, F_KANDORA_LATE, F_NAGASHI, F_ANKAN_ROB = 1, 2, 4, 8, 16, 32, 64, 128
+F_RED, F_ABORT, F_KUITAN, F_MULTIRON, F_ENDGAME, F_KANDORA_LATE, F_NAGASHI, F_ANKAN_ROB, F_PAO = 1, 2, 4, 8, 16, 32, 64, 128, 256
 RULES_NORED = F_KUITAN | F_MULTIRON
 RULES_RED = F_RED | F_ABORT | F_KUITAN | F_MULTIRON
 MODE_SINGLE, MODE_EAST, MODE_HALF = 0, 1, 2

@@ -33,7 +33,7 @@
 namespace mj {
 
 // ---------------------------------------------------------------- constants
-enum { F_RED = 1, F_ABORT = 2, F_KUITAN = 4, F_ENDGAME = 16, F_KANDORA_LATE = 32, F_NAGASHI = 64, F_ANKAN_ROB = 128 };
+enum { F_RED = 1, F_ABORT = 2, F_KUITAN = 4, F_ENDGAME = 16, F_KANDORA_LATE = 32, F_NAGASHI = 64, F_ANKAN_ROB = 128, F_PAO = 256 };
 enum { PH_TURN = 0, PH_RESPOND = 1, PH_RESPOND_KAKAN = 2, PH_TERMINAL = 3 };
 enum { A_DISCARD = 0, A_DISCARD_RED = 34, A_KAN = 37, A_RIICHI = 71, A_TSUMO = 72, A_KYUUSHU = 73, A_RON = 74,
        A_PON = 75, A_PON_RED = 76, A_MINKAN = 77, A_CHI_L = 78, A_CHI_L_RED = 81, A_PASS = 84, N_ACTIONS = 85 };

@@ -421,6 +421,26 @@ MJ_HD void finish_kyoku(Ctx &c, bool renchan, bool honba_up)
   c.need_deal = true;
 }
 
+// MJ_F_PAO: who fed the last exposed set of winner s's three dragons / four winds (-1: nobody is liable).  The meld
+// word keeps the melds in the order they were made, each with the seat it was claimed from.
+MJ_HD int pao_seat(Ctx &c, int s, uint64_t yaku)
+{
+  const int big3 = (int)(yaku >> Y_DAISANGEN & 1), big4 = (int)(yaku >> Y_DAISUUSHII & 1);
+  if (!(big3 | big4)) return -1;
+  const int lo = big3 ? 31 : 27, need = big3 ? 3 : 4;
+  const uint64_t mw = MELDW(c, s);
+  const int nm = swf(c, s, SW_NMELD, 3);
+  int cnt = 0;
+  uint32_t last = 0;
+  for (int j = 0; j < nm; j++) {
+    const uint32_t m = meld_at(mw, j);
+    const int k = m_kind(m);
+    if (k >= lo && k < lo + need) { cnt++; last = m; }         // honors are never part of a run
+  }
+  if (cnt != need || m_type(last) == MT_ANKAN) return -1;
+  return (s + (int)(last >> 9 & 3)) & 3;
+}
+
 MJ_HD void win(Ctx &c, int winners, bool tsumo, int loser, int w, bool chankan)
 {
   int dealer = dealer_of(c);
@@ -441,7 +461,29 @@ MJ_HD void win(Ctx &c, int winners, bool tsumo, int loser, int w, bool chankan)
     c.e.resw[(int64_t)s * c.e.n] = (uint64_t)(uint8_t)r.han | (uint64_t)(uint8_t)r.fu << 8 | (uint64_t)r.units << 16 |
                                    (uint64_t)r.n_dora << 24 | (uint64_t)r.n_ura << 32 | (uint64_t)r.n_aka << 40;
     int32_t base = base_points(r.han, r.fu, r.units), got = 0;
-    if (tsumo) {
+    int liable = -1;
+    if ((c.R.flags & F_PAO) && r.units) liable = pao_seat(c, s, r.yaku);
+    if (liable >= 0 && (tsumo || liable != loser)) {
+      // one unit of the hand is the liable seat's: all of it (and the counter bonus) on a self-draw, half of it on
+      // a ron off somebody else, who pays the other half, the bonus and whatever else the hand is worth
+      const int32_t mult = s == dealer ? 6 : 4, part = 8000 * mult, other = base - 8000;
+      if (tsumo) {
+        got = part + 300 * honba;
+        credit(c, liable, -got);
+        if (other > 0)
+          for (int o = 0; o < 4; o++) {
+            if (o == s) continue;
+            const int32_t x = (s == dealer || o == dealer) ? other * 2 : other;
+            credit(c, o, -x);
+            got += x;
+          }
+      } else {
+        const int32_t from_loser = part / 2 + other * mult + 300 * honba;
+        credit(c, liable, -(part / 2));
+        credit(c, loser, -from_loser);
+        got = part / 2 + from_loser;
+      }
+    } else if (tsumo) {
       for (int o = 0; o < 4; o++) {
         if (o == s) continue;
         int32_t x = ((s == dealer || o == dealer) ? up100(base * 2) : up100(base)) + 100 * honba;

@@ -114,7 +114,7 @@ def test_observation_more_groups_than_resident_blocks():
 
 
 @pytest.mark.parametrize("flags,lpw,seed", [(mjo.RULES_NORED, 32, 3), (mjo.RULES_RED, 64, 4),
-                                            (mjo.RULES_RED | mjo.F_ENDGAME | mjo.F_KANDORA_LATE | mjo.F_NAGASHI | mjo.F_ANKAN_ROB, 32, 5)])
+                                            (mjo.RULES_RED | mjo.F_ENDGAME | mjo.F_KANDORA_LATE | mjo.F_NAGASHI | mjo.F_ANKAN_ROB | mjo.F_PAO, 32, 5)])
 def test_fused_rollout_large(flags, lpw, seed, monkeypatch):
     """16,384 games x 1,600 fused steps (more than a full hanchan each, so the rare paths are walked many times: wins of every
     kind, kans, robbed kans, abortive draws, busts, game ends), every field and the observation against the

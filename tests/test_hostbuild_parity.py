@@ -27,7 +27,7 @@ def test_hand_microbatch():
 @pytest.mark.parametrize("flags,mode,steps", [(mjo.RULES_NORED, mjo.MODE_SINGLE, 160), (mjo.RULES_RED, mjo.MODE_HALF, 1200),
                                               (mjo.RULES_NORED | mjo.F_ABORT, mjo.MODE_EAST, 500),
                                               (mjo.RULES_RED | mjo.F_ENDGAME, mjo.MODE_EAST, 900),
-                                              (mjo.RULES_RED | mjo.F_KANDORA_LATE | mjo.F_NAGASHI | mjo.F_ANKAN_ROB, mjo.MODE_HALF, 900)])
+                                              (mjo.RULES_RED | mjo.F_KANDORA_LATE | mjo.F_NAGASHI | mjo.F_ANKAN_ROB | mjo.F_PAO, mjo.MODE_HALF, 900)])
 def test_rollout_trace(flags, mode, steps):
     B = 48
     o, s = mjo.Oracle(B, 7, flags, mode), HostSim(B, 7, flags, mode)

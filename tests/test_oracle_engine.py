@@ -9,7 +9,7 @@ from tests.invariants import check_env
 @pytest.mark.parametrize("flags,mode", [(mjo.RULES_NORED, mjo.MODE_SINGLE), (mjo.RULES_RED, mjo.MODE_HALF),
                                         (mjo.RULES_NORED | mjo.F_ABORT, mjo.MODE_EAST),
                                         (mjo.RULES_RED | mjo.F_ENDGAME, mjo.MODE_EAST),
-                                        (mjo.RULES_RED | mjo.F_KANDORA_LATE | mjo.F_NAGASHI | mjo.F_ANKAN_ROB, mjo.MODE_HALF)])
+                                        (mjo.RULES_RED | mjo.F_KANDORA_LATE | mjo.F_NAGASHI | mjo.F_ANKAN_ROB | mjo.F_PAO, mjo.MODE_HALF)])
 def test_invariants_every_step(flags, mode):
     B = 24
     o = mjo.Oracle(B, seed=17, flags=flags, mode=mode)

@@ -325,10 +325,12 @@ def test_late_kan_indicator(engine):
         check_env(e, mjo.RULES_NORED | mjo.F_KANDORA_LATE)
 
 
-def _play_out(o, claims=()):
-    """everybody discards the tile just drawn (after a claim: the lowest legal tile) and passes on every offer, except
-    the (seat, action) pairs in `claims`, which are taken the first time they are offered; returns the final record"""
+def _play_out(o, claims=(), discards=None, tsumo=()):
+    """everybody discards the tile just drawn (after a claim: the lowest legal tile) and passes on every offer, except:
+    the (seat, action) pairs in `claims` are taken the first time they are offered, a seat in `discards` discards the
+    listed kinds first, one per turn, and a seat in `tsumo` wins by self-draw when it can; returns the final record"""
     claims = list(claims)
+    discards = {s: list(v) for s, v in (discards or {}).items()}
     for _ in range(400):
         e = o.export(0, 1)[0]
         if e["end_type"] != 0:
@@ -340,7 +342,12 @@ def _play_out(o, claims=()):
             legal = bits(e["mask"][s])
             if e["phase"] == 0:
                 d = int(e["drawn"])
-                moves[s] = d if d != 255 and d in legal else min(a for a in legal if a < 34)
+                if s in tsumo and A_TSUMO in legal:
+                    moves[s] = A_TSUMO
+                elif discards.get(s):
+                    moves[s] = discards[s].pop(0)
+                else:
+                    moves[s] = d if d != 255 and d in legal else min(a for a in legal if a < 34)
             else:
                 take = [c for c in claims if c[0] == s and c[1] in legal]
                 if take:
@@ -418,3 +425,38 @@ def test_thirteen_orphans_rob_a_concealed_kan(engine):
     assert o.export()[0]["waits"][2] == (1 << kind("6s")) | (1 << kind("9s"))
     e = act(o, 0, {0: A_KAN + kind("9s")})
     assert e["phase"] == 0 and e["n_kan"] == 1 and e["furiten_temp"][2] == 0
+
+
+def test_liability_for_the_three_dragons(engine):
+    """MJ_F_PAO: seat 1 claims the white and the green dragon, then the red one from seat 0, who is liable from then on"""
+    hands = ["147m 258p 369s 12z 57z", "55z 66z 77z 23m 11p 5s 9s 8p", J2, "369m 147p 258s 1234z"]
+    plan = dict(claims=[(1, A_PON), (1, A_PON), (1, A_PON)],
+                discards={0: [kind("5z"), kind("7z")], 2: [kind("6z")], 1: [kind("5s"), kind("9s"), kind("8p")]})
+    F = mjo.RULES_NORED | mjo.F_PAO
+    # draws in the order they happen (claims skip seats): 0, 2, 2, 3, 0, 2, 3, 0, 1
+    def run(flags, draws, extra_claims=(), tsumo=()):
+        o = engine(flags=flags, mode=mjo.MODE_HALF)
+        o.deal_from_wall(0, build_wall(hands, draws=draws, dora="9m"))
+        p = dict(plan)
+        p["claims"] = plan["claims"] + list(extra_claims)
+        return _play_out(o, tsumo=tsumo, **p)
+    # self-draw: the liable seat pays all of it; without the flag everybody pays a share
+    e = run(F, "1z 2z 3z 4z 3z 3z 4z 2z 4m", tsumo=(1,))
+    assert e["end_type"] == 1 and e["yakuman_units"][1] == 1 and e["yaku"][1] == 1 << 34
+    assert e["delta"].tolist() == [-32000, 32000, 0, 0]
+    e = run(mjo.RULES_NORED, "1z 2z 3z 4z 3z 3z 4z 2z 4m", tsumo=(1,))
+    assert e["end_type"] == 1 and e["delta"].tolist() == [-16000, 32000, -8000, -8000]
+    # ron off seat 2: the liable seat and the discarder pay half each
+    e = run(F, "1z 2z 3z 4z 3z 1m 4z 2z 4m", extra_claims=[(1, A_RON)])
+    assert e["end_type"] == 2 and e["loser"] == 2 and e["delta"].tolist() == [-16000, 32000, -16000, 0]
+    # ron off the liable seat itself: an ordinary ron
+    e = run(F, "1z 2z 3z 4z 3z 3z 4z 1m 4m", extra_claims=[(1, A_RON)])
+    assert e["end_type"] == 2 and e["loser"] == 0 and e["delta"].tolist() == [-32000, 32000, 0, 0]
+    # a second yakuman in the same hand (all honors) is paid by all three as usual
+    hands = ["147m 258p 369s 12z 57z", "55z 66z 77z 11z 22z 5s 9s 8p", J2, "3689m 147p 2458s 34z"]
+    for flags, want in ((F, [-48000, 64000, -8000, -8000]), (mjo.RULES_NORED, [-32000, 64000, -16000, -16000])):
+        o = engine(flags=flags, mode=mjo.MODE_HALF)
+        o.deal_from_wall(0, build_wall(hands, draws="3z 4z 3z 4z 3z 9m 9m 9m 1z", dora="2s"))
+        e = _play_out(o, tsumo=(1,), **plan)
+        assert e["end_type"] == 1 and e["yakuman_units"][1] == 2 and e["yaku"][1] == (1 << 34) | (1 << 37)
+        assert e["delta"].tolist() == want
