@@ -395,12 +395,12 @@ __device__ __forceinline__ uint32_t sample_actors(Ctx &c, uint64_t step, int &ro
 // n_steps of { sample, step, optional reset } without leaving the kernel: environments never interact
 template <int LPW>
 __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t B, Rules R, DevTables T, uint64_t step0,
-                                                    int n_steps, int auto_reset)
+                                                    int n_steps, int auto_reset, int64_t env_lo, int64_t env_hi)
 {
   extern __shared__ __align__(16) uint8_t lds[];
   BlockMem m = stage_block<LPW>(T, lds);
-  const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
-  const bool active = m.lane_on && b < B;
+  const int64_t b = env_lo + (int64_t)blockIdx.x * m.epb + m.idx;      // the launch covers environments [env_lo, env_hi)
+  const bool active = m.lane_on && b < env_hi;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
@@ -792,10 +792,11 @@ inline int pick_lpw(int64_t B)
                                         // per SIMD only (LDS), measured slower at every batch size
   return 16;
 }
-#define MJ_LAUNCH_STEP(kern, h, st, ...)                                                                         \
+#define MJ_LAUNCH_STEP(kern, h, st, ...) MJ_LAUNCH_STEP_N(kern, h, st, (h)->B, __VA_ARGS__)
+#define MJ_LAUNCH_STEP_N(kern, h, st, n_envs, ...)                                                               \
   do {                                                                                                           \
     size_t lds_ = step_lds_bytes((int)(h)->probe_bytes, (h)->lpw);                                               \
-    unsigned nb_ = step_blocks((h)->B, (h)->lpw);                                                                \
+    unsigned nb_ = step_blocks((n_envs), (h)->lpw);                                                              \
     if ((h)->lpw == 64) kern<64><<<nb_, kBlock, lds_, st>>>(__VA_ARGS__);                                        \
     else if ((h)->lpw == 32) kern<32><<<nb_, kBlock, lds_, st>>>(__VA_ARGS__);                                   \
     else kern<16><<<nb_, kBlock, lds_, st>>>(__VA_ARGS__);                                                       \
@@ -964,14 +965,26 @@ int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, 
     // MJ_CHUNK overrides the length for experiments.
     int chunk = MJ_ROLLOUT_CHUNK;
     if (const char *cv = std::getenv("MJ_CHUNK")) { int v = std::atoi(cv); if (v > 0) chunk = v; }
+    // A batch of up to six times what the machine holds at once (4 blocks per compute unit) can go out in slices of
+    // that size (the last one smaller), one launch each.  Measured in units of one full slice's time: a single launch
+    // over x slices' worth of games takes about x + 0.5 (x = 2 / 3 / 4: 2.6 / 3.5 / 4.3; B = 131,072: 5.3 G env
+    // steps/s) and only from x = 6 on about x; sliced launches take ceil(x), however small the last slice is
+    // (B = 131,072: 7.0 G).  So slices are used when the last one is more than half full.
+    const int64_t resident = (int64_t)h->n_cu * 4 * envs_per_block(h->lpw);
+    const int64_t tail = h->B % resident;
+    const bool slices = h->lpw == 32 && h->B <= 6 * resident && (tail == 0 || 2 * tail > resident);
+    const int64_t per_slice = slices ? resident : h->B;
     for (int t = 0; t < n_steps && rc == MJ_OK; t += chunk) {
       int n = n_steps - t < chunk ? n_steps - t : chunk;
-      MJ_LAUNCH_STEP(k_rollout, h, st, h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset);
-      rc = check(hipGetLastError());
+      for (int64_t lo = 0; lo < h->B && rc == MJ_OK; lo += per_slice) {
+        const int64_t hi = lo + per_slice < h->B ? lo + per_slice : h->B;
+        MJ_LAUNCH_STEP_N(k_rollout, h, st, hi - lo, h->d_state, h->B, h->R, h->T, h->step + t, n, auto_reset, lo, hi);
+        rc = check(hipGetLastError());
+      }
     }
   } else {
     for (int t = 0; t < n_steps && rc == MJ_OK; t++) {
-      MJ_LAUNCH_STEP(k_rollout, h, st, h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset);
+      MJ_LAUNCH_STEP(k_rollout, h, st, h->d_state, h->B, h->R, h->T, h->step + t, 1, auto_reset, (int64_t)0, h->B);
       rc = check(hipGetLastError());
       if (rc == MJ_OK) rc = mj_observe(h, d_obs, stream);
     }

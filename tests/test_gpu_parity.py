@@ -99,6 +99,20 @@ def test_fused_rollout_many_games():
     assert np.array_equal(o.observe(), g.observe())
 
 
+def test_fused_rollout_batch_in_slices():
+    """110,001 games are more than the machine holds at once (65,536) and the rest fills more than half of it, so the
+    fused path sends them as two launches per chunk, each over its own range of games; every field against the
+    oracle after 300 steps, 150 of them in a second call"""
+    from tests.engines import oracle_rollout_sharded
+    B, steps = 110001, 300
+    g = GpuEngine(B, seed=8, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    g.step_random(150); g.step_random(150)
+    eo, oo = oracle_rollout_sharded(B, 8, mjo.RULES_RED, mjo.MODE_HALF, steps)
+    d = diff_records(eo, g.export())
+    assert not d, d[:4]
+    assert np.array_equal(oo, g.observe())
+
+
 def test_observation_more_groups_than_resident_blocks():
     """40,003 games are 1,251 groups of 32 for the observation writer, more than the blocks it keeps resident, so every
     block takes several groups from the work counter; a second launch checks that the counters were set back"""
