@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TOKEN_BYTES_PER_ENV = 4 * 224      # token observation written per game (4 viewers)
+TOKEN_BYTES_PER_ENV = 4 * 496      # token observation written per game (4 viewers)
 # Algorithmic HBM bytes of one env step of the fused path ("Algorithmic bytes"): the state fields a
 # step has to read and write when nothing is cached between steps, outputs included.
 ALGO_BYTES_PER_ENV_STEP = 512
@@ -166,7 +166,7 @@ def main():
                 env.observe(obs)
             torch.cuda.synchronize()
             extras["observe_kernel_GBps"] = OBS_BYTES_PER_ENV * Bo * 20 / (time.perf_counter() - t0) / 1e9
-            # the token observation of the same batch: 4 x 224 B per game, shanten number included
+            # the token observation of the same batch: 4 x 496 B per game, shanten number and action history included
             tok = env.observe_tokens()
             torch.cuda.synchronize()
             t0 = time.perf_counter()

@@ -87,7 +87,7 @@ enum {
 enum { MJ_PHASE_TURN = 0, MJ_PHASE_RESPOND = 1, MJ_PHASE_RESPOND_KAKAN = 2, MJ_PHASE_TERMINAL = 3 };
 
 /* Canonical per-environment record written by mj_export / read by mj_import
- * (array of structures, 744 bytes, no padding between fields).
+ * (array of structures, 1000 bytes, no padding between fields).
  * Tile kinds 0..33 (1m..9m, 1p..9p, 1s..9s, E S W N, white green red); tile
  * ids 0..135, kind = id >> 2.  "tile code" = kind | red << 6, 255 = none.
  * meld word: type(3: 1 chi 2 pon 3 open kan 4 concealed kan 5 added kan) |
@@ -104,6 +104,8 @@ typedef struct MjEnvCanon {
   int32_t  gain[4];              /* last result: amount credited to each winner */
   uint32_t episode, kyoku_serial;
   uint16_t meld[4][4];
+  uint16_t hist[128];            /* the kyoku's public actions in the order they took effect: action | seat << 8
+                                    (passes and draws are not recorded); entries from n_hist on are 0 */
   uint8_t  wall[136];
   uint8_t  hand[4][34];
   uint8_t  river[4][32];
@@ -118,7 +120,7 @@ typedef struct MjEnvCanon {
            first_wind, same_wind_cnt, illegal_seat;
   uint8_t  end_type, winners, loser, tenpai_mask;
   uint8_t  dora_pending;         /* kan indicators not turned yet (MJ_F_KANDORA_LATE) */
-  uint8_t  pad_[1];
+  uint8_t  n_hist;               /* entries of hist in use (at most 128; later actions of a kyoku are dropped) */
 } MjEnvCanon;
 
 /* one hand to evaluate (64 bytes) and its value (24 bytes) */
@@ -142,10 +144,10 @@ typedef struct MjHandResult {
   uint8_t  pad_[4];
 } MjHandResult;
 
-/* Token observation of one (environment, viewer) pair, 224 bytes (section
+/* Token observation of one (environment, viewer) pair, 496 bytes (section
  * 3.2, "Observation Space": a structured observation for sequence models --
- * hand indices, the public history of discards and calls, scalar properties
- * such as the shanten number and the scores -- ego-centric; the field layout is
+ * hand indices, the action history, scalar properties such as the shanten
+ * number and the scores -- ego-centric; the field layout is
  * this library's).  Seats are relative to the viewer: 0 self, 1 next, 2 across,
  * 3 previous.  A tile token is its kind 0..33, or 34 / 35 / 36 for the red
  * 5m / 5p / 5s; 255 pads.  A river entry is token | called_away << 7.  Meld
@@ -163,6 +165,10 @@ typedef struct MjTokenObs {
   int32_t  score[4];
   uint16_t meld[4][4];
   uint8_t  river[4][32];
+  uint8_t  n_hist;          /* public actions of the kyoku so far */
+  uint8_t  zero_[15];
+  uint16_t hist[128];       /* in the order they took effect: action id | relative seat << 8 (discards, kans, riichi,
+                               wins, claims; no passes, no draws); unused entries 0xFFFF */
 } MjTokenObs;
 
 typedef struct MjHandle MjHandle;   /* host object: B, seed, rules, step counter, pointers into the caller's buffers */

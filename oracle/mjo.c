@@ -746,6 +746,7 @@ static void deal(MjoHandle *h, int64_t b, int reshuffle)
   memset(e->kan_by, 0, 4);
   memset(e->discarded_kinds, 0, sizeof e->discarded_kinds);
   e->draw_ptr = 52; e->n_kan = 0; e->live_left = 70; e->n_dora = 1; e->dora_pending = 0;
+  e->n_hist = 0; memset(e->hist, 0, sizeof e->hist);
   e->drawn = 255; e->riichi_pending = 0; e->rinshan = 0;
   e->last_discard = 255; e->last_discarder = 255; e->kakan_tile = 255;
   e->kuikae[0] = e->kuikae[1] = 255;
@@ -1236,6 +1237,16 @@ static void mark_passed_ron(E *e)
   }
 }
 
+/* The action history of the observation (section 3.2, "Observation Space"): every public action of the kyoku in
+ * the order it took effect -- discards, kans, riichi, wins and the nine-terminals draw by the seat to move; the
+ * wins on a discard or kan tile in turn order from the seat that gave it; otherwise the one claim (pon, kan, chi)
+ * that took the discard.  Passes and draws are not public and are not recorded.  Reading: the paper names the
+ * history but not its content; this is what the other players can see. */
+static void hist_push(E *e, int s, int a)
+{
+  if (e->n_hist < 128) e->hist[e->n_hist++] = (uint16_t)(a | s << 8);
+}
+
 static void step_env(MjoHandle *h, int64_t b, const int8_t a[4])
 {
   E *e = &h->env[b];
@@ -1256,6 +1267,7 @@ static void step_env(MjoHandle *h, int64_t b, const int8_t a[4])
   }
   if (e->phase == MJO_TURN) {
     int s = e->cur, act = a[s];
+    hist_push(e, s, act);
     if (act < MJO_A_DISCARD_RED) discard(h, b, s, act, 0);
     else if (act < MJO_A_KAN) discard(h, b, s, 4 + 9 * (act - MJO_A_DISCARD_RED), 1);
     else if (act < MJO_A_RIICHI) own_kan(h, b, act - MJO_A_KAN);
@@ -1265,6 +1277,7 @@ static void step_env(MjoHandle *h, int64_t b, const int8_t a[4])
   } else if (e->phase == MJO_RESPOND) {
     int d = e->last_discarder, ronners = 0, n_ron = 0;
     for (int s = 0; s < 4; s++) if ((e->actor_mask >> s & 1) && a[s] == MJO_A_RON) { ronners |= 1 << s; n_ron++; }
+    for (int j = 1; j < 4; j++) if (ronners >> ((d + j) & 3) & 1) hist_push(e, (d + j) & 3, MJO_A_RON);
     if (n_ron == 3 && (h->rules.flags & MJO_F_ABORT)) { abortive_draw(h, b, 8); return; }
     if (n_ron) { win(h, b, ronners, 0, d, t_kind(e->last_discard), 0); return; }
     mark_passed_ron(e);
@@ -1275,11 +1288,13 @@ static void step_env(MjoHandle *h, int64_t b, const int8_t a[4])
       if ((e->actor_mask >> nx & 1) && a[nx] >= MJO_A_CHI_L && a[nx] <= MJO_A_CHI_H_RED) { caller = nx; call = a[nx]; }
     }
     if (settle_discard(h, b)) return;
+    if (caller >= 0) hist_push(e, caller, call);
     if (caller >= 0) do_call(h, b, caller, call);
     else advance(h, b);
   } else if (e->phase == MJO_RESPOND_KAKAN) {
     int ronners = 0;
     for (int s = 0; s < 4; s++) if ((e->actor_mask >> s & 1) && a[s] == MJO_A_RON) ronners |= 1 << s;
+    for (int j = 1; j < 4; j++) if (ronners >> ((e->cur + j) & 3) & 1) hist_push(e, (e->cur + j) & 3, MJO_A_RON);
     if (ronners) { win(h, b, ronners, 0, e->cur, t_kind(e->kakan_tile), 1); return; }
     mark_passed_ron(e);
     finish_kan(h, b, !(e->kakan_tile & 0x80));
@@ -1443,6 +1458,10 @@ int mjo_observe_tokens(const MjoHandle *h, MjoTokenObs *out)
           o->river[rel][i] = (uint8_t)(tile_token(t & 63, t >> 6 & 1) | (t & 0x80));
         }
       }
+      o->n_hist = e->n_hist;
+      memset(o->zero_, 0, sizeof o->zero_);
+      for (int i = 0; i < e->n_hist; i++)
+        o->hist[i] = (uint16_t)((e->hist[i] & 0xFF) | (((e->hist[i] >> 8) - me) & 3) << 8);
     }
   }
   return 0;

@@ -67,7 +67,7 @@ enum {
 };
 
 /* One environment, all logical state.  Field order is by descending
- * alignment so the struct has no internal padding (sizeof == 744). */
+ * alignment so the struct has no internal padding (sizeof == 1000). */
 typedef struct MjoEnv {
   uint64_t discarded_kinds[4];
   uint64_t waits[4];
@@ -78,6 +78,7 @@ typedef struct MjoEnv {
   int32_t  gain[4];
   uint32_t episode, kyoku_serial;
   uint16_t meld[4][4];
+  uint16_t hist[128];     /* the kyoku's public actions in order: action | seat << 8; entries from n_hist on are 0 */
   uint8_t  wall[136];
   uint8_t  hand[4][34];
   uint8_t  river[4][32];
@@ -92,7 +93,7 @@ typedef struct MjoEnv {
            first_wind, same_wind_cnt, illegal_seat;
   uint8_t  end_type, winners, loser, tenpai_mask;
   uint8_t  dora_pending;  /* kan indicators not turned yet (MJO_F_KANDORA_LATE) */
-  uint8_t  pad_[1];
+  uint8_t  n_hist;        /* entries of hist in use */
 } MjoEnv;
 
 /* hand-evaluation query / result (the 2^20-hand micro-batch) */
@@ -120,10 +121,10 @@ typedef struct MjoHandResult {
 typedef struct MjoHandle MjoHandle;
 
 /* pins / building blocks exposed for the tests */
-/* Token observation of one (environment, viewer) pair, 224 bytes (paper
+/* Token observation of one (environment, viewer) pair, 496 bytes (paper
  * section 3.2: a structured observation for sequence models -- hand indices,
- * the public history of discards and calls, scalar properties such as the
- * shanten number and the scores -- ego-centric).  Seats are relative to the
+ * the action history, scalar properties such as the shanten number and the
+ * scores -- ego-centric).  Seats are relative to the
  * viewer: 0 self, 1 next, 2 across, 3 previous.  A tile token is its kind
  * 0..33, or 34 / 35 / 36 for the red 5m / 5p / 5s; 255 pads.  A river entry is
  * token | called_away << 7.  Meld words are those of MjoEnv. */
@@ -139,6 +140,9 @@ typedef struct MjoTokenObs {
   int32_t  score[4];
   uint16_t meld[4][4];
   uint8_t  river[4][32];
+  uint8_t  n_hist;        /* public actions of the kyoku so far */
+  uint8_t  zero_[15];
+  uint16_t hist[128];     /* in order: action id | relative seat << 8; unused entries 0xFFFF */
 } MjoTokenObs;
 
 void mjo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);

@@ -19,7 +19,7 @@ ENV_DTYPE = np.dtype([
     ("discarded_kinds", "<u8", (4,)), ("waits", "<u8", (4,)), ("mask", "<u8", (4, 2)), ("yaku", "<u8", (4,)),
     ("score", "<i4", (4,)), ("delta", "<i4", (4,)), ("gain", "<i4", (4,)),
     ("episode", "<u4"), ("kyoku_serial", "<u4"),
-    ("meld", "<u2", (4, 4)),
+    ("meld", "<u2", (4, 4)), ("hist", "<u2", (128,)),
     ("wall", "u1", (136,)), ("hand", "u1", (4, 34)), ("river", "u1", (4, 32)),
     ("hand_red", "u1", (4,)), ("n_meld", "u1", (4,)), ("n_river", "u1", (4,)), ("riichi_idx", "u1", (4,)),
     ("riichi", "u1", (4,)), ("ippatsu", "u1", (4,)), ("first_turn", "u1", (4,)), ("furiten_temp", "u1", (4,)),
@@ -32,7 +32,7 @@ ENV_DTYPE = np.dtype([
     ("rinshan", "u1"), ("last_discard", "u1"), ("last_discarder", "u1"), ("kakan_tile", "u1"),
     ("kuikae", "u1", (2,)), ("first_wind", "u1"), ("same_wind_cnt", "u1"), ("illegal_seat", "u1"),
     ("end_type", "u1"), ("winners", "u1"), ("loser", "u1"), ("tenpai_mask", "u1"),
-    ("dora_pending", "u1"), ("pad_", "u1", (1,)),
+    ("dora_pending", "u1"), ("n_hist", "u1"),
 ])
 QUERY_DTYPE = np.dtype([
     ("meld", "<u2", (4,)), ("hand", "u1", (34,)), ("n_meld", "u1"), ("win_kind", "u1"), ("flags", "u1"),
@@ -50,9 +50,10 @@ TOKEN_DTYPE = np.dtype([        # MjTokenObs
     ("dealer", "u1"), ("live_left", "u1"), ("n_dora", "u1"), ("dora", "u1", (5,)), ("n_meld", "u1", (4,)),
     ("n_river", "u1", (4,)), ("riichi", "u1", (4,)), ("riichi_idx", "u1", (4,)), ("score", "<i4", (4,)),
     ("meld", "<u2", (4, 4)), ("river", "u1", (4, 32)),
+    ("n_hist", "u1"), ("zero_", "u1", (15,)), ("hist", "<u2", (128,)),
 ])
-assert ENV_DTYPE.itemsize == 744 and QUERY_DTYPE.itemsize == 64 and RESULT_DTYPE.itemsize == 24
-assert TOKEN_DTYPE.itemsize == 224
+assert ENV_DTYPE.itemsize == 1000 and QUERY_DTYPE.itemsize == 64 and RESULT_DTYPE.itemsize == 24
+assert TOKEN_DTYPE.itemsize == 496
 
 
 class MjRules(C.Structure):
@@ -250,7 +251,7 @@ class MahjongEnv:
         return o
 
     def observe_tokens(self, out=None):
-        """token observation: uint8 tensor [B, 4, 224], one MjTokenObs per (game, viewer); view it on the host as
+        """token observation: uint8 tensor [B, 4, 496], one MjTokenObs per (game, viewer); view it on the host as
         TOKEN_DTYPE, or slice the byte fields on the device"""
         torch = self.torch
         o = out if out is not None else torch.empty((self.B, 4, TOKEN_DTYPE.itemsize), dtype=torch.uint8, device=self.device)

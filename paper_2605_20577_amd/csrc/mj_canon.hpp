@@ -47,11 +47,13 @@ MJ_HD void export_env(const Env &e, MjEnvCanon &o)
   o.kyoku = g.kyoku; o.honba = g.honba; o.kyotaku = g.kyotaku; o.terminated = g.terminated;
   o.draw_ptr = g.draw_ptr; o.n_kan = g.n_kan; o.live_left = g.live_left; o.n_dora = g.n_dora;
   o.drawn = g.drawn; o.phase = g.phase; o.cur = g.cur; o.actor_mask = g.actor_mask;
-  o.riichi_pending = g.riichi_pending; o.rinshan = g.rinshan; o.last_discard = g.last_discard;
+  o.riichi_pending = g.riichi_pending; o.rinshan = g.kanflags & 1; o.last_discard = g.last_discard;
   o.last_discarder = g.last_discarder; o.kakan_tile = g.kakan_tile; o.kuikae[0] = g.kuikae0; o.kuikae[1] = g.kuikae1;
   o.first_wind = g.first_wind; o.same_wind_cnt = g.same_wind_cnt; o.illegal_seat = g.illegal_seat;
   o.end_type = g.end_type; o.winners = g.winners; o.loser = g.loser; o.tenpai_mask = g.tenpai_mask;
-  o.dora_pending = g.dora_pending; o.pad_[0] = 0;
+  o.dora_pending = g.kanflags >> 1 & 1; o.n_hist = g.hist_len;
+  for (int i = 0; i < 128; i++)
+    o.hist[i] = i < g.hist_len ? e.hist[(int64_t)i * n] : (uint16_t)0;
 }
 
 MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
@@ -94,11 +96,13 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
   g.kyoku = o.kyoku; g.honba = o.honba; g.kyotaku = o.kyotaku; g.terminated = o.terminated;
   g.draw_ptr = o.draw_ptr; g.n_kan = o.n_kan; g.live_left = o.live_left; g.n_dora = o.n_dora;
   g.drawn = o.drawn; g.phase = o.phase; g.cur = o.cur; g.actor_mask = o.actor_mask;
-  g.riichi_pending = o.riichi_pending; g.rinshan = o.rinshan; g.last_discard = o.last_discard;
+  g.riichi_pending = o.riichi_pending; g.kanflags = (uint8_t)((o.rinshan & 1) | (o.dora_pending & 1) << 1); g.last_discard = o.last_discard;
   g.last_discarder = o.last_discarder; g.kakan_tile = o.kakan_tile; g.kuikae0 = o.kuikae[0]; g.kuikae1 = o.kuikae[1];
   g.first_wind = o.first_wind; g.same_wind_cnt = o.same_wind_cnt; g.illegal_seat = o.illegal_seat;
   g.end_type = o.end_type; g.winners = o.winners; g.loser = o.loser; g.tenpai_mask = o.tenpai_mask;
-  g.wall_sel = 0; g.dora_pending = o.dora_pending;                      // the imported wall goes to buffer 0
+  g.wall_sel = 0;                      // the imported wall goes to buffer 0
+  g.hist_len = o.n_hist > 128 ? 128 : o.n_hist;
+  for (int i = 0; i < 128; i++) e.hist[(int64_t)i * n] = o.hist[i];
   store_glob(e, g);
 }
 
@@ -278,6 +282,8 @@ MJ_HD void tok_river(const Env &e, int s, uint8_t out[32])
 #pragma unroll
   for (int i = 0; i < 32; i++) out[i] = i < nriv ? river_token(t[i]) : (uint8_t)255;
 }
+// one entry of the action history as viewer `me` sees it
+MJ_HD uint16_t hist_token(uint32_t ev, int me) { return (uint16_t)((ev & 0xFFu) | (((ev >> 8) - (uint32_t)me) & 3u) << 8); }
 // the whole record of viewer `me` (the plain composition; every field of the record is written)
 MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, const uint32_t *sh_suit, const uint32_t *sh_honor,
                      MjTokenObs &o)
@@ -290,6 +296,10 @@ MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, c
   tok_env(e, g, me, rule_flags, o);
   tok_seats(sw, score, meld, me, o);
   for (int rel = 0; rel < 4; rel++) tok_river(e, (me + rel) & 3, o.river[rel]);
+  o.n_hist = g.hist_len;
+  for (int i = 0; i < 15; i++) o.zero_[i] = 0;
+  for (int i = 0; i < 128; i++)
+    o.hist[i] = i < g.hist_len ? hist_token(e.hist[(int64_t)i * e.n], me) : (uint16_t)0xFFFF;
 }
 
 }  // namespace mj

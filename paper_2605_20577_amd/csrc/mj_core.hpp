@@ -91,6 +91,7 @@ struct Env {
   uint32_t *nexth, *nextred;                          // cold [16] [1]: its four dealt hands by seat wind, red fives
   uint64_t *nextwaits;                                // cold [4]: their waits
   uint8_t *river;                                     // cold [128]
+  uint16_t *hist;                                     // cold [128]: the kyoku's public actions in order, action | seat << 8
 };
 
 // control bytes kept in registers during a step (7 words in HBM)
@@ -98,12 +99,13 @@ struct Glob {
   uint8_t kyoku, honba, kyotaku, terminated;
   uint8_t draw_ptr, n_kan, live_left, n_dora;
   uint8_t drawn, phase, cur, actor_mask;
-  uint8_t riichi_pending, rinshan, last_discard, last_discarder;
+  uint8_t riichi_pending, kanflags, last_discard, last_discarder;   // kanflags: bit 0 the drawn tile is a replacement
+                                                                    // tile, bit 1 a kan indicator waits to be turned (F_KANDORA_LATE)
   uint8_t kakan_tile, kuikae0, kuikae1, first_wind;
   uint8_t same_wind_cnt, illegal_seat, end_type, winners;
   uint8_t loser, tenpai_mask;
   uint8_t wall_sel;     // which of the two wall buffers holds the current wall (not part of the logical state)
-  uint8_t dora_pending; // kan indicators not turned yet (F_KANDORA_LATE)
+  uint8_t hist_len;     // entries of Env::hist in use
 };
 union GlobU { Glob g; uint32_t w[7]; };
 

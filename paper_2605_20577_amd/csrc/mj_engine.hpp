@@ -123,9 +123,9 @@ MJ_HD void eval_seat(Ctx &c, int s, int w, bool tsumo, bool chankan, HandOut &ou
   int f = 0;
   if (tsumo) f |= 1;
   if (sw >> SW_IPPATSU & 1) f |= 2;
-  if (tsumo && c.g.rinshan) f |= 4;
+  if (tsumo && (c.g.kanflags & 1)) f |= 4;
   if (chankan) f |= 8;
-  if (tsumo && c.g.live_left == 0 && !c.g.rinshan) f |= 16;
+  if (tsumo && c.g.live_left == 0 && !(c.g.kanflags & 1)) f |= 16;
   if (!tsumo && !chankan && c.g.live_left == 0) f |= 32;
   if (tsumo && (sw >> SW_FIRST & 1)) f |= 64;
   q.flags = f;
@@ -275,7 +275,7 @@ MJ_HD void draw_live(Ctx &c, int s)
   c.live_ptr = -1;
   c.g.draw_ptr++;
   c.g.live_left--;
-  c.g.rinshan = 0;
+  c.g.kanflags &= (uint8_t)~1u;
   c.g.drawn = (uint8_t)take_tile(c, s, id);
 }
 
@@ -311,8 +311,8 @@ MJ_HD void deal_reset(Ctx &c)
     MELDW(c, s) = 0;
     DK(c, s) = 0;
   }
-  c.g.n_kan = 0; c.g.n_dora = 1; c.g.dora_pending = 0;
-  c.g.riichi_pending = 0; c.g.rinshan = 0;
+  c.g.n_kan = 0; c.g.n_dora = 1; c.g.hist_len = 0;
+  c.g.riichi_pending = 0; c.g.kanflags = 0;
   c.g.last_discard = 255; c.g.last_discarder = 255; c.g.kakan_tile = 255;
   c.g.kuikae0 = c.g.kuikae1 = 255;
   c.g.first_wind = 255; c.g.same_wind_cnt = 0;
@@ -554,8 +554,8 @@ MJ_HD void abortive_draw(Ctx &c, int type)
 // indicators of earlier open / added kans that wait to be turned are turned now (see MJ_F_KANDORA_LATE)
 MJ_HD void turn_pending_indicators(Ctx &c)
 {
-  c.g.n_dora = (uint8_t)(c.g.n_dora + c.g.dora_pending);
-  c.g.dora_pending = 0;
+  c.g.n_dora = (uint8_t)(c.g.n_dora + (c.g.kanflags >> 1 & 1));
+  c.g.kanflags &= (uint8_t)~2u;
 }
 
 // the replacement draw that completes any kan (the mask follows in step_finish); `open` = a kan from a discard or
@@ -564,14 +564,14 @@ MJ_HD void kan_draw(Ctx &c, bool open)
 {
   int s = c.g.cur;
   swf_set(c, s, SW_KANBY, 3, swf(c, s, SW_KANBY, 3) + 1);
-  if ((c.R.flags & F_KANDORA_LATE) && open) c.g.dora_pending++;
+  if ((c.R.flags & F_KANDORA_LATE) && open) c.g.kanflags |= 2;
   else c.g.n_dora++;
   int id = WALL(c, 122 + c.g.n_kan);
   c.g.n_kan++;
   c.g.live_left--;
   clear_first_and_ippatsu(c);
   c.g.drawn = (uint8_t)take_tile(c, s, id);
-  c.g.rinshan = 1;
+  c.g.kanflags |= 1;
   c.g.kakan_tile = 255;
 }
 
@@ -719,7 +719,7 @@ MJ_HD bool apply_call(Ctx &c, int s, int a)
   RIVER(c, d, (int)sw_get(sw_d, SW_NRIVER, 6) - 1) = (uint8_t)(c.g.last_discard | 0x80);      // the called tile, marked
   c.g.cur = (uint8_t)s;
   c.g.drawn = 255;
-  c.g.rinshan = 0;
+  c.g.kanflags &= (uint8_t)~1u;
   const bool red_held = su < 3 && r == 4 && (sw >> su & 1u);
   int tr = 0;                        // the red five leaves the hand
   uint32_t gone, meld;               // tiles taken from the hand (3-bit fields), the meld record
@@ -792,6 +792,13 @@ MJ_HD void mark_passed_ron(Ctx &c, int ron_offered)
     if (ron_offered >> s & 1) mark_furiten(c, s);
 }
 
+// the action history (section 3.2, "Observation Space"): one entry per public action, action | seat << 8
+MJ_HD void hist_push(Ctx &c, int s, int a)
+{
+  const int i = c.g.hist_len;
+  if (i < 128) { c.e.hist[(int64_t)i * c.e.n] = (uint16_t)(a | s << 8); c.g.hist_len = (uint8_t)(i + 1); }
+}
+
 // One step of one environment, as a fixed sequence of stages that every lane walks through in the same order
 // (each lane skips the stages it does not need), so that a wavefront executes each piece of code once per step:
 //   0 check the actions   1 apply them (discard, call, kan, declarations)   2 refresh the actor's waits
@@ -850,6 +857,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   uint32_t todo = 0;
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
+    hist_push(c, s, act);
     if (act < A_KAN) {
       const int k = act < A_DISCARD_RED ? act : 4 + 9 * (act - A_DISCARD_RED);
       // a seat in riichi gives back the drawn tile: its waits stay; any other seat's waits follow from the discard
@@ -874,6 +882,15 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   } else {
     int ronners = 0;
     for (int s = 0; s < 4; s++) if ((actors >> s & 1) && act_of(acts, s) == A_RON) ronners |= 1 << s;
+    if (ronners) {
+      // wins on a discard or on the tile of a kan, in turn order from the seat that gave the tile
+      const int from = c.g.phase == PH_RESPOND ? c.g.last_discarder : c.g.cur;
+#pragma unroll 1
+      for (int j = 1; j < 4; j++) {
+        const int o = (from + j) & 3;
+        if (ronners >> o & 1) hist_push(c, o, A_RON);
+      }
+    }
     if (c.g.phase == PH_RESPOND) {
       int d = c.g.last_discarder;
       if (popc32((uint32_t)ronners) == 3 && (c.R.flags & F_ABORT)) end_abort = 8;
@@ -886,6 +903,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
         if (caller < 0 && (actors >> nx & 1) && act_of(acts, nx) >= A_CHI_L && act_of(acts, nx) < A_PASS) { caller = nx; call = act_of(acts, nx); }
         end_abort = settle_discard(c);
         if (!end_abort) {
+          if (caller >= 0) hist_push(c, caller, call);
           if (caller < 0) todo |= DO_ADVANCE;
           else if (apply_call(c, caller, call)) { waits_seat = caller; todo |= DO_KANFIN; }
           else c.need_turn = true;

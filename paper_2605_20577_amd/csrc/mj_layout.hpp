@@ -8,8 +8,8 @@
 //   u32 hot : score[4] delta[4] episode serial hand[16] seatw[4]            (30 arrays)
 //   u32 cold: gain[4] glob[7] wall[2][34] (two buffers of 136 tile ids, four per word: the current wall and
 //             the next one) next_serial next_hand[16] next_red (the next deal, made ahead)     (97 arrays)
-//   u8  cold: river[128]                                                    (128 arrays)
-// = 900 bytes per environment, 288 of them hot.  The "next" arrays are not part of the logical state: they are
+//   u8  cold: river[128]; then u16 cold: history[128] (action | seat << 8)  (128 + 2 x 128 bytes)
+// = 1,156 bytes per environment, 288 of them hot.  The "next" arrays are not part of the logical state: they are
 // a pure function of (seed, env id, kyoku_serial + 1), valid when next_serial says so; tenpai_discards is a cache
 // (a function of the hand of the seat to move, valid when its top bit is set).  The step kernels copy the
 // hot arrays of their block into LDS, run there, and copy them back.
@@ -18,7 +18,7 @@
 
 namespace mj {
 
-constexpr int kHotU64 = 21, kColdU64 = 12, kHotU32 = 30, kColdU32 = 97, kU8Arrays = 128;
+constexpr int kHotU64 = 21, kColdU64 = 12, kHotU32 = 30, kColdU32 = 97, kU8Arrays = 384;
 constexpr int kU64Arrays = kHotU64 + kColdU64, kU32Arrays = kHotU32 + kColdU32;
 constexpr int64_t kBytesPerEnv = 8 * kU64Arrays + 4 * kU32Arrays + kU8Arrays;
 constexpr int kHotBytesPerEnv = 8 * kHotU64 + 4 * kHotU32;
@@ -48,6 +48,7 @@ MJ_HD Env make_env(void *state, int64_t B, int64_t b)
   e.wallw = w + (int64_t)(kHotU32 + 11) * B;
   e.nserial = w + (int64_t)(kHotU32 + 79) * B; e.nexth = w + (int64_t)(kHotU32 + 80) * B;
   e.nextred = w + (int64_t)(kHotU32 + 96) * B; e.nextwaits = q + (int64_t)(kHotU64 + 8) * B; e.river = y;
+  e.hist = (uint16_t *)(state_u8(state, B) + (int64_t)128 * B) + b;
   return e;
 }
 

@@ -23,8 +23,8 @@
 
 using namespace mj;
 
-static_assert(sizeof(MjTokenObs) == 224, "token record");
-static_assert(sizeof(MjEnvCanon) == 744, "canonical record layout");
+static_assert(sizeof(MjTokenObs) == 496, "token record");
+static_assert(sizeof(MjEnvCanon) == 1000, "canonical record layout");
 static_assert(sizeof(MjHandQuery) == 64 && sizeof(MjHandResult) == 24, "hand records");
 static_assert(sizeof(Glob) == 28, "control bytes");
 
@@ -211,7 +211,7 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_
 #pragma unroll
       for (int s = 0; s < 4; s++) WAITS(c, s) = w4[s];
       // the dealer's first draw (wall[52]) without going through HBM
-      c.g.draw_ptr = 53; c.g.live_left = 69; c.g.rinshan = 0;
+      c.g.draw_ptr = 53; c.g.live_left = 69; c.g.kanflags &= (uint8_t)~1u;
       c.g.drawn = (uint8_t)take_tile(c, dealer, (int)first_id);
       c.need_deal = false;
       c.need_turn = true;
@@ -290,7 +290,7 @@ __device__ __forceinline__ void deal_from_next(Ctx &c)
     SW(c, s) |= (reds >> (3 * j)) & 7u;
     WAITS(c, s) = wt[j];
   }
-  c.g.draw_ptr = 53; c.g.live_left = 69; c.g.rinshan = 0;
+  c.g.draw_ptr = 53; c.g.live_left = 69; c.g.kanflags &= (uint8_t)~1u;
   c.g.drawn = (uint8_t)take_tile(c, dealer, (int)first);
   c.need_deal = false;
   c.need_turn = true;
@@ -668,13 +668,17 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
 // Token observation.  One lane per (environment, seat).  What the four viewers of a game share is computed once:
 // lane (env, s) turns seat s's river into token bytes and publishes the seat's control word, points and melds in
 // LDS; then, as viewer s, it writes the first 96 bytes of its record (own hand, shanten number, scalars, the seats'
-// words rotated to it) into LDS.  The block then streams the records out, consecutive lanes on consecutive
-// 16 bytes: six chunks from the record head, eight from the four rivers picked by relative seat.
+// words rotated to it) into LDS, and stages a quarter of the game's action history (two entries per word, absolute
+// seats).  The block then streams the records out, one record per wavefront and iteration, consecutive lanes on
+// consecutive words: 24 words from the record head, 32 from the four rivers picked by relative seat, 4 for the
+// length of the history, 64 of history with the seats turned to the viewer.
 constexpr int kTokEnvs = kAuxBlock / 4;           // 64 environments per block
 constexpr int kTokHead = 96;                      // bytes of MjTokenObs before river[][]
 constexpr int kTokHeadStride = 100, kTokRivStride = 36;   // LDS strides: an odd number of words, so that the lanes of a
                                                           // wavefront (consecutive environments) fall into different banks
-static_assert(offsetof(MjTokenObs, river) == kTokHead && sizeof(MjTokenObs) == kTokHead + 128, "token record layout");
+constexpr int kTokHistStride = 65;                // words per game in the LDS copy of the history (odd, as above)
+static_assert(offsetof(MjTokenObs, river) == kTokHead && offsetof(MjTokenObs, n_hist) == kTokHead + 128 &&
+              offsetof(MjTokenObs, hist) == kTokHead + 144 && sizeof(MjTokenObs) == kTokHead + 144 + 256, "token record layout");
 __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64_t B, uint32_t rule_flags, const uint32_t *sh_suit,
                                                            const uint32_t *sh_honor, MjTokenObs *out)
 {
@@ -683,6 +687,8 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
   __shared__ uint32_t p_sw[4][kTokEnvs];
   __shared__ int32_t p_score[4][kTokEnvs];
   __shared__ uint64_t p_meld[4][kTokEnvs];
+  __shared__ uint32_t p_hist[kTokEnvs][kTokHistStride];                    // two entries per word: action | seat << 8
+  __shared__ uint32_t p_nhist[kTokEnvs];
   const int tid = threadIdx.x;
   const int64_t base = (int64_t)blockIdx.x * kTokEnvs;
   const int nenv = (int)((B - base) < kTokEnvs ? (B - base) : kTokEnvs);
@@ -699,6 +705,18 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
     load_glob(e, g);
     tok_own(e, s, sh_suit, sh_honor, o);
     tok_env(e, g, s, rule_flags, o);
+    // entries 32 s .. 32 s + 31 of the history: 2-byte loads, consecutive games on consecutive addresses
+    const int nh = g.hist_len;
+    if (s == 0) p_nhist[el] = (uint32_t)nh;
+    uint16_t hv[32];
+#pragma unroll
+    for (int j = 0; j < 32; j++) hv[j] = e.hist[(int64_t)(32 * s + j) * B];      // all 32 loads in flight together
+#pragma unroll
+    for (int j = 0; j < 16; j++) {
+      const int i0 = 32 * s + 2 * j;
+      const uint32_t lo = i0 < nh ? (uint32_t)hv[2 * j] : 0xFFFFu, hi = i0 + 1 < nh ? (uint32_t)hv[2 * j + 1] : 0xFFFFu;
+      p_hist[el][16 * s + j] = lo | hi << 16;
+    }
   }
   __syncthreads();
   if (on) {
@@ -708,20 +726,36 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
     tok_seats(sw, sc, ml, s, o);
   }
   __syncthreads();
-  // out: lane c < 56 of a wavefront owns word c of every record the wavefront writes (one record per iteration, 224
-  // consecutive bytes), so the source is a fixed offset plus a stride: 24 words from the record head, 32 from the
-  // rivers picked by relative seat
-  constexpr int kRecWords = (int)(sizeof(MjTokenObs) / 4), kHeadWords = kTokHead / 4;
-  const int c = tid & 63, wave = tid >> 6;
-  if (c < kRecWords) {
-    uint32_t *dst = (uint32_t *)(out + base * 4) + c;
-    const bool in_head = c < kHeadWords;
-    const int rel = (c - kHeadWords) >> 3, w = (c - kHeadWords) & 7;
-    for (int rec = wave; rec < nenv * 4; rec += kAuxBlock / 64) {
-      const int env = rec >> 2, me = rec & 3;
-      const uint32_t *src = in_head ? (const uint32_t *)head[me][env] + c : (const uint32_t *)riv[(me + rel) & 3][env] + w;
-      __builtin_nontemporal_store(*src, dst + (size_t)rec * kRecWords);
-    }
+  // out: wavefront `me` writes the records of viewer `me`, one game per iteration; lane c owns words c and 64 + c of
+  // the record (124 words), so each of its two sources is a fixed LDS address plus a stride per game
+  constexpr int kRecWords = (int)(sizeof(MjTokenObs) / 4), kHeadWords = kTokHead / 4, kRivWords = 32, kLenWords = 4;
+  constexpr int kHistWord0 = kHeadWords + kRivWords + kLenWords;             // 60
+  static_assert(kRecWords == kHistWord0 + 64 && kHistWord0 <= 64 && kAuxBlock / 64 == 4, "token record words");
+  const int c = tid & 63, me = tid >> 6;
+  const uint8_t *src0;
+  int stride0;
+  if (c < kHeadWords) { src0 = &head[me][0][4 * c]; stride0 = kTokHeadStride; }
+  else if (c < kHeadWords + kRivWords) { src0 = &riv[(me + ((c - kHeadWords) >> 3)) & 3][0][4 * ((c - kHeadWords) & 7)]; stride0 = kTokRivStride; }
+  else if (c < kHistWord0) { src0 = (const uint8_t *)&p_nhist[0]; stride0 = 4; }
+  else { src0 = (const uint8_t *)&p_hist[0][c - kHistWord0]; stride0 = 4 * kTokHistStride; }
+  const bool len_pad = c > kHeadWords + kRivWords && c < kHistWord0, hist0 = c >= kHistWord0, two = c < kRecWords - 64;
+  const uint8_t *src1 = (const uint8_t *)&p_hist[0][two ? c + 64 - kHistWord0 : 0];
+  // a history word as this viewer sees it: seats turned, unused entries left at 0xFFFF
+  const uint32_t sub = 0x00040004u - (uint32_t)me * 0x00010001u;
+  auto turned = [&](uint32_t x) {
+    uint32_t y = (x & 0x00FF00FFu) | (((x >> 8 & 0x00030003u) + sub) & 0x00030003u) << 8;
+    if ((x & 0xFFu) == 0xFFu) y |= 0x0000FFFFu;
+    if ((x >> 16 & 0xFFu) == 0xFFu) y |= 0xFFFF0000u;
+    return y;
+  };
+  uint32_t *dst = (uint32_t *)(out + base * 4) + (size_t)me * kRecWords + c;
+#pragma unroll 4
+  for (int env = 0; env < nenv; env++) {
+    uint32_t v = *(const uint32_t *)(src0 + env * stride0);
+    if (len_pad) v = 0u;
+    if (hist0) v = turned(v);
+    __builtin_nontemporal_store(v, dst + (size_t)env * 4 * kRecWords);
+    if (two) __builtin_nontemporal_store(turned(*(const uint32_t *)(src1 + env * 4 * kTokHistStride)), dst + (size_t)env * 4 * kRecWords + 64);
   }
 }
 

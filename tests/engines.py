@@ -23,6 +23,10 @@ class GpuEngine:
     def observe(self):
         return self.env.observe().cpu().numpy()
 
+    def observe_tokens(self):
+        import paper_2605_20577_amd as mj
+        return self.env.observe_tokens().cpu().numpy().view(mj.TOKEN_DTYPE).reshape(self.B, 4)
+
     def reward(self):
         d, r, t = self.env.reward()
         return d.cpu().numpy(), r.cpu().numpy(), t.cpu().numpy()

@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
     lib.mj_strerror.restype = ctypes.c_char_p
     assert lib.mj_strerror(-1) == b"bad argument"
     r = b.MjRules(12, 0, 25000, -1.0, 2)
-    assert b.mj_state_bytes(65536, r) == 65536 * 900 and b.mj_state_bytes(0, r) == 0
+    assert b.mj_state_bytes(65536, r) == 65536 * 1156 and b.mj_state_bytes(0, r) == 0
     assert 0 < b.mj_scratch_bytes(1, r) < 16 << 20          # tables only (8 MB of shanten block tables), independent of B
 
 

@@ -460,3 +460,37 @@ def test_liability_for_the_three_dragons(engine):
         e = _play_out(o, tsumo=(1,), **plan)
         assert e["end_type"] == 1 and e["yakuman_units"][1] == 2 and e["yaku"][1] == (1 << 34) | (1 << 37)
         assert e["delta"].tolist() == want
+
+
+def test_action_history(engine):
+    """the kyoku's public actions in the order they took effect (action | seat << 8), and the viewer's copy of them
+    with relative seats; passes are not recorded"""
+    hands = ["55p 147m 28p 369s 123z", "5p 258m 39p 147s 1247z", "234m 46p 456s 22s 678s", J3]
+    o = engine()
+    o.deal_from_wall(0, build_wall(hands, draws="4z 9m 7z 6z 5z 5p", dora="1z"))
+    script = [({0: kind("4z")}, (0, kind("4z"))), ({1: kind("5p")}, (1, kind("5p"))), ({0: A_PON, 2: A_PASS}, (0, A_PON)),
+              ({0: kind("1m")}, (0, kind("1m"))), ({1: kind("7z")}, (1, kind("7z"))), ({2: kind("6z")}, (2, kind("6z"))),
+              ({3: kind("5z")}, (3, kind("5z"))), ({0: A_KAN + kind("5p")}, (0, A_KAN + kind("5p"))), ({2: A_RON}, (2, A_RON))]
+    want = []
+    for moves, (seat, action) in script:
+        e = act(o, 0, moves)
+        want.append(action | seat << 8)
+        assert e["n_hist"] == len(want) and e["hist"][:len(want)].tolist() == want and (e["hist"][len(want):] == 0).all()
+        t = o.observe_tokens()[0]
+        for me in range(4):
+            assert t["n_hist"][me] == len(want) and (t["zero_"][me] == 0).all()
+            assert t["hist"][me][:len(want)].tolist() == [(w & 0xFF) | (((w >> 8) - me) & 3) << 8 for w in want]
+            assert (t["hist"][me][len(want):] == 0xFFFF).all()
+    assert e["end_type"] == 2 and e["terminated"] == 1
+    # a new kyoku starts with an empty history; a double ron is recorded in turn order from the discarder
+    o = engine(mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, build_wall([J1, TENPAI, J2, TENPAI2], draws="5p", dora="1z"))
+    e = act(o, 0, {0: kind("5p")})
+    assert e["hist"][:1].tolist() == [kind("5p")] and A_RON in bits(e["mask"][1]) and A_RON in bits(e["mask"][3])
+    e = act(o, 0, {1: A_RON, 3: A_RON})
+    assert e["end_type"] == 2 and e["winners"] == 0b1010 and e["kyoku_serial"] == 1 and e["n_hist"] == 0 and (e["hist"] == 0).all()
+    o = engine()                                   # a single kyoku: the game ends there and the history stays
+    o.deal_from_wall(0, build_wall([J1, TENPAI, J2, TENPAI2], draws="5p", dora="1z"))
+    act(o, 0, {0: kind("5p")})
+    e = act(o, 0, {1: A_RON, 3: A_RON})
+    assert e["terminated"] == 1 and e["hist"][:3].tolist() == [kind("5p"), A_RON | 1 << 8, A_RON | 3 << 8] and e["n_hist"] == 3
