@@ -666,9 +666,9 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
 }
 
 // Token observation.  One lane per (environment, seat).  What the four viewers of a game share is computed once:
-// lane (env, s) turns seat s's river into token bytes and publishes the seat's control word, points and melds in
-// LDS; then, as viewer s, it writes the first 96 bytes of its record (own hand, shanten number, scalars, the seats'
-// words rotated to it) into LDS, and stages a quarter of the game's action history (two entries per word, absolute
+// lane (env, s) turns seat s's river into token bytes in LDS; as viewer s, it writes the first 96 bytes of its record
+// (own hand, shanten number, scalars, the seats' words rotated to it) into LDS, and stages a quarter of the game's
+// action history (two entries per word, absolute
 // seats).  The block then streams the records out, one record per wavefront and iteration, consecutive lanes on
 // consecutive words: 24 words from the record head, 32 from the four rivers picked by relative seat, 4 for the
 // length of the history, 64 of history with the seats turned to the viewer.
@@ -684,9 +684,6 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
 {
   __shared__ __align__(4) uint8_t head[4][kTokEnvs][kTokHeadStride];       // [viewer][env]
   __shared__ __align__(4) uint8_t riv[4][kTokEnvs][kTokRivStride];         // [seat][env]
-  __shared__ uint32_t p_sw[4][kTokEnvs];
-  __shared__ int32_t p_score[4][kTokEnvs];
-  __shared__ uint64_t p_meld[4][kTokEnvs];
   __shared__ uint32_t p_hist[kTokEnvs][kTokHistStride];                    // two entries per word: action | seat << 8
   __shared__ uint32_t p_nhist[kTokEnvs];
   const int tid = threadIdx.x;
@@ -700,7 +697,13 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
   MjTokenObs &o = *(MjTokenObs *)head[on ? s : 0][on ? el : 0];
   if (on) {
     tok_river(e, s, riv[s][el]);
-    p_sw[s][el] = e.seatw[s * B]; p_score[s][el] = e.score[s * B]; p_meld[s][el] = e.meld[s * B];
+    // the four seats' public words, read by each of the game's four lanes (the repeats are cache hits): 52 KB of LDS
+    // instead of 56 KB lets three blocks share a compute unit
+    uint32_t sw[4];
+    int32_t sc[4];
+    uint64_t ml[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) { sw[t] = e.seatw[t * B]; sc[t] = e.score[t * B]; ml[t] = e.meld[t * B]; }
     Glob g;
     load_glob(e, g);
     tok_own(e, s, sh_suit, sh_honor, o);
@@ -717,29 +720,20 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
       const uint32_t lo = i0 < nh ? (uint32_t)hv[2 * j] : 0xFFFFu, hi = i0 + 1 < nh ? (uint32_t)hv[2 * j + 1] : 0xFFFFu;
       p_hist[el][16 * s + j] = lo | hi << 16;
     }
-  }
-  __syncthreads();
-  if (on) {
-    const uint32_t sw[4] = {p_sw[0][el], p_sw[1][el], p_sw[2][el], p_sw[3][el]};
-    const int32_t sc[4] = {p_score[0][el], p_score[1][el], p_score[2][el], p_score[3][el]};
-    const uint64_t ml[4] = {p_meld[0][el], p_meld[1][el], p_meld[2][el], p_meld[3][el]};
     tok_seats(sw, sc, ml, s, o);
   }
   __syncthreads();
-  // out: wavefront `me` writes the records of viewer `me`, one game per iteration; lane c owns words c and 64 + c of
-  // the record (124 words), so each of its two sources is a fixed LDS address plus a stride per game
-  constexpr int kRecWords = (int)(sizeof(MjTokenObs) / 4), kHeadWords = kTokHead / 4, kRivWords = 32, kLenWords = 4;
-  constexpr int kHistWord0 = kHeadWords + kRivWords + kLenWords;             // 60
-  static_assert(kRecWords == kHistWord0 + 64 && kHistWord0 <= 64 && kAuxBlock / 64 == 4, "token record words");
-  const int c = tid & 63, me = tid >> 6;
-  const uint8_t *src0;
-  int stride0;
-  if (c < kHeadWords) { src0 = &head[me][0][4 * c]; stride0 = kTokHeadStride; }
-  else if (c < kHeadWords + kRivWords) { src0 = &riv[(me + ((c - kHeadWords) >> 3)) & 3][0][4 * ((c - kHeadWords) & 7)]; stride0 = kTokRivStride; }
-  else if (c < kHistWord0) { src0 = (const uint8_t *)&p_nhist[0]; stride0 = 4; }
-  else { src0 = (const uint8_t *)&p_hist[0][c - kHistWord0]; stride0 = 4 * kTokHistStride; }
-  const bool len_pad = c > kHeadWords + kRivWords && c < kHistWord0, hist0 = c >= kHistWord0, two = c < kRecWords - 64;
-  const uint8_t *src1 = (const uint8_t *)&p_hist[0][two ? c + 64 - kHistWord0 : 0];
+  // out: wavefront `me` writes the records of viewer `me`, two games per iteration; each half of the wavefront streams
+  // one record of 31 chunks of 16 bytes (6 from the record head, 8 from the four rivers picked by relative seat, 1 with
+  // the length of the history, 16 of history), lane by lane on consecutive addresses; a lane's source is a fixed LDS
+  // address plus a stride per game
+  static_assert(sizeof(MjTokenObs) == 31 * 16 && kAuxBlock / 64 == 4, "token record chunks");
+  const int lane = tid & 63, me = tid >> 6, ch = lane & 31;
+  const bool live = ch < 31, is_len = ch == 14, is_hist = ch > 14;
+  const uint8_t *src = &head[me][0][16 * (ch < 6 ? ch : 0)];
+  int stride = kTokHeadStride;
+  if (ch >= 6 && ch < 14) { src = &riv[(me + ((ch - 6) >> 1)) & 3][0][16 * ((ch - 6) & 1)]; stride = kTokRivStride; }
+  if (is_hist && live) { src = (const uint8_t *)&p_hist[0][4 * (ch - 15)]; stride = 4 * kTokHistStride; }
   // a history word as this viewer sees it: seats turned, unused entries left at 0xFFFF
   const uint32_t sub = 0x00040004u - (uint32_t)me * 0x00010001u;
   auto turned = [&](uint32_t x) {
@@ -748,14 +742,15 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
     if ((x >> 16 & 0xFFu) == 0xFFu) y |= 0xFFFF0000u;
     return y;
   };
-  uint32_t *dst = (uint32_t *)(out + base * 4) + (size_t)me * kRecWords + c;
-#pragma unroll 4
-  for (int env = 0; env < nenv; env++) {
-    uint32_t v = *(const uint32_t *)(src0 + env * stride0);
-    if (len_pad) v = 0u;
-    if (hist0) v = turned(v);
-    __builtin_nontemporal_store(v, dst + (size_t)env * 4 * kRecWords);
-    if (two) __builtin_nontemporal_store(turned(*(const uint32_t *)(src1 + env * 4 * kTokHistStride)), dst + (size_t)env * 4 * kRecWords + 64);
+  u32x4 *dst = (u32x4 *)(out + base * 4 + me) + ch;
+#pragma unroll 2
+  for (int env = lane >> 5; env < nenv; env += 2) {
+    const uint32_t *p = (const uint32_t *)(src + env * stride);
+    u32x4 v;
+    v.x = p[0]; v.y = p[1]; v.z = p[2]; v.w = p[3];
+    if (is_hist) { v.x = turned(v.x); v.y = turned(v.y); v.z = turned(v.z); v.w = turned(v.w); }
+    if (is_len) { v.x = p_nhist[env]; v.y = 0u; v.z = 0u; v.w = 0u; }
+    if (live) __builtin_nontemporal_store(v, dst + (size_t)env * (4 * sizeof(MjTokenObs) / 16));
   }
 }
 
