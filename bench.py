@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the batched Riichi Mahjong environment step on one MI355X.
 
-Workload (benchmark configs[2]): B = 65,536 four-player games, no-red rules, full hanchan, uniform-random
+Workload: B = 65,536 four-player games, no-red rules, full hanchan, uniform-random
 legal policy (Philox keyed by seed, env, step, seat), auto-reset; W warm-up steps, then exactly K timed steps.
 One "step" = one batched step of all B games = B env steps.  State lives in HBM before the timed region.
 
@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 TOKEN_BYTES_PER_ENV = 4 * 496      # token observation written per game (4 viewers)
-# Algorithmic HBM bytes of one env step of the fused path ("Algorithmic bytes"): the state fields a
+# Algorithmic HBM bytes of one env step of the fused path: the state fields a
 # step has to read and write when nothing is cached between steps, outputs included.
 ALGO_BYTES_PER_ENV_STEP = 512
 OBS_BYTES_PER_ENV = 4 * 56 * 34
@@ -71,7 +71,7 @@ def main():
                     help="only run a plain device copy of 1 GiB three times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (environments are independent; see DESIGN.md for sharding); "
+        print("bench.py: this build runs on ONE GPU (environments are independent, so a batch shards by env id); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
