@@ -183,6 +183,46 @@ def test_full_size_sampled_envs():
         g.close()
 
 
+def test_full_size_observation_workload():
+    """B = 2^20, red rules, the observation written after every step (the large configuration of the benchmark, in
+    its launch shape): sampled environments recomputed one by one by the oracle -- record, plane observation, token
+    observation -- and whole-batch properties of the observation tensor"""
+    import torch
+    B, steps = 1 << 20, 12
+    g = GpuEngine(B, seed=3, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    obs = torch.zeros((B, 4, 56, 34), dtype=torch.uint8, device="cuda:0")
+    g.env.step_random(steps, True, obs)
+    tok = g.env.observe_tokens()
+    rng = np.random.default_rng(2)
+    ids = sorted(set([0, 31, 32, 65535, 65536, B - 33, B - 1] + rng.integers(0, B, 17).tolist()))
+    import paper_2605_20577_amd as mj
+    for b in ids:
+        o = mjo.Oracle(1, 3, mjo.RULES_RED, mjo.MODE_HALF, env_id_base=b)
+        o.step_random(steps)
+        d = diff_records(o.export(), g.export(b, 1))
+        assert not d, (b, d[:4])
+        assert np.array_equal(o.observe()[0], obs[b].cpu().numpy()), b
+        assert o.observe_tokens()[0].tobytes() == tok[b].cpu().numpy().tobytes(), b
+    # every byte is 0 or 1; the own-hand planes of a viewer count 13 or 14 tiles minus three per meld
+    assert int(obs.max()) == 1
+    hand_tiles = obs[:, :, 0:4, :].sum(dim=(2, 3), dtype=torch.int32).cpu().numpy()
+    e = g.export()
+    expect = 13 - 3 * e["n_meld"].astype(np.int32)
+    turn = (e["phase"] == 0) & (e["drawn"] != 255)
+    expect[np.arange(B)[turn], e["cur"][turn]] += 1
+    after_call = (e["phase"] == 0) & (e["drawn"] == 255)            # a claim: the seat to move holds one tile more
+    expect[np.arange(B)[after_call], e["cur"][after_call]] += 1
+    assert np.array_equal(hand_tiles, expect)
+    # the fused path over the same batch: one launch, sixteen times what the machine holds at once
+    g.step_random(300)
+    for b in ids[::3]:
+        o = mjo.Oracle(1, 3, mjo.RULES_RED, mjo.MODE_HALF, env_id_base=b)
+        o.step_random(steps + 300)
+        d = diff_records(o.export(), g.export(b, 1))
+        assert not d, (b, d[:4])
+    g.close()
+
+
 def test_import_export_roundtrip():
     o = mjo.Oracle(64, 8, mjo.RULES_RED, mjo.MODE_HALF)
     o.step_random(333)
