@@ -666,17 +666,22 @@ MJ_HD uint32_t chi_options(const Ctx &c, int su, int r, uint32_t sw, uint32_t hw
   return m;
 }
 
-// seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later
-MJ_HD void apply_discard(Ctx &c, int s, int k, int red)
+// seat s puts the tile (kind k, red flag) into its river; everything that follows from it comes later.
+// The three words it changes are read together, changed in registers and written once; returns the suit word of the
+// hand after the discard and, in was_riichi, whether the seat is in riichi.
+MJ_HD uint32_t apply_discard(Ctx &c, int s, int k, int red, bool &was_riichi)
 {
   turn_pending_indicators(c);
-  hand_add(c, s, k, -1);
+  const int su = suit_of(k);
   uint32_t sw = SW(c, s);
+  uint32_t hw = HW(c, s, su);
+  const uint64_t dk = DK(c, s);
+  hw -= 1u << (3 * rank_of(k, su));
+  was_riichi = sw_get(sw, SW_RIICHI, 2) != 0;
   if (red) sw &= ~(1u << (k / 9));
   int nr = (int)sw_get(sw, SW_NRIVER, 6);
   RIVER(c, s, nr) = (uint8_t)(k | red << 6);
   sw = sw_set(sw, SW_NRIVER, 6, nr + 1);
-  DK(c, s) |= kbit(k);
   sw &= ~(1u << SW_FTEMP);
   if (sw_get(sw, SW_RIICHI, 2)) sw &= ~(1u << SW_IPPATSU);
   if ((sw >> SW_FIRST & 1) && c.g.same_wind_cnt != 255) {
@@ -684,11 +689,14 @@ MJ_HD void apply_discard(Ctx &c, int s, int k, int red)
     else c.g.same_wind_cnt = 255;
   }
   sw &= ~(1u << SW_FIRST);
+  HW(c, s, su) = hw;
+  DK(c, s) = dk | kbit(k);
   SW(c, s) = sw;
   c.g.kuikae0 = c.g.kuikae1 = 255;
   c.g.last_discard = (uint8_t)(k | red << 6);
   c.g.last_discarder = (uint8_t)s;
   c.g.drawn = 255;
+  return hw;
 }
 
 MJ_HD void remove_tiles(Ctx &c, int s, int k, int n_nonred, int take_red)
@@ -855,14 +863,16 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   // scalar register pair across the stages)
   enum : uint32_t { DO_RESPOND = 1, DO_ROB = 2, DO_ADVANCE = 4, DO_KANFIN = 8, WIN_TSUMO = 16, WIN_ROB = 32, KAN_CONCEALED = 64 };
   uint32_t todo = 0;
+  uint32_t discard_hw = 0;           // the discarder's hand word of the discarded tile's suit, after the discard
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
     hist_push(c, s, act);
     if (act < A_KAN) {
       const int k = act < A_DISCARD_RED ? act : 4 + 9 * (act - A_DISCARD_RED);
       // a seat in riichi gives back the drawn tile: its waits stay; any other seat's waits follow from the discard
-      if (!sw_get(SW(c, s), SW_RIICHI, 2)) { waits_seat = s; waits_k = k; }
-      apply_discard(c, s, k, act < A_DISCARD_RED ? 0 : 1);
+      bool was_riichi;
+      discard_hw = apply_discard(c, s, k, act < A_DISCARD_RED ? 0 : 1, was_riichi);
+      if (!was_riichi) { waits_seat = s; waits_k = k; }
       todo |= DO_RESPOND;
     } else if (act < A_RIICHI) {
       const int kk = act - A_KAN;
@@ -923,7 +933,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
       // a discard: the facts of the 14-tile hand came with the turn's mask, the discard changed one suit; the set of
       // tenpai-keeping discards, when it was searched for, says at once whether any wait is left
       const int cs = suit_of(waits_k);
-      const uint32_t facts = facts_update(c.L, (uint32_t)(td >> FACTS_SHIFT) & 0xFFFu, cs, HW(c, waits_seat, cs));
+      const uint32_t facts = facts_update(c.L, (uint32_t)(td >> FACTS_SHIFT) & 0xFFFu, cs, discard_hw);
       if ((td & TD_VALID) && !(td >> waits_k & 1)) WAITS(c, waits_seat) = (uint64_t)facts << FACTS_SHIFT | W_FACTS_VALID;
       else
         WAITS(c, waits_seat) = waits_from_facts(&c.L, HW(c, waits_seat, 0), HW(c, waits_seat, 1), HW(c, waits_seat, 2),
