@@ -149,6 +149,14 @@ def main():
             env.sample_random(a); env.step(a); env.reset_done()
         torch.cuda.synchronize()
         extras["unfused_api_env_steps_per_s"] = B * n / (time.perf_counter() - t0)
+        # the agent loop through mj_step_full: sample -> step with rewards, restart and next mask, two launches per step
+        sf = env.step_full(a, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            env.sample_random(a); env.step_full(a, True, sf)
+        torch.cuda.synchronize()
+        extras["step_full_api_env_steps_per_s"] = B * n / (time.perf_counter() - t0)
         env.close()
         # configs[4]: B = 1,048,576, red rules, observation tensor written every step
         try:

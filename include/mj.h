@@ -200,6 +200,18 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
  * step counter, which keys the random policy. */
 int mj_step(MjHandle *h, const int8_t *d_actions /*[B][4]*/, void *stream);
 
+/* The same step, handing back in the same launch what an agent loop reads after
+ * it (section 3.1: step returns the state with rewards, termination flags and
+ * the next legal_action_mask).  Every output pointer may be NULL.  d_delta,
+ * d_reward (as mj_reward) and d_terminated describe THIS step.  With auto_reset
+ * a game that this step ended (or that had ended before) is started again as by
+ * mj_reset_done before d_mask is written, so d_mask always belongs to the state
+ * the next actions are for; without it, ended games keep an empty mask.
+ * d_mask, d_delta, d_reward must be 16-byte aligned. */
+int mj_step_full(MjHandle *h, const int8_t *d_actions /*[B][4]*/, int auto_reset,
+                 uint64_t *d_mask /*[B][4][2]*/, int32_t *d_delta /*[B][4]*/, float *d_reward /*[B][4]*/,
+                 uint8_t *d_terminated /*[B]*/, void *stream);
+
 /* legal_action_mask (section 3.2): d_mask[b][s][w], bit a of word a >> 6; all
  * zero for seats that do not act and for terminated envs. */
 int mj_legal_mask(const MjHandle *h, uint64_t *d_mask /*[B][4][2]*/, void *stream);

@@ -69,6 +69,7 @@ EXPORTS = {
     "mj_init": (C.c_int, [C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.POINTER(MjRules),
                           C.c_void_p]),
     "mj_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mj_step_full": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_legal_mask": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_observe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_observe_tokens": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -143,6 +144,11 @@ def mj_init(state, scratch, B, seed, rules):
 
 def mj_step(h, actions):
     _check(lib().mj_step(h, _ptr(actions), _stream()))
+
+
+def mj_step_full(h, actions, auto_reset, mask=None, delta=None, reward=None, terminated=None):
+    _check(lib().mj_step_full(h, _ptr(actions), int(bool(auto_reset)), _ptr(mask), _ptr(delta), _ptr(reward), _ptr(terminated),
+                              _stream()))
 
 
 def mj_legal_mask(h, mask):
@@ -234,6 +240,22 @@ class MahjongEnv:
         a = a.to(self.device, dtype=torch.int8).contiguous()
         with self._dev():
             mj_step(self._h, a)
+
+    def step_full(self, actions, auto_reset=True, out=None):
+        """one launch: the step, this step's (delta int32 [B,4], reward float32 [B,4], terminated uint8 [B]), the restart
+        of finished games when auto_reset, and the legal mask (int64 [B,4,2]) of the state the next actions are for.
+        Returns (mask, delta, reward, terminated); `out` may hold these four tensors to write into."""
+        torch = self.torch
+        a = torch.as_tensor(np.ascontiguousarray(actions, dtype=np.int8).reshape(self.B, 4)) if not torch.is_tensor(actions) else actions
+        a = a.to(self.device, dtype=torch.int8).contiguous()
+        if out is None:
+            out = (torch.empty((self.B, 4, 2), dtype=torch.int64, device=self.device),
+                   torch.empty((self.B, 4), dtype=torch.int32, device=self.device),
+                   torch.empty((self.B, 4), dtype=torch.float32, device=self.device),
+                   torch.empty((self.B,), dtype=torch.uint8, device=self.device))
+        with self._dev():
+            mj_step_full(self._h, a, auto_reset, *out)
+        return out
 
     def legal_mask(self, out=None):
         """int64 tensor [B, 4, 2] holding the two 64-bit mask words per seat"""

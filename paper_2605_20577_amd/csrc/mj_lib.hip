@@ -354,8 +354,17 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_new_games(void *state, int64
   if (mode == 0 && active) refill_next_wall(c, m.col, m.epb, 1);
 }
 
+// what a step can hand back besides the new state (any pointer may be null)
+struct StepOut {
+  uint64_t *mask;          // [B][4][2] legal actions of the state after the step (after the restart, if any)
+  int32_t *delta;          // [B][4] point changes of this step
+  float *reward;           // [B][4] the same as reward (points / 1000, or the penalty for an illegal action)
+  uint8_t *terminated;     // [B] the game ended with this step (or had ended before)
+};
+
 template <int LPW>
-__global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions, int refill)
+__global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B, Rules R, DevTables T, const int8_t *actions, int refill,
+                                                 int auto_reset, StepOut out)
 {
   extern __shared__ __align__(16) uint8_t lds[];
   BlockMem m = stage_block<LPW>(T, lds);
@@ -369,9 +378,31 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B,
     load_glob(c.e, c.g);
     if (refill && c.e.nserial[0] != c.e.serial[0] + 1) refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
     step_env(c, ((const uint32_t *)actions)[b]);
+    // the step's own results go out before a finished game is started again
+    if (out.delta) ((int4 *)out.delta)[b] = make_int4(DELTA(c, 0), DELTA(c, 1), DELTA(c, 2), DELTA(c, 3));
+    if (out.reward) {
+      float r[4];
+#pragma unroll
+      for (int s = 0; s < 4; s++) r[s] = c.g.illegal_seat == s ? R.illegal_penalty : (float)DELTA(c, s) * 0.001f;
+      ((float4 *)out.reward)[b] = make_float4(r[0], r[1], r[2], r[3]);
+    }
+    if (out.terminated) out.terminated[b] = c.g.terminated;
+    if (auto_reset && c.g.terminated) reset_env(c, false);
   }
   deal_stage(c, active, state, B, b);
-  if (active) { step_finish(c); store_hot(m, state, B, b); store_glob(c.e, c.g); }
+  if (active) {
+    step_finish(c);
+    if (out.mask) {
+#pragma unroll
+      for (int s = 0; s < 4; s++) {
+        ulonglong2 w;
+        w.x = MASK(c, s, 0); w.y = MASK(c, s, 1);
+        ((ulonglong2 *)out.mask)[b * 4 + s] = w;
+      }
+    }
+    store_hot(m, state, B, b);
+    store_glob(c.e, c.g);
+  }
 }
 
 // the random policy for every acting seat of the lane's environment, packed as four signed bytes
@@ -916,7 +947,20 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
 int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
 {
   if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
-  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kRefillEvery == 0));
+  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kRefillEvery == 0), 0,
+                 StepOut{nullptr, nullptr, nullptr, nullptr});
+  h->step++;
+  return check(hipGetLastError());
+}
+
+int mj_step_full(MjHandle *h, const int8_t *d_actions, int auto_reset, uint64_t *d_mask, int32_t *d_delta, float *d_reward,
+                 uint8_t *d_terminated, void *stream)
+{
+  if (!h || !d_actions || ((uintptr_t)d_actions & 3) || ((uintptr_t)d_mask & 15) || ((uintptr_t)d_delta & 15) ||
+      ((uintptr_t)d_reward & 15))
+    return MJ_E_ARG;
+  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kRefillEvery == 0),
+                 auto_reset ? 1 : 0, StepOut{d_mask, d_delta, d_reward, d_terminated});
   h->step++;
   return check(hipGetLastError());
 }

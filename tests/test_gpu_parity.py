@@ -223,6 +223,29 @@ def test_full_size_observation_workload():
     g.close()
 
 
+@pytest.mark.parametrize("mode,auto_reset", [(mjo.MODE_SINGLE, True), (mjo.MODE_HALF, True), (mjo.MODE_EAST, False)])
+def test_step_full_equals_the_separate_calls(mode, auto_reset):
+    """mj_step_full hands back in one launch what step + reward + reset_done + legal_mask give on the oracle"""
+    B = 321
+    o = mjo.Oracle(B, 6, mjo.RULES_RED, mode)
+    g = GpuEngine(B, seed=6, flags=mjo.RULES_RED, mode=mode)
+    ended = 0
+    for t in range(260):
+        a = o.sample_random()
+        if t == 100:
+            a[7, :] = 84                              # an illegal action somewhere: the penalty must show in the reward
+        o.step(a)
+        want = o.reward()
+        if auto_reset:
+            o.reset_done()
+        mask, delta, reward, term = [x.cpu().numpy() for x in g.env.step_full(a, auto_reset)]
+        assert np.array_equal(delta, want[0]) and np.array_equal(reward, want[1]) and np.array_equal(term, want[2]), t
+        assert np.array_equal(mask.view(np.uint64), o.legal_mask()), t
+        ended += int(want[2].sum())
+    assert not diff_records(o.export(), g.export())
+    assert ended > 0
+
+
 def test_import_export_roundtrip():
     o = mjo.Oracle(64, 8, mjo.RULES_RED, mjo.MODE_HALF)
     o.step_random(333)
