@@ -147,8 +147,9 @@ inline uint32_t pack_frontier(const Frontier &f)
 {
   uint32_t v = 0;
   for (int m = 0; m < 5; m++) {
-    v |= (f.n[m] < 0 ? 7u : (uint32_t)f.n[m]) << (3 * m);
-    v |= (f.h[m] < 0 ? 7u : (uint32_t)f.h[m]) << (15 + 3 * m);
+    const int without = f.n[m], with = f.h[m];
+    v |= (uint32_t)(without < 0 ? 7 : without) << (3 * m);
+    v |= (uint32_t)(with < 0 ? 7 : with) << (15 + 3 * m);
   }
   return v;
 }
