@@ -45,6 +45,24 @@ def cpu_baseline(flags, mode, seconds_target=12.0):
                       "after 20 warm-up steps, single thread" % n}
 
 
+def cpu_all_cores(flags, mode, steps=400):
+    """the same oracle, one independent instance per host thread over consecutive env-id ranges (games never interact,
+    and the C oracle keeps no global state; ctypes drops the GIL during a call)"""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import mjo
+    threads = max(1, min(16, len(os.sched_getaffinity(0))))
+    per = 256
+    shards = [mjo.Oracle(per, 0, flags, mode, env_id_base=i * per) for i in range(threads)]
+    for o in shards:
+        o.step_random(10)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda o: o.step_random(steps), shards))
+    dt = time.perf_counter() - t0
+    return {"value": threads * per * steps / dt, "unit": "env steps/s", "cores": threads, "kind": "oracle",
+            "sample": "%d shards of 256 games, %d batched steps each, one thread per shard" % (threads, steps)}
+
+
 def timed_rollout(env, torch, warmup, steps, obs=None):
     env.step_random(warmup, True, obs)
     torch.cuda.synchronize()
@@ -212,6 +230,7 @@ def main():
     if not args.no_cpu:
         from oracle import mjo
         out["cpu_baseline"] = cpu_baseline(mjo.RULES_NORED, mjo.MODE_HALF)
+        out["cpu_baseline"]["all_cores"] = cpu_all_cores(mjo.RULES_NORED, mjo.MODE_HALF)
     print(json.dumps(out))
 
 
