@@ -54,7 +54,10 @@ def _check_transition(p, c, a, flags, mode):
         honba = int(p["honba"]) + 1
     assert int(c["honba"]) == min(honba, 255)
     last = {0: 0, 1: 3, 2: 7}[mode]
-    over = mode == 0 or (c["score"] - (c["delta"] if False else 0) < 0).any() or (not renchan and int(p["kyoku"]) == last)
+    if not flags & mjo.F_ENDGAME:
+        # the game is over after a single kyoku, when somebody is below zero, or when the last kyoku is not repeated
+        over = mode == 0 or bool((c["score"] < 0).any()) or (not renchan and int(p["kyoku"]) == last)
+        assert bool(c["terminated"]) == over
     if c["terminated"]:
         assert c["kyotaku"] == 0
         order = sorted(range(4), key=lambda s: (-int(c["score"][s]), s))
@@ -71,7 +74,9 @@ def _check_transition(p, c, a, flags, mode):
                 want[s] = 3000 // n if T >> s & 1 else -(3000 // (4 - n))
         extra = c["delta"] - want
         if c["terminated"]:
-            assert extra.sum() == 1000 * int(p["kyotaku"]) + (c["delta"].sum() - want.sum() - 1000 * int(p["kyotaku"]))
+            # the deposits left on the table go to the first in rank, and to nobody else
+            top = int(np.flatnonzero(c["final_rank"] == 0)[0])
+            assert extra[top] == 1000 * int(p["kyotaku"]) and extra.sum() == extra[top]
         else:
             assert (extra == 0).all()
     if et == 2:
