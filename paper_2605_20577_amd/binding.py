@@ -109,6 +109,17 @@ class MjError(RuntimeError):
     pass
 
 
+class _NoCtx:
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        return False
+
+
+_NOCTX = _NoCtx()
+
+
 def _check(rc):
     if rc != 0:
         raise MjError("libmj: %s (%d)" % (lib().mj_strerror(rc).decode(), rc))
@@ -118,9 +129,20 @@ def _ptr(t):
     return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p()
 
 
+_torch = None
+
+
+def _th():
+    """torch, imported once (device memory and streams only)"""
+    global _torch
+    if _torch is None:
+        import torch
+        _torch = torch
+    return _torch
+
+
 def _stream():
-    import torch
-    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return C.c_void_p(_th().cuda.current_stream().cuda_stream)
 
 
 # --- the C entry points under their own names (tensors in, nothing computed here) -------------------------
@@ -203,15 +225,26 @@ def mj_destroy(h):
     _check(lib().mj_destroy(h))
 
 
+def _npz_path(path):
+    """numpy appends .npz to a name without it when it writes; save and restore agree on the same file"""
+    path = os.fspath(path)
+    return path if path.endswith(".npz") else path + ".npz"
+
+
 class MahjongEnv:
     """B games on one GPU.  Owns the device buffers (torch tensors) that libmj works on."""
 
     def __init__(self, B, seed=0, flags=RULES_NORED, mode=MODE_SINGLE, start_score=25000, illegal_penalty=-1.0,
                  env_id_base=0, device="cuda:0"):
-        import torch
+        torch = _th()
         self.torch = torch
         self.B = int(B)
         self.device = torch.device(device)
+        if self.device.type != "cuda":
+            raise MjError("libmj runs on a GPU: device %r" % (device,))
+        if self.device.index is None:
+            self.device = torch.device("cuda", torch.cuda.current_device())
+        self._dev_index = self.device.index
         self.rules = MjRules(flags, env_id_base, start_score, illegal_penalty, mode)
         self._seed = int(seed)
         with torch.cuda.device(self.device):
@@ -232,12 +265,42 @@ class MahjongEnv:
             pass
 
     def _dev(self):
+        """context that makes the environment's device current; free when it already is"""
+        if self.torch.cuda.current_device() == self._dev_index:
+            return _NOCTX
         return self.torch.cuda.device(self.device)
 
-    def step(self, actions):
+    def _want(self, t, dtype, numel, name):
+        """a caller's tensor must be what the kernel will index: on this device, of this dtype, contiguous, large
+        enough; anything else is refused here, before a launch could read or write out of bounds"""
         torch = self.torch
-        a = torch.as_tensor(np.ascontiguousarray(actions, dtype=np.int8).reshape(self.B, 4)) if not torch.is_tensor(actions) else actions
-        a = a.to(self.device, dtype=torch.int8).contiguous()
+        if not torch.is_tensor(t):
+            raise MjError("%s: expected a torch tensor" % name)
+        if t.device != self.device:
+            raise MjError("%s: tensor is on %s, the environment on %s" % (name, t.device, self.device))
+        if t.dtype != dtype:
+            raise MjError("%s: dtype %s, expected %s" % (name, t.dtype, dtype))
+        if not t.is_contiguous():
+            raise MjError("%s: tensor is not contiguous" % name)
+        if t.numel() != numel:
+            raise MjError("%s: %d elements, expected %d" % (name, t.numel(), numel))
+        return t
+
+    def _actions(self, actions):
+        torch = self.torch
+        if not torch.is_tensor(actions):
+            a = np.ascontiguousarray(actions, dtype=np.int8)
+            if a.size != self.B * 4:
+                raise MjError("actions: %d elements, expected %d" % (a.size, self.B * 4))
+            return torch.from_numpy(a.reshape(self.B, 4)).to(self.device)
+        if actions.device != self.device or actions.dtype != torch.int8 or not actions.is_contiguous():
+            actions = actions.to(self.device, dtype=torch.int8).contiguous()
+        if actions.numel() != self.B * 4:
+            raise MjError("actions: %d elements, expected %d" % (actions.numel(), self.B * 4))
+        return actions
+
+    def step(self, actions):
+        a = self._actions(actions)
         with self._dev():
             mj_step(self._h, a)
 
@@ -246,13 +309,19 @@ class MahjongEnv:
         of finished games when auto_reset, and the legal mask (int64 [B,4,2]) of the state the next actions are for.
         Returns (mask, delta, reward, terminated); `out` may hold these four tensors to write into."""
         torch = self.torch
-        a = torch.as_tensor(np.ascontiguousarray(actions, dtype=np.int8).reshape(self.B, 4)) if not torch.is_tensor(actions) else actions
-        a = a.to(self.device, dtype=torch.int8).contiguous()
+        a = self._actions(actions)
         if out is None:
             out = (torch.empty((self.B, 4, 2), dtype=torch.int64, device=self.device),
                    torch.empty((self.B, 4), dtype=torch.int32, device=self.device),
                    torch.empty((self.B, 4), dtype=torch.float32, device=self.device),
                    torch.empty((self.B,), dtype=torch.uint8, device=self.device))
+        else:
+            if len(out) != 4:
+                raise MjError("step_full: out must hold (mask, delta, reward, terminated)")
+            self._want(out[0], torch.int64, self.B * 8, "step_full mask")
+            self._want(out[1], torch.int32, self.B * 4, "step_full delta")
+            self._want(out[2], torch.float32, self.B * 4, "step_full reward")
+            self._want(out[3], torch.uint8, self.B, "step_full terminated")
         with self._dev():
             mj_step_full(self._h, a, auto_reset, *out)
         return out
@@ -260,14 +329,16 @@ class MahjongEnv:
     def legal_mask(self, out=None):
         """int64 tensor [B, 4, 2] holding the two 64-bit mask words per seat"""
         torch = self.torch
-        m = out if out is not None else torch.empty((self.B, 4, 2), dtype=torch.int64, device=self.device)
+        m = (self._want(out, torch.int64, self.B * 8, "legal_mask out") if out is not None
+             else torch.empty((self.B, 4, 2), dtype=torch.int64, device=self.device))
         with self._dev():
             mj_legal_mask(self._h, m)
         return m
 
     def observe(self, out=None):
         torch = self.torch
-        o = out if out is not None else torch.empty((self.B, 4, 56, 34), dtype=torch.uint8, device=self.device)
+        o = (self._want(out, torch.uint8, self.B * 4 * 56 * 34, "observe out") if out is not None
+             else torch.empty((self.B, 4, 56, 34), dtype=torch.uint8, device=self.device))
         with self._dev():
             mj_observe(self._h, o)
         return o
@@ -276,7 +347,8 @@ class MahjongEnv:
         """token observation: uint8 tensor [B, 4, 496], one MjTokenObs per (game, viewer); view it on the host as
         TOKEN_DTYPE, or slice the byte fields on the device"""
         torch = self.torch
-        o = out if out is not None else torch.empty((self.B, 4, TOKEN_DTYPE.itemsize), dtype=torch.uint8, device=self.device)
+        o = (self._want(out, torch.uint8, self.B * 4 * TOKEN_DTYPE.itemsize, "observe_tokens out") if out is not None
+             else torch.empty((self.B, 4, TOKEN_DTYPE.itemsize), dtype=torch.uint8, device=self.device))
         with self._dev():
             mj_observe_tokens(self._h, o)
         return o
@@ -305,12 +377,15 @@ class MahjongEnv:
 
     def sample_random(self, out=None):
         torch = self.torch
-        a = out if out is not None else torch.empty((self.B, 4), dtype=torch.int8, device=self.device)
+        a = (self._want(out, torch.int8, self.B * 4, "sample_random out") if out is not None
+             else torch.empty((self.B, 4), dtype=torch.int8, device=self.device))
         with self._dev():
             mj_sample_random(self._h, a)
         return a
 
     def step_random(self, n, auto_reset=True, obs=None):
+        if obs is not None:
+            self._want(obs, self.torch.uint8, self.B * 4 * 56 * 34, "step_random obs")
         with self._dev():
             mj_step_random(self._h, n, auto_reset, obs is not None, obs)
 
@@ -335,14 +410,14 @@ class MahjongEnv:
         """checkpoint: the canonical records of every game, the step counter and the construction arguments
         (numpy .npz).  restore() of it continues the same trajectory, random policy included."""
         seed = int(self._seed)
-        np.savez_compressed(path, records=self.export(), step_count=np.uint64(self.step_count), B=np.int64(self.B),
+        np.savez_compressed(_npz_path(path), records=self.export(), step_count=np.uint64(self.step_count), B=np.int64(self.B),
                             seed=np.uint64(seed), flags=np.uint32(self.rules.flags), mode=np.uint8(self.rules.mode),
                             env_id_base=np.uint32(self.rules.env_id_base), start_score=np.int32(self.rules.start_score),
                             illegal_penalty=np.float32(self.rules.illegal_penalty))
 
     @classmethod
     def restore(cls, path, device="cuda:0"):
-        z = np.load(path, allow_pickle=False)
+        z = np.load(_npz_path(path), allow_pickle=False)
         env = cls(int(z["B"]), seed=int(z["seed"]), flags=int(z["flags"]), mode=int(z["mode"]),
                   start_score=int(z["start_score"]), illegal_penalty=float(z["illegal_penalty"]),
                   env_id_base=int(z["env_id_base"]), device=device)
@@ -370,8 +445,12 @@ class MahjongEnv:
 
     def eval_hands_device(self, dq, dr):
         """same, on records already resident on the device: uint8 tensors holding n MjHandQuery / n MjHandResult"""
+        torch = self.torch
+        if not torch.is_tensor(dq) or dq.numel() % QUERY_DTYPE.itemsize:
+            raise MjError("eval_hands_device: the query tensor must hold whole 64-byte records")
         n = dq.numel() // QUERY_DTYPE.itemsize
-        assert dq.is_contiguous() and dr.is_contiguous() and dr.numel() >= n * RESULT_DTYPE.itemsize
+        self._want(dq, torch.uint8, n * QUERY_DTYPE.itemsize, "eval_hands_device queries")
+        self._want(dr, torch.uint8, n * RESULT_DTYPE.itemsize, "eval_hands_device results")
         with self._dev():
             mj_eval_hands(self._h, n, dq, dr)
 
