@@ -35,6 +35,7 @@ extern "C" {
 #define MJ_E_HIP        -2   /* a HIP call or kernel launch failed */
 #define MJ_E_NOMEM      -3   /* host allocation of the handle failed */
 #define MJ_E_UNSUPPORTED -4  /* the device cannot run the kernels (LDS too small) */
+#define MJ_E_RANGE      -5   /* a size beyond the stated maximum of the entry point */
 
 /* rule flags (section 3.2, "Rules") */
 #define MJ_F_RED      1u     /* red fives: tile ids 16, 52, 88 */
@@ -264,6 +265,19 @@ int mj_import(MjHandle *h, int64_t env_lo, int64_t n, const MjEnvCanon *d_in, vo
 /* hand-evaluation micro-batch: value of n hands (best interpretation under
  * the order points, han, fu, yaku mask).  Needs only the tables of `h`. */
 int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandResult *d_out, void *stream);
+
+/* The same evaluation for callers that can not allocate and hold no handle: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The tables the kernel reads (the per-suit pattern table, about
+ * 200 KB) live in a device array that is part of the library image, one copy per GPU, kept until the process
+ * ends; no workspace argument, no handle.  The call allocates nothing: no hipMalloc, no hipFree, no allocating
+ * library routine.  d_in / d_out as for mj_eval_hands (device memory, 16- and 8-byte aligned), n at most
+ * MJ_EVAL_STATIC_MAX_HANDS (MJ_E_RANGE beyond it; the tables do not grow with n, the limit is that of one launch).
+ * The tables of a GPU are uploaded by the first mj_init on that GPU; if none has run there, the first call of this
+ * entry point uploads them itself with one synchronous copy (so THAT call must not sit inside a graph capture).
+ * The kernel only reads the array, so calls on one GPU may overlap each other; they must not overlap that first
+ * upload. */
+#define MJ_EVAL_STATIC_MAX_HANDS ((int64_t)1 << 24)
+int mj_eval_hands_static(int64_t n, const MjHandQuery *d_in, MjHandResult *d_out, void *stream);
 
 /* scripting / test aid: env b receives the 136 tile ids at d_wall (a
  * permutation of 0..135, not checked) as its wall and the current kyoku is

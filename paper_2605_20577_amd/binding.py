@@ -81,6 +81,7 @@ EXPORTS = {
     "mj_export": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "mj_import": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "mj_eval_hands": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mj_eval_hands_static": (C.c_int, [C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "mj_deal_from_wall": (C.c_int, [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
     "mj_step_count": (C.c_uint64, [C.c_void_p]),
     "mj_set_step_count": (C.c_int, [C.c_void_p, C.c_uint64]),
@@ -215,6 +216,10 @@ def mj_import(h, env_lo, n, src):
 
 def mj_eval_hands(h, n, queries, results):
     _check(lib().mj_eval_hands(h, n, _ptr(queries), _ptr(results), _stream()))
+
+
+def mj_eval_hands_static(n, queries, results):
+    _check(lib().mj_eval_hands_static(n, _ptr(queries), _ptr(results), _stream()))
 
 
 def mj_deal_from_wall(h, b, wall):

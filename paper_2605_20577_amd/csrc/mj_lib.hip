@@ -15,7 +15,9 @@
 #include <cstddef>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "../../include/mj.h"
 #include "mj_canon.hpp"
@@ -863,6 +865,52 @@ inline int pick_lpw(int64_t B)
   } while (0)
 inline int check(hipError_t e) { return e == hipSuccess ? MJ_OK : MJ_E_HIP; }
 
+// ---- tables for callers that can not allocate (mj_eval_hands_static) ----------------------------------------
+// A copy of the per-suit pattern tables (probe part and records, without the shanten block tables) in a file-scope
+// device array: every GPU the library runs on holds its own copy at its own address until the process ends.  In
+// host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr size_t kStaticScratchBytes = 224 * 1024;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 16;
+struct StaticTables { bool ready; DevTables T; };
+StaticTables g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+// the tables of the CURRENT device, uploaded on first use (a synchronous copy from a host image)
+int static_tables(const DevTables **out)
+{
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MJ_E_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return MJ_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  StaticTables &st = g_static[dev];
+  if (!st.ready) {
+    const mjt::SuitTables &t = tables();
+    const ScratchLayout sl = scratch_layout();
+    const size_t need = sl.sh_suit;                       // everything before the shanten tables
+    if (need > kStaticScratchBytes || (sl.probe_bytes & 15)) return MJ_E_UNSUPPORTED;
+    uint8_t *ptr = nullptr;
+    if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MJ_E_HIP;
+    std::vector<uint8_t> img(need, 0);
+    std::memcpy(img.data() + sl.probe, t.rowid.data(), t.rowid.size());
+    std::memcpy(img.data() + sl.probe + t.rowid.size(), t.bitmap.data(), t.bitmap.size() * 4);
+    std::memcpy(img.data() + sl.base, t.base.data(), t.base.size() * 2);
+    std::memcpy(img.data() + sl.rowrank, t.rowrank.data(), t.rowrank.size() * 2);
+    std::memcpy(img.data() + sl.keyinfo, t.keyinfo.data(), t.keyinfo.size() * 4);
+    std::memcpy(img.data() + sl.recs, t.recs.data(), t.recs.size() * 4);
+    if (hipMemcpy(ptr, img.data(), need, hipMemcpyHostToDevice) != hipSuccess) return MJ_E_HIP;
+    st.T.probe = ptr + sl.probe;
+    st.T.base = (const uint16_t *)(ptr + sl.base);
+    st.T.rowrank = (const uint16_t *)(ptr + sl.rowrank);
+    st.T.keyinfo = (const uint32_t *)(ptr + sl.keyinfo);
+    st.T.recs = (const uint32_t *)(ptr + sl.recs);
+    st.T.probe_bytes = (int)sl.probe_bytes;
+    st.ready = true;
+  }
+  *out = &st.T;
+  return MJ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -875,6 +923,7 @@ const char *mj_strerror(int code)
     case MJ_E_HIP: return "HIP call or kernel launch failed";
     case MJ_E_NOMEM: return "host allocation failed";
     case MJ_E_UNSUPPORTED: return "device cannot run the kernels";
+    case MJ_E_RANGE: return "size beyond the entry point's stated maximum";
     default: return "unknown error";
   }
 }
@@ -934,6 +983,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   h->sh_suit = (const uint32_t *)(sc + sl.sh_suit);
   h->sh_honor = (const uint32_t *)(sc + sl.sh_honor);
   h->obs_ctr = (unsigned *)(sc + sl.counters);
+  if (rc == MJ_OK) { const DevTables *unused; rc = static_tables(&unused); }   // for mj_eval_hands_static on this device
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[0]));
   if (rc == MJ_OK) rc = check(hipEventCreate(&h->ev[1]));
   if (rc != MJ_OK) { delete h; return rc; }
@@ -1093,6 +1143,18 @@ int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandR
   if (n == 0) return MJ_OK;                               // an empty batch needs no buffers
   if (!d_in || !d_out || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 7)) return MJ_E_ARG;
   k_eval_hands<<<blocks_for(n), kAuxBlock, h->probe_bytes, (hipStream_t)stream>>>(h->T, n, d_in, d_out);
+  return check(hipGetLastError());
+}
+
+int mj_eval_hands_static(int64_t n, const MjHandQuery *d_in, MjHandResult *d_out, void *stream)
+{
+  if (n < 0 || n > MJ_EVAL_STATIC_MAX_HANDS) return MJ_E_RANGE;
+  if (n == 0) return MJ_OK;
+  if (!d_in || !d_out || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 7)) return MJ_E_ARG;
+  const DevTables *T = nullptr;
+  int rc = static_tables(&T);          // ready since mj_init on this device, otherwise uploaded now
+  if (rc != MJ_OK) return rc;
+  k_eval_hands<<<blocks_for(n), kAuxBlock, T->probe_bytes, (hipStream_t)stream>>>(*T, n, d_in, d_out);
   return check(hipGetLastError());
 }
 
