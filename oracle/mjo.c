@@ -16,6 +16,7 @@
  */
 #include "mjo.h"
 #include <stdlib.h>
+#include <assert.h>
 #include <string.h>
 
 typedef MjoEnv E;
@@ -1070,6 +1071,10 @@ static void discard(MjoHandle *h, int64_t b, int s, int k, int red)
   turn_pending_indicators(e);
   e->hand[s][k]--;
   if (red) e->hand_red[s] &= (uint8_t)~(1 << (k / 9));
+  /* A seat never discards more than 30 times in a kyoku: between two discards of one seat the turn goes once round the
+   * table (4 seats); a live draw moves it by one seat, a claim by at most three; there are at most 70 live draws and
+   * 16 claims (4 melds per seat), so 4 (n - 1) <= 70 + 3 * 16 gives n <= 30.  The 32 entries are enough. */
+  assert(e->n_river[s] < 32);
   e->river[s][e->n_river[s]++] = (uint8_t)(k | red << 6);
   e->discarded_kinds[s] |= 1ull << k;
   e->furiten_temp[s] = 0;

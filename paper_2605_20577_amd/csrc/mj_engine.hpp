@@ -7,6 +7,7 @@
 // simultaneous responses, wall geography, tie-breaks) are this library's and
 // are listed in the design document.
 #pragma once
+#include <cassert>
 #include "mj_core.hpp"
 
 namespace mj {
@@ -16,6 +17,13 @@ namespace mj {
 #define MJ_TICK(c, i) do { long long now_ = clock64(); (c).t[i] += now_ - (c).t0; (c).t0 = now_; } while (0)
 #else
 #define MJ_TICK(c, i) ((void)0)
+#endif
+
+// checked in the host build of this code (tests, sanitizers), nothing on the device
+#ifdef __HIP_DEVICE_COMPILE__
+#define MJ_HOST_ASSERT(x) ((void)0)
+#else
+#define MJ_HOST_ASSERT(x) assert(x)
 #endif
 
 // pins a per-lane value in a vector register at this point (otherwise the compiler turns bit tests of it back into
@@ -680,6 +688,8 @@ MJ_HD uint32_t apply_discard(Ctx &c, int s, int k, int red, bool &was_riichi)
   was_riichi = sw_get(sw, SW_RIICHI, 2) != 0;
   if (red) sw &= ~(1u << (k / 9));
   int nr = (int)sw_get(sw, SW_NRIVER, 6);
+  // at most 30 discards per seat and kyoku (4 (n - 1) <= 70 live draws + 3 seats x 16 claims), so 32 entries suffice
+  MJ_HOST_ASSERT(nr < 32);
   RIVER(c, s, nr) = (uint8_t)(k | red << 6);
   sw = sw_set(sw, SW_NRIVER, 6, nr + 1);
   sw &= ~(1u << SW_FTEMP);

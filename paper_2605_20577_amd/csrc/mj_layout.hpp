@@ -1,7 +1,8 @@
 // Structure-of-arrays layout of the environment state in HBM.
 //
-// For B environments every field is an array over b, so the 64 lanes of a
-// wavefront (64 consecutive environments) touch consecutive addresses.
+// For B environments every field is an array over b, so the lanes of a
+// wavefront (16, 32 or 64 consecutive environments, see mj_lib.hip) touch
+// consecutive addresses.
 // Sections, in this order, each array of length B:
 //   u64 hot : discarded_kinds[4] waits[4] mask[8] meld[4] tenpai_discards   (21 arrays)
 //   u64 cold: yaku[4] result[4] next_waits[4]                               (12 arrays)

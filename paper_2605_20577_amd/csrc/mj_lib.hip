@@ -1,15 +1,15 @@
 // libmj: HIP kernels (gfx950) and the C ABI of include/mj.h.
 //
-// Step kernels map one lane to one environment (64 consecutive environments
-// per wavefront, structure-of-arrays state, see mj_layout.hpp).  A block of
-// 128 lanes stages into LDS: the probe part of the per-suit pattern table
-// (11 KB), the hot state arrays of its 128 environments (35 KB) and a small
-// per-wave slot for dealing; it runs its steps there and writes the hot
-// arrays back.  The rare heavy step, the wall shuffle, is done by the whole
-// wavefront for one environment at a time (ballot over the lanes that need a
-// deal, 34 lanes run Philox, one lane applies the swaps in LDS).  The
-// observation writer builds bit planes per environment and then streams bytes
-// with all lanes.
+// Step kernels (k_rollout, k_step, k_new_games) map one lane to one environment, with LPW = 16 or 32 (or 64)
+// environments per wavefront and the remaining lanes idle: the step is bound by instruction issue along divergent
+// paths, so narrower wavefronts and two of them per SIMD run faster than full ones.  A block of 128 lanes (two
+// wavefronts) stages into LDS the probe part of the per-suit pattern table (11 KB), the hot state arrays of its
+// environments (288 B each, structure of arrays, see mj_layout.hpp) and a 136-byte shuffle column per environment;
+// it runs its steps there and writes the hot arrays back.  Walls are shuffled ahead of time, every lane for itself
+// on its LDS column; a deal that finds no wall ready is done by the whole wavefront for one environment at a time
+// (ballot over the lanes that need it, 34 lanes run Philox, the wall sits in one vector register and the swaps are
+// readlane / select pairs).  The observation writers build bit planes / token records per environment in LDS and
+// then stream them out with all lanes, 16 bytes per lane.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 #include <cstddef>

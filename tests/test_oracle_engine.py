@@ -162,3 +162,40 @@ def test_observation_planes():
             assert P[53][:18].sum() == int(e["live_left"][b]) // 4
             ind = np.bincount(e["wall"][b][126:126 + e["n_dora"][b]] >> 2, minlength=34)
             assert (P[37:41].sum(0) == ind).all()
+
+
+def test_river_capacity_under_claims_that_feed_one_seat():
+    """A river holds at most 32 tiles (oracle and kernels assert it).  A seat never discards more than 30 times in a
+    kyoku: between two of its discards the turn goes once round the table, a live draw moves it by one seat and a
+    claim by at most three, and there are at most 70 live draws and 16 claims, so 4 (n - 1) <= 70 + 48.  Here every
+    seat plays to bring the turn back to seat 0 (the dealer) as often as the tiles allow: nobody wins, declares or
+    makes a kan, seat 0 claims whatever it can, the seat before it claims seat 0's discards, the others claim only
+    when that skips seats on the way to seat 0.  The longest river stays inside the bound (and well above the 18 to
+    19 discards of a kyoku without claims, so the scenario does what it is meant to)."""
+    B = 192
+    o = mjo.Oracle(B, seed=3, flags=mjo.RULES_NORED, mode=mjo.MODE_SINGLE)
+    longest = 0
+    for _ in range(400):
+        e = o.export()
+        if e["terminated"].all():
+            break
+        m = o.legal_mask()
+        a = np.full((B, 4), -1, dtype=np.int8)
+        for b in range(B):
+            if e["terminated"][b]:
+                continue
+            d = int(e["last_discarder"][b])
+            for s in range(4):
+                if not int(e["actor_mask"][b]) >> s & 1:
+                    continue
+                legal = [x for x in range(85) if int(m[b, s, x >> 6]) >> (x & 63) & 1]
+                if e["phase"][b] == 0:
+                    a[b, s] = [x for x in legal if x < 37][-1]          # a discard, never a declaration
+                    continue
+                claims = [x for x in legal if 75 <= x <= 83 and x != 77]
+                # seats passed over on the way from the discarder to seat 0 if s takes the tile
+                helps = s == 0 or (d == 0 and s == 3) or (s == 3 and d == 1) or (s == 2 and d == 0)
+                a[b, s] = claims[0] if claims and helps else 84
+        o.step(a)
+        longest = max(longest, int(o.export()["n_river"].max()))
+    assert 22 <= longest <= 30, longest
