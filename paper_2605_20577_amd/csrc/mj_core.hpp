@@ -25,6 +25,37 @@
 #ifndef MJ_STAT
 #define MJ_STAT(x) ((void)0)
 #endif
+// -DMJ_PROFILE (never in the shipped library): wave-level region timers of the step kernels.  MJ_RB notes which
+// lanes need a region and the time; MJ_RE adds, once per wavefront, the cycles spent in it, one entry and the
+// number of lanes that needed it to three counters per region in LDS, which k_rollout prints for one block.
+#if defined(MJ_PROFILE) && defined(__HIPCC__)
+enum { PR_LOOP, PR_REFILL, PR_SAMPLE, PR_STEP, PR_RESET, PR_DEAL, PR_DEAL_NEXT, PR_DEAL_WAVE, PR_FINISH,
+       PR_S0, PR_S1_TURN, PR_DISCARD, PR_KAN, PR_DECL, PR_S1_RESP, PR_CALL, PR_S2, PR_W_SHORT, PR_W_FACTS, PR_W_REFRESH,
+       PR_WF_CAND, PR_WF_SPECIAL, PR_S3, PR_S3_RON, PR_WIN, PR_ABORT, PR_EXH, PR_DRAW, PR_KANDRAW,
+       PR_TM_FACTS, PR_TM_EXACT, PR_TP_STD, PR_TP_OWN, PR_TP_SPECIAL, PR_TM_TSUMO, PR_TM_RIICHI, PR_TM_BITS, PR_EVAL, PR_N };
+__shared__ unsigned long long mj_prof[3 * PR_N];
+#endif
+#if defined(MJ_PROFILE) && defined(__HIP_DEVICE_COMPILE__)
+#define MJ_RB(name, cond) const unsigned long long rbm_##name = __ballot((cond) ? 1 : 0); const long long rbt_##name = clock64()
+#define MJ_RE(name, idx)                                                                                   \
+  do {                                                                                                     \
+    if (rbm_##name) {                                                                                      \
+      const unsigned long long act_ = __ballot(1);                                                         \
+      if ((int)(threadIdx.x & 63) == __ffsll((long long)act_) - 1) {                                       \
+        atomicAdd(&mj_prof[3 * (idx)], (unsigned long long)(clock64() - rbt_##name));                      \
+        atomicAdd(&mj_prof[3 * (idx) + 1], 1ull);                                                          \
+        atomicAdd(&mj_prof[3 * (idx) + 2], (unsigned long long)__popcll(rbm_##name));                      \
+      }                                                                                                    \
+    }                                                                                                      \
+  } while (0)
+#elif defined(MJ_MARKS) && defined(__HIP_DEVICE_COMPILE__)
+// -DMJ_MARKS (never in the shipped library): the same region boundaries as comments in the generated assembly
+#define MJ_RB(name, cond) asm volatile("; MJMARK B " #name)
+#define MJ_RE(name, idx) asm volatile("; MJMARK E " #name)
+#else
+#define MJ_RB(name, cond) ((void)0)
+#define MJ_RE(name, idx) ((void)0)
+#endif
 // Everything is force-inlined: the kernels contain no function calls.  Out-of-line device functions (tried for
 // the hand evaluator and the waits search) gave wrong results on the GPU on rare paths while the same source was
 // right on the host, and each call site cost a few hundred instructions of register save and restore.  The big
@@ -411,14 +442,18 @@ MJ_HD uint64_t waits_from_facts(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_
   // suits with remainder 2; every other suit must already be valid.  With remainder pattern (1,0,0,0) the
   // remainder-1 suit is the only "bad" one allowed; with (2,2,0,0) either no suit is bad (both are candidates)
   // or one of the two is (then it must take the tile).
+  MJ_RB(wfc, ((r1 == 1 && r2 == 0) || (r1 == 0 && r2 == 2)) && (bad & (bad - 1)) == 0);
   if (((r1 == 1 && r2 == 0) || (r1 == 0 && r2 == 2)) && (bad & (bad - 1)) == 0) {
     uint32_t cands = bad ? (bad & nonzero) : nonzero;
     while (cands) {
+      MJ_STAT(n_waits_cand);
       const int s = __builtin_ctz(cands);
       cands &= cands - 1;
       w |= (uint64_t)suit_addmask(Lp, s, pick4(h0, h1, h2, h3, s)) << (9 * s);
     }
   }
+  MJ_RE(wfc, PR_WF_CAND);
+  MJ_RB(wfs, n_meld == 0 && (kinds_held_twice(h) == 6 || few_simples(h, 0)));
   if (n_meld == 0 && (kinds_held_twice(h) == 6 || few_simples(h, 0))) {
     SpecialCounts c = special_counts(h);
     if (c.c2 == 6 && c.c1 == 1 && c.c3 == 0 && c.c4 == 0) w |= kinds_where(h, 1);      // seven pairs
@@ -427,6 +462,7 @@ MJ_HD uint64_t waits_from_facts(const Lut *Lp, uint32_t h0, uint32_t h1, uint32_
       else if (c.c1 == 11 && c.c2 == 1) w |= K_YAOCHU & ~(kinds_where(h, 1) | kinds_where(h, 2));
     }
   }
+  MJ_RE(wfs, PR_WF_SPECIAL);
   if (w) w &= ~own4_mask(h, meldw, n_meld);
   return w | (uint64_t)facts << FACTS_SHIFT | W_FACTS_VALID;
 }
@@ -462,6 +498,8 @@ MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h
   const bool special = n_meld == 0 && (kinds_held_twice(h) >= 6 || few_simples(h, 1));
   const bool standard = popc32(~valid & 15u) <= 2;      // a discard and a draw touch at most two suits
   if (!exact) return (standard || special) ? TD_UNKNOWN : 0;
+  if (standard) MJ_STAT(n_tp_standard);
+  MJ_RB(tps, standard);
   if (standard) {                       // rare: the search proper
     const SuitFacts f0 = suit_facts<true>(L, h0), f1 = suit_facts<true>(L, h1), f2 = suit_facts<true>(L, h2);
     const uint64_t full = own4_mask(h, meldw, n_meld);
@@ -501,7 +539,9 @@ MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h
         own_suit |= (uint64_t)squeeze9(fields_nonzero(h[s1])) << (9 * s1);
     }
     own_suit &= ~out;
+    MJ_RB(tpo, own_suit != 0);
     while (own_suit) {
+      MJ_STAT(n_tp_own);
       const int k = ctz64(own_suit);
       own_suit &= own_suit - 1;
       const int su = suit_of(k), r = rank_of(k, su);
@@ -509,7 +549,10 @@ MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h
       const uint32_t blocked = (uint32_t)(full >> (9 * su) & 0x1FF) & ~(1u << r);     // the discarded kind is owned one less
       if (suit_addmask(Lp, su, g) & ~blocked) out |= kbit(k);
     }
+    MJ_RE(tpo, PR_TP_OWN);
   }
+  MJ_RE(tps, PR_TP_STD);
+  MJ_RB(tpx, special);
   if (special) {
     // seven pairs and thirteen orphans in closed form: the counts of singles, pairs, triplets after the discard
     const SpecialCounts c = special_counts(h);
@@ -528,6 +571,7 @@ MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h
       }
     }
   }
+  MJ_RE(tpx, PR_TP_SPECIAL);
   return out;
 }
 
@@ -735,6 +779,7 @@ MJ_HD void add_record(Decomp &d, uint32_t rec, int su)
 // value of one decomposition under one way of waiting
 MJ_HD void eval_placed(EvalCtx &c, const Decomp &d, uint64_t trip_c, uint64_t trip_o, int wait_fu, bool two_sided)
 {
+  MJ_STAT(n_placed);
   uint64_t y = c.colour_y, ym = c.colour_ym;
   uint32_t run[3] = {d.crun[0] + d.orun[0], d.crun[1] + d.orun[1], d.crun[2] + d.orun[2]};
   int n_run = tiles_in(run[0]) + tiles_in(run[1]) + tiles_in(run[2]);
@@ -860,6 +905,7 @@ MJ_HD void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
   bool kokushi = n_meld == 0 && (present & ~K_YAOCHU) == 0 && popc64(present) == 13 && pairs == 1 && other == 0;
   if (!std_ok && !chiitoi && !kokushi) return;
   out.shape_ok = 1;
+  MJ_STAT(n_eval_shape);
 
   // context shared by every interpretation
   EvalCtx c;
@@ -943,6 +989,7 @@ MJ_HD void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
     for (int i0 = 0; i0 < nd[0]; i0++)
       for (int i1 = 0; i1 < nd[1]; i1++)
         for (int i2 = 0; i2 < nd[2]; i2++) {
+          MJ_STAT(n_decomp);
           Decomp d = base;
           add_record(d, L.recs[idx[0] + i0], 0);
           add_record(d, L.recs[idx[1] + i1], 1);

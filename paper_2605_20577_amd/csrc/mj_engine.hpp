@@ -12,13 +12,6 @@
 
 namespace mj {
 
-// -DMJ_PROFILE: cycles per stage, accumulated per lane, printed by k_rollout (never in the shipped library)
-#ifdef MJ_PROFILE
-#define MJ_TICK(c, i) do { long long now_ = clock64(); (c).t[i] += now_ - (c).t0; (c).t0 = now_; } while (0)
-#else
-#define MJ_TICK(c, i) ((void)0)
-#endif
-
 // checked in the host build of this code (tests, sanitizers), nothing on the device
 #ifdef __HIP_DEVICE_COMPILE__
 #define MJ_HOST_ASSERT(x) ((void)0)
@@ -44,9 +37,6 @@ struct Ctx {
   bool need_turn;      // the seat to move still needs its legal mask (step_finish)
   uint32_t live_word;  // the wall word that holds the next live tile, loaded at the start of the step ...
   int live_ptr;        // ... for this draw pointer (-1: nothing loaded)
-#ifdef MJ_PROFILE
-  long long t[16], t0;  // cycle counters per stage (profiling builds only)
-#endif
 };
 
 // ------------------------------------------------------------- field access
@@ -149,7 +139,9 @@ MJ_HD void eval_seat(Ctx &c, int s, int w, bool tsumo, bool chankan, HandOut &ou
   if (chankan && code_red(c.g.kakan_tile)) aka++;
   q.n_aka = aka;
   q.kuitan = (c.R.flags & F_KUITAN) ? 1 : 0;
+  MJ_RB(ev, true);
   eval_hand(&c.L, q, out);
+  MJ_RE(ev, PR_EVAL);
 }
 
 MJ_HD bool furiten(Ctx &c, int s)
@@ -202,7 +194,6 @@ MJ_HD void turn_mask(Ctx &c)
   const uint32_t h[4] = {HW(c, s, 0), HW(c, s, 1), HW(c, s, 2), HW(c, s, 3)};
   const uint64_t mw = MELDW(c, s), wfull = WAITS(c, s), waits = wfull & K_ALL;
   const int riichi = (int)sw_get(sw, SW_RIICHI, 2), n_meld = (int)sw_get(sw, SW_NMELD, 3);
-  MJ_TICK(c, 11);
 
   // Discards that keep the hand tenpai: needed for the riichi declaration and the discard that follows it, and
   // kept for the next step, where the discard then tells whether the seat's waits are empty without a search.
@@ -214,22 +205,30 @@ MJ_HD void turn_mask(Ctx &c)
   // call took (all of the called tile's suit): one probe brings the facts up to date.
   const int changed = drawn_k >= 0 ? drawn_k : (c.g.kuikae0 != 255 ? (int)c.g.kuikae0 : -1);
   uint32_t facts;
+  MJ_RB(tmf, true);
   if ((wfull & W_FACTS_VALID) && changed >= 0) {
     const int cs = suit_of(changed);
     facts = facts_update(c.L, (uint32_t)(wfull >> FACTS_SHIFT) & 0xFFFu, cs, pick4(h[0], h[1], h[2], h[3], cs));
   } else facts = hand_facts(c.L, h);
   const bool exact = !riichi && (may_riichi || c.g.riichi_pending);        // the set itself is only searched for when
   uint64_t td = 0;                                                         // the mask needs it
+  MJ_RE(tmf, PR_TM_FACTS);
+  MJ_RB(tme, exact);
+  if (exact) MJ_STAT(n_exact);
   if (exact) td = tenpai_discards_from_facts(&c.L, h[0], h[1], h[2], h[3], mw, n_meld, true, facts);
   TD(c) = (exact || riichi ? td | TD_VALID : 0) | (uint64_t)facts << FACTS_SHIFT | TD_FACTS;
-  MJ_TICK(c, 14);
+  MJ_RE(tme, PR_TM_EXACT);
+  MJ_RB(tmt, !c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1));
   if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
+    MJ_STAT(n_tsumo_eval);
     HandOut r;
     eval_seat(c, s, drawn_k, true, false, r);
     if (r.yaku_ok) set_action(m, A_TSUMO);
   }
-  MJ_TICK(c, 12);
+  MJ_RE(tmt, PR_TM_TSUMO);
   const bool kan_ok = !c.g.riichi_pending && drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
+  MJ_RB(tmr, riichi != 0);
+  MJ_RB(tmb, riichi == 0);
   if (riichi) {
     if (code_red(c.g.drawn)) set_action(m, A_DISCARD_RED + drawn_k / 9);
     else set_action(m, A_DISCARD + drawn_k);
@@ -270,8 +269,9 @@ MJ_HD void turn_mask(Ctx &c)
         if (popc64(present & K_YAOCHU) >= 9) set_action(m, A_KYUUSHU);
       }
     }
-    MJ_TICK(c, 13);
   }
+  MJ_RE(tmr, PR_TM_RIICHI);
+  MJ_RE(tmb, PR_TM_BITS);
   MASK(c, s, 0) = m.w0;
   MASK(c, s, 1) = m.w1;
 }
@@ -619,6 +619,7 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   if (!(WAITS(c, o) >> k & 1)) return false;
   bool ok = false;
   if (!furiten(c, o)) {
+    MJ_STAT(n_ron_eval);
     HandOut r;
     eval_seat(c, o, k, false, chankan, r);
     ok = r.yaku_ok;
@@ -835,6 +836,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   c.g.illegal_seat = 255;
   c.live_ptr = -1;
   if (c.g.terminated) return;
+  MJ_RB(s0, true);
   // the next live tile is needed at the end of most steps: start its load now
   if (c.g.draw_ptr <= 121) {
     c.live_word = c.e.wallw[(int64_t)(c.g.wall_sel * 34 + (c.g.draw_ptr >> 2)) * c.e.n];
@@ -866,7 +868,6 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
     clear_masks(c);
     return;
   }
-  MJ_TICK(c, 1);
   // stage 1: apply
   int waits_seat = -1, waits_k = -1, win_mask = 0, win_loser = -1, win_tile = 0, end_abort = 0;
   // what the later stages have to do, as bits of one per-lane word (six separate booleans would each live in a
@@ -874,9 +875,15 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   enum : uint32_t { DO_RESPOND = 1, DO_ROB = 2, DO_ADVANCE = 4, DO_KANFIN = 8, WIN_TSUMO = 16, WIN_ROB = 32, KAN_CONCEALED = 64 };
   uint32_t todo = 0;
   uint32_t discard_hw = 0;           // the discarder's hand word of the discarded tile's suit, after the discard
+  MJ_RE(s0, PR_S0);
+  MJ_RB(s1t, c.g.phase == PH_TURN);
+  MJ_RB(s1r, c.g.phase != PH_TURN);
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
     hist_push(c, s, act);
+    MJ_RB(dis, act < A_KAN);
+    MJ_RB(kan, act >= A_KAN && act < A_RIICHI);
+    MJ_RB(dcl, act >= A_RIICHI);
     if (act < A_KAN) {
       const int k = act < A_DISCARD_RED ? act : 4 + 9 * (act - A_DISCARD_RED);
       // a seat in riichi gives back the drawn tile: its waits stay; any other seat's waits follow from the discard
@@ -899,6 +906,9 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
     } else if (act == A_TSUMO) {
       win_mask = 1 << s; todo |= WIN_TSUMO; win_tile = code_kind(c.g.drawn);
     } else end_abort = 4;
+    MJ_RE(dis, PR_DISCARD);
+    MJ_RE(kan, PR_KAN);
+    MJ_RE(dcl, PR_DECL);
   } else {
     int ronners = 0;
     for (int s = 0; s < 4; s++) if ((actors >> s & 1) && act_of(acts, s) == A_RON) ronners |= 1 << s;
@@ -924,9 +934,11 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
         end_abort = settle_discard(c);
         if (!end_abort) {
           if (caller >= 0) hist_push(c, caller, call);
+          MJ_RB(cal, caller >= 0);
           if (caller < 0) todo |= DO_ADVANCE;
           else if (apply_call(c, caller, call)) { waits_seat = caller; todo |= DO_KANFIN; }
           else c.need_turn = true;
+          MJ_RE(cal, PR_CALL);
         }
       }
     } else {
@@ -934,26 +946,39 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
       else { mark_passed_ron(c, ron_offered); todo |= (c.g.kakan_tile & 0x80) ? (DO_KANFIN | KAN_CONCEALED) : DO_KANFIN; }
     }
   }
+  MJ_RE(s1t, PR_S1_TURN);
+  MJ_RE(s1r, PR_S1_RESP);
   clear_masks(c);
-  MJ_TICK(c, 2);
+  MJ_RB(s2, waits_seat >= 0);
   // stage 2: the seat whose concealed hand is back to 13 - 3 * melds tiles gets its waits refreshed
   if (waits_seat >= 0) {
+    MJ_STAT(n_waits_stage);
     const uint64_t td = TD(c);
     if (waits_k >= 0 && (td & TD_FACTS)) {
       // a discard: the facts of the 14-tile hand came with the turn's mask, the discard changed one suit; the set of
       // tenpai-keeping discards, when it was searched for, says at once whether any wait is left
       const int cs = suit_of(waits_k);
       const uint32_t facts = facts_update(c.L, (uint32_t)(td >> FACTS_SHIFT) & 0xFFFu, cs, discard_hw);
+      MJ_RB(wsh, (td & TD_VALID) && !(td >> waits_k & 1));
+      MJ_RB(wfa, !((td & TD_VALID) && !(td >> waits_k & 1)));
       if ((td & TD_VALID) && !(td >> waits_k & 1)) WAITS(c, waits_seat) = (uint64_t)facts << FACTS_SHIFT | W_FACTS_VALID;
       else
         WAITS(c, waits_seat) = waits_from_facts(&c.L, HW(c, waits_seat, 0), HW(c, waits_seat, 1), HW(c, waits_seat, 2),
                                                 HW(c, waits_seat, 3), MELDW(c, waits_seat), swf(c, waits_seat, SW_NMELD, 3), facts);
-    } else refresh_waits(c, waits_seat);
+      MJ_RE(wsh, PR_W_SHORT);
+      MJ_RE(wfa, PR_W_FACTS);
+    } else {
+      MJ_RB(wre, true);
+      refresh_waits(c, waits_seat);
+      MJ_RE(wre, PR_W_REFRESH);
+    }
   }
-  MJ_TICK(c, 3);
+  MJ_RE(s2, PR_S2);
   // stage 3: responses of the other seats
   MJ_KEEP_IN_VGPR(todo);
+  MJ_RB(s3, (todo & (DO_RESPOND | DO_ROB)) != 0);
   if (todo & (DO_RESPOND | DO_ROB)) {
+    MJ_STAT(n_respond_stage);
     const bool respond = todo & DO_RESPOND, rob = todo & DO_ROB;
     const int from = respond ? c.g.last_discarder : c.g.cur;
     const int code = respond ? c.g.last_discard : c.g.kakan_tile;
@@ -988,10 +1013,13 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
     }
     // ... and the wins: one evaluation site in a loop over the (rare) seats that wait on the tile, in turn order
     uint32_t ron = 0;
+    MJ_RB(s3r, hit != 0);
     for (int j = 1; j < 4 && hit; j++) {
+      MJ_STAT(n_ron_loop);
       const int o = (from + j) & 3;
       if ((hit >> o & 1) && ron_option(c, o, k, rob)) ron |= 1u << o;
     }
+    MJ_RE(s3r, PR_S3_RON);
     int any = 0;
 #pragma unroll
     for (int t = 0; t < 4; t++) {
@@ -1006,19 +1034,30 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
       if (!end_abort) todo |= DO_ADVANCE;
     } else todo |= DO_KANFIN;
   }
-  MJ_TICK(c, 4);
+  MJ_RE(s3, PR_S3);
   bool exhaust = false;
   MJ_KEEP_IN_VGPR(todo);
   if ((todo & DO_ADVANCE) && c.g.live_left == 0) { exhaust = true; todo &= ~DO_ADVANCE; }
   // stage 4: the kyoku ends
+  if (win_mask) MJ_STAT(n_win);
+  if (exhaust) MJ_STAT(n_exhaust);
+  MJ_RB(win, win_mask != 0);
+  MJ_RB(abo, !win_mask && end_abort);
+  MJ_RB(exh, !win_mask && !end_abort && exhaust);
   if (win_mask) win(c, win_mask, (todo & WIN_TSUMO) != 0, win_loser, win_tile, (todo & WIN_ROB) != 0);
   else if (end_abort) abortive_draw(c, end_abort);
   else if (exhaust) exhaustive_draw(c);
-  MJ_TICK(c, 5);
+  MJ_RE(win, PR_WIN);
+  MJ_RE(abo, PR_ABORT);
+  MJ_RE(exh, PR_EXH);
   // stage 5: draws
   MJ_KEEP_IN_VGPR(todo);
+  MJ_RB(drw, (todo & DO_ADVANCE) != 0);
   if (todo & DO_ADVANCE) { draw_live(c, (c.g.last_discarder + 1) & 3); c.need_turn = true; }
+  MJ_RE(drw, PR_DRAW);
+  MJ_RB(kdr, (todo & DO_KANFIN) != 0);
   if (todo & DO_KANFIN) { kan_draw(c, !(todo & KAN_CONCEALED)); c.need_turn = true; }
+  MJ_RE(kdr, PR_KANDRAW);
 }
 
 // uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)

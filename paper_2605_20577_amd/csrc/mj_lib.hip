@@ -303,8 +303,12 @@ __device__ __forceinline__ void deal_stage(Ctx &c, bool active, void *state, int
 {
   const bool need = active && c.need_deal;
   const bool ready = need && c.e.nserial[0] == c.e.serial[0];
+  MJ_RB(dn, ready);
   if (ready) deal_from_next(c);
+  MJ_RE(dn, PR_DEAL_NEXT);
+  MJ_RB(dw, need && !ready);
   deal_wave(c, need && !ready, state, B, b);
+  MJ_RE(dw, PR_DEAL_WAVE);
 }
 
 __device__ __forceinline__ void reset_env(Ctx &c, bool first)
@@ -439,38 +443,54 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
 #ifdef MJ_PROFILE
-  for (int i = 0; i < 16; i++) c.t[i] = 0;
-  c.t0 = clock64();
+  for (int i = threadIdx.x; i < 3 * PR_N; i += blockDim.x) mj_prof[i] = 0;
+  __syncthreads();
 #endif
   for (int t = 0; t < n_steps; t++) {
     uint32_t acts = 0;
+    MJ_RB(loop, true);
     // The stride of the cold arrays is made opaque once per step: otherwise every address "array + k * stride" is
     // computed before the loop and kept in a register pair for the whole launch (dozens of pairs, many of them
     // spilled to scratch memory and fetched back one by one on the rare paths that use them).
     { int64_t stride = c.e.n; asm volatile("" : "+s"(stride)); c.e.n = stride; }
     if (active) {
+      MJ_RB(rf, (step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1);
       if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
         refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
-      MJ_TICK(c, 10);
+      MJ_RE(rf, PR_REFILL);
       int ron_offered;
+      MJ_RB(sa, true);
       acts = sample_actors(c, step0 + t, ron_offered);
-      MJ_TICK(c, 0);
+      MJ_RE(sa, PR_SAMPLE);
+      MJ_RB(st, true);
       step_env(c, acts, ron_offered);
-      MJ_TICK(c, 6);
+      MJ_RE(st, PR_STEP);
+      MJ_RB(rs, auto_reset && c.g.terminated);
       if (auto_reset && c.g.terminated) reset_env(c, false);
+      MJ_RE(rs, PR_RESET);
     }
-    MJ_TICK(c, 7);
+    MJ_RB(dl, active && c.need_deal);
     deal_stage(c, active, state, B, b);
-    MJ_TICK(c, 8);
+    MJ_RE(dl, PR_DEAL);
+    MJ_RB(fin, active && c.need_turn);
     if (active) step_finish(c);
-    MJ_TICK(c, 9);
+    MJ_RE(fin, PR_FINISH);
+    MJ_RE(loop, PR_LOOP);
   }
 #ifdef MJ_PROFILE
-  if (blockIdx.x == 7 && threadIdx.x == 0 && n_steps >= 128)
-    printf("PROF/step: refill %lld sample %lld | check %lld apply %lld waits %lld respond %lld end %lld draw %lld | reset %lld deal %lld mask %lld (pre %lld tsumo %lld bits %lld riichi %lld)\n",
-           c.t[10] / n_steps, c.t[0] / n_steps, c.t[1] / n_steps, c.t[2] / n_steps, c.t[3] / n_steps, c.t[4] / n_steps, c.t[5] / n_steps,
-           c.t[6] / n_steps, c.t[7] / n_steps, c.t[8] / n_steps, c.t[9] / n_steps, c.t[11] / n_steps, c.t[12] / n_steps,
-           c.t[13] / n_steps, c.t[14] / n_steps);
+  __syncthreads();
+  if (blockIdx.x == 7 && threadIdx.x == 0 && n_steps >= 128) {
+    static const char *const nm[PR_N] = {"LOOP", "REFILL", "SAMPLE", "STEP", "RESET", "DEAL", "DEAL_NEXT", "DEAL_WAVE", "FINISH",
+      "S0", "S1_TURN", "DISCARD", "KAN", "DECL", "S1_RESP", "CALL", "S2", "W_SHORT", "W_FACTS", "W_REFRESH", "WF_CAND",
+      "WF_SPECIAL", "S3", "S3_RON", "WIN", "ABORT", "EXH", "DRAW", "KANDRAW", "TM_FACTS", "TM_EXACT", "TP_STD", "TP_OWN",
+      "TP_SPECIAL", "TM_TSUMO", "TM_RIICHI", "TM_BITS", "EVAL"};
+    // two wavefronts per block: cycles and entries are summed over both, so divide by 2 x steps for "per wave-step"
+    for (int i = 0; i < PR_N; i++)
+      printf("PROF %-10s cyc/wave-step %8.1f  entries/wave-step %6.3f  lanes/entry %5.2f  cyc/entry %8.1f\n", nm[i],
+             (double)mj_prof[3 * i] / (2.0 * n_steps), (double)mj_prof[3 * i + 1] / (2.0 * n_steps),
+             mj_prof[3 * i + 1] ? (double)mj_prof[3 * i + 2] / (double)mj_prof[3 * i + 1] : 0.0,
+             mj_prof[3 * i + 1] ? (double)mj_prof[3 * i] / (double)mj_prof[3 * i + 1] : 0.0);
+  }
 #endif
   if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
 }

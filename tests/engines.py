@@ -77,10 +77,10 @@ def diff_records(a, b, skip=("pad_",)):
     return out
 
 
-def oracle_rollout_sharded(B, seed, flags, mode, steps, shards=16):
+def oracle_rollout_sharded(B, seed, flags, mode, steps, shards=16, with_obs=True):
     """B oracle games stepped `steps` times with the random policy, as `shards` independent oracle instances over
     consecutive env-id ranges, one thread each (the C oracle keeps no global state and ctypes drops the GIL).
-    Returns the concatenated canonical records and observations."""
+    Returns the concatenated canonical records and observations (None without with_obs)."""
     from concurrent.futures import ThreadPoolExecutor
     from oracle import mjo
     bounds = [B * i // shards for i in range(shards + 1)]
@@ -89,9 +89,9 @@ def oracle_rollout_sharded(B, seed, flags, mode, steps, shards=16):
         lo, hi = bounds[i], bounds[i + 1]
         o = mjo.Oracle(hi - lo, seed, flags, mode, env_id_base=lo)
         o.step_random(steps)
-        out = o.export().copy(), o.observe().copy()
+        out = o.export().copy(), (o.observe().copy() if with_obs else None)
         o.close()
         return out
     with ThreadPoolExecutor(shards) as ex:
         parts = list(ex.map(run, range(shards)))
-    return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+    return np.concatenate([p[0] for p in parts]), (np.concatenate([p[1] for p in parts]) if with_obs else None)

@@ -6,7 +6,9 @@
 // and so that it can be put under gdb or a sanitizer.  It is not part of the
 // product: the Python package never loads it, and nothing here is reachable
 // from libmj.so.
+#ifndef MJ_HD
 #define MJ_HD inline __attribute__((always_inline))
+#endif
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>

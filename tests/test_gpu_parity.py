@@ -183,6 +183,26 @@ def test_full_size_sampled_envs():
         g.close()
 
 
+@pytest.mark.parametrize("flags", [mjo.RULES_NORED, mjo.RULES_RED])
+def test_full_size_every_game(flags):
+    """B = 65,536 hanchan games in the benchmark's launch shape (both rule sets of the benchmark): 1,000 fused steps,
+    then 200 steps through the step-at-a-time entry points (sample, step, reset) at the same size; EVERY game's
+    record against the oracle, which runs the same 1,200 steps as sixteen shards on the host cores"""
+    from tests.engines import oracle_rollout_sharded
+    B, fused, unfused = 65536, 1000, 200
+    g = GpuEngine(B, seed=0, flags=flags, mode=mjo.MODE_HALF)
+    g.step_random(fused)
+    a = g.env.sample_random()
+    for _ in range(unfused):
+        g.env.sample_random(a); g.env.step(a); g.env.reset_done()
+    eo, _ = oracle_rollout_sharded(B, 0, flags, mjo.MODE_HALF, fused + unfused, with_obs=False)
+    eg = g.export()
+    d = diff_records(eo, eg)
+    assert not d, d[:4]
+    assert eg["episode"].max() >= 1 and eg["kyoku"].max() >= 6            # restarts and late kyoku were reached
+    g.close()
+
+
 def test_full_size_observation_workload():
     """B = 2^20, red rules, the observation written after every step (the large configuration of the benchmark, in
     its launch shape): sampled environments recomputed one by one by the oracle -- record, plane observation, token
@@ -215,11 +235,16 @@ def test_full_size_observation_workload():
     assert np.array_equal(hand_tiles, expect)
     # the fused path over the same batch: one launch, sixteen times what the machine holds at once
     g.step_random(300)
+    # ... and both observations again, now that rivers and melds have filled up
+    g.env.observe(obs)
+    tok = g.env.observe_tokens(tok)
     for b in ids[::3]:
         o = mjo.Oracle(1, 3, mjo.RULES_RED, mjo.MODE_HALF, env_id_base=b)
         o.step_random(steps + 300)
         d = diff_records(o.export(), g.export(b, 1))
         assert not d, (b, d[:4])
+        assert np.array_equal(o.observe()[0], obs[b].cpu().numpy()), b
+        assert o.observe_tokens()[0].tobytes() == tok[b].cpu().numpy().tobytes(), b
     g.close()
 
 
@@ -389,3 +414,22 @@ def test_token_observation(B, flags, mode):
         shanten_seen |= set(np.unique(want["shanten"]).tolist())
     if B >= 3000:
         assert {-1, 0, 1, 2, 3, 4, 5} <= shanten_seen
+
+
+def test_binding_refuses_tensors_the_kernels_could_not_index():
+    """a caller's tensor of the wrong size, dtype or device is refused on the host, before any launch"""
+    import torch
+    import paper_2605_20577_amd as mj
+    env = mj.MahjongEnv(100, seed=0)
+    with pytest.raises(mj.binding.MjError):
+        env.step(torch.zeros((99, 4), dtype=torch.int8, device="cuda:0"))
+    with pytest.raises(mj.binding.MjError):
+        env.observe(torch.empty((100, 4, 56, 33), dtype=torch.uint8, device="cuda:0"))
+    with pytest.raises(mj.binding.MjError):
+        env.legal_mask(torch.empty((100, 4, 2), dtype=torch.int32, device="cuda:0"))
+    with pytest.raises(mj.binding.MjError):
+        env.sample_random(torch.empty((100, 4), dtype=torch.int8))
+    with pytest.raises(mj.binding.MjError):
+        env.observe_tokens(torch.empty((100, 4, 496), dtype=torch.uint8, device="cuda:0")[:, :, ::2])
+    env.step(env.sample_random())                        # and the environment still works
+    env.close()
