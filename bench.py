@@ -212,8 +212,10 @@ def main():
         Bo = 1 << 20
         env = mj.MahjongEnv(Bo, seed=0, flags=mj.RULES_RED, mode=mj.MODE_HALF)
         obs = torch.empty((Bo, 4, 56, 34), dtype=torch.uint8, device="cuda:0")
+        if not args.no_preroll:
+            env.step_random(1024)
         dt, _ = timed_rollout(env, torch, 10, 30, obs)
-        print(json.dumps({"obs_B": Bo, "obs_env_steps_per_s": Bo * 30 / dt}))
+        print(json.dumps({"obs_B": Bo, "obs_env_steps_per_s": Bo * 30 / dt, "ms_per_step": dt / 30 * 1e3}))
         return
     if args.only_api:
         print(json.dumps(api_loops(mj, torch, B, 0 if args.no_preroll else PREROLL)))

@@ -268,7 +268,7 @@ int mj_eval_hands(const MjHandle *h, int64_t n, const MjHandQuery *d_in, MjHandR
 
 /* The same evaluation for callers that can not allocate and hold no handle: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  The tables the kernel reads (the per-suit pattern table, about
- * 200 KB) live in a device array that is part of the library image, one copy per GPU, kept until the process
+ * 370 KB) live in a device array that is part of the library image, one copy per GPU, kept until the process
  * ends; no workspace argument, no handle.  The call allocates nothing: no hipMalloc, no hipFree, no allocating
  * library routine.  d_in / d_out as for mj_eval_hands (device memory, 16- and 8-byte aligned), n at most
  * MJ_EVAL_STATIC_MAX_HANDS (MJ_E_RANGE beyond it; the tables do not grow with n, the limit is that of one launch).

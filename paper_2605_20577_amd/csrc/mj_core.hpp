@@ -100,8 +100,8 @@ struct Lut {
   const uint32_t *bitmap;    // [rows][20] valid suffixes of a row
   const uint16_t *base;      // [3125] keys before this prefix
   const uint16_t *rowrank;   // [rows][20] set bits before each word
-  const uint32_t *keyinfo;   // [keys] first record | count << 16
-  const uint32_t *recs;
+  const uint32_t *recs;      // [keys][4] the decompositions of a key, unused entries 0; the first one carries their number
+  const uint32_t *nb;        // [5^9] neighbours of every count pattern (global memory): valid | can take r | can lose r | ...
 };
 
 // One environment's view of the structure-of-arrays state.  "Hot" fields (touched by every step) live at
@@ -193,18 +193,30 @@ MJ_HD bool lut_valid(const Lut &L, uint32_t w)
   uint32_t row = L.rowid[prefix5(w)];
   return (L.bitmap[row * 20 + (s >> 5)] >> (s & 31)) & 1u;
 }
-// records of a suit word: count (0 = not valid) and the index of the first one
-MJ_HD int lut_records(const Lut &L, uint32_t w, uint32_t *first)
+// The decomposition records of the three numbered suits of a hand, every table read of one kind issued together:
+// the probe (two LDS reads per suit), the key's number (two small global reads per suit), the first record (one
+// global read per suit; it also says how many records the key has).  n[s] = number of records (0 = the suit is not
+// a valid pattern), rec0[s] = the first one, key[s] = where the others are (recs[4 key + i]): they are read only when
+// they are used, so that the usual hand with one decomposition per suit keeps few values alive.
+MJ_HD void lut_records3(const Lut &L, const uint32_t h[4], int n[3], uint32_t rec0[3], uint32_t key[3])
 {
-  uint32_t p = prefix5(w), s = suffix5(w);
-  uint32_t row = L.rowid[p];
-  uint32_t word = L.bitmap[row * 20 + (s >> 5)];
-  *first = 0;
-  if (!((word >> (s & 31)) & 1u)) return 0;
-  uint32_t key = (uint32_t)L.base[p] + L.rowrank[row * 20 + (s >> 5)] + (uint32_t)popc32(word & ((1u << (s & 31)) - 1u));
-  uint32_t info = L.keyinfo[key];
-  *first = info & 0xFFFFu;
-  return (int)(info >> 16);
+  uint32_t p[3], sfx[3], row[3], word[3];
+#pragma unroll
+  for (int s = 0; s < 3; s++) { p[s] = prefix5(h[s]); sfx[s] = suffix5(h[s]); row[s] = L.rowid[p[s]]; }
+#pragma unroll
+  for (int s = 0; s < 3; s++) word[s] = L.bitmap[row[s] * 20 + (sfx[s] >> 5)];
+#pragma unroll
+  for (int s = 0; s < 3; s++) {
+    const bool valid = (word[s] >> (sfx[s] & 31)) & 1u;
+    const uint32_t k = (uint32_t)L.base[p[s]] + L.rowrank[row[s] * 20 + (sfx[s] >> 5)] + (uint32_t)popc32(word[s] & ((1u << (sfx[s] & 31)) - 1u));
+    key[s] = valid ? k : 0u;
+    n[s] = valid ? 1 : 0;
+  }
+#pragma unroll
+  for (int s = 0; s < 3; s++) {
+    rec0[s] = L.recs[4 * (size_t)key[s]];
+    n[s] = n[s] ? 1 + (int)(rec0[s] >> 28 & 3u) : 0;
+  }
 }
 
 MJ_HD int tiles_in(uint32_t w)      // sum of the nine 3-bit fields
@@ -309,48 +321,9 @@ MJ_HD uint32_t honors_submask(uint32_t w)
   if (n1 == 0 && n4 == 1 && n2 <= 1) cand |= four;      // the four become a triplet
   return squeeze9(cand) & 0x7Fu;
 }
-// One numbered suit, every table probe issued together (rows first, then bitmap words: two LDS round trips in
-// all): is w valid, which ranks can take a tile (count < 4) so that it becomes valid, and -- WITH_SUB -- which
-// held ranks can lose a tile so that it is valid.
+// what the search for tenpai-keeping discards asks about one numbered suit: is it valid, which ranks can take a tile
+// (count < 4) so that it becomes valid, which held ranks can lose a tile so that it is valid
 struct SuitFacts { uint32_t valid, addm, subm; };
-template <bool WITH_SUB>
-MJ_HD SuitFacts suit_facts(const Lut &L, uint32_t w)
-{
-  const uint32_t p = prefix5(w), sfx = suffix5(w);
-  const uint32_t full = (w >> 2) & O111, present = fields_nonzero(w);
-  uint32_t rowa[5], rows[5];
-  const uint32_t rowp = L.rowid[p];
-  uint32_t pw = 1;
-#pragma unroll
-  for (int r = 0; r < 5; r++) {                            // a full / an empty field probes the key of w itself
-    rowa[r] = L.rowid[p + ((full >> (3 * r) & 1u) ? 0u : pw)];
-    rows[r] = WITH_SUB ? L.rowid[p - ((present >> (3 * r) & 1u) ? pw : 0u)] : 0u;
-    pw *= 5;
-  }
-  const uint32_t wi = sfx >> 5, bi = sfx & 31;
-  SuitFacts f;
-  f.valid = (L.bitmap[rowp * 20 + wi] >> bi) & 1u;
-  f.addm = 0; f.subm = 0;
-#pragma unroll
-  for (int r = 0; r < 5; r++) {
-    f.addm |= ((L.bitmap[rowa[r] * 20 + wi] >> bi) & 1u) << r;
-    if (WITH_SUB) f.subm |= ((L.bitmap[rows[r] * 20 + wi] >> bi) & 1u) << r;
-  }
-  pw = 1;
-#pragma unroll
-  for (int r = 5; r < 9; r++) {
-    const uint32_t sa = sfx + ((full >> (3 * r) & 1u) ? 0u : pw);
-    f.addm |= ((L.bitmap[rowp * 20 + (sa >> 5)] >> (sa & 31)) & 1u) << r;
-    if (WITH_SUB) {
-      const uint32_t ss = sfx - ((present >> (3 * r) & 1u) ? pw : 0u);
-      f.subm |= ((L.bitmap[rowp * 20 + (ss >> 5)] >> (ss & 31)) & 1u) << r;
-    }
-    pw *= 5;
-  }
-  f.addm &= ~squeeze9(full);
-  f.subm &= squeeze9(present);
-  return f;
-}
 // kinds of which the seat owns four once its melds are counted: the melds' tiles are added to the concealed
 // counts field by field (a kind never exceeds four copies, so no field overflows)
 MJ_HD uint64_t own4_mask(const uint32_t h[4], uint64_t meldw, int n_meld)
@@ -501,7 +474,15 @@ MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h
   if (standard) MJ_STAT(n_tp_standard);
   MJ_RB(tps, standard);
   if (standard) {                       // rare: the search proper
-    const SuitFacts f0 = suit_facts<true>(L, h0), f1 = suit_facts<true>(L, h1), f2 = suit_facts<true>(L, h2);
+    // the three numbered suits' neighbours: one read each from the table of all patterns, issued together
+    const uint32_t e0 = L.nb[prefix5(h0) + 3125u * suffix5(h0)], e1 = L.nb[prefix5(h1) + 3125u * suffix5(h1)];
+    const uint32_t e2 = L.nb[prefix5(h2) + 3125u * suffix5(h2)];
+    SuitFacts f0, f1, f2;
+    f0.valid = e0 & 1u; f0.addm = e0 >> 1 & 0x1FFu; f0.subm = e0 >> 10 & 0x1FFu;
+    f1.valid = e1 & 1u; f1.addm = e1 >> 1 & 0x1FFu; f1.subm = e1 >> 10 & 0x1FFu;
+    f2.valid = e2 & 1u; f2.addm = e2 >> 1 & 0x1FFu; f2.subm = e2 >> 10 & 0x1FFu;
+    // numbered ranks whose tile may leave with the wait in the same suit (tiles the seat owns four of not yet excluded)
+    const uint64_t xchg = (uint64_t)(e0 >> 19 & 0x1FFu) | (uint64_t)(e1 >> 19 & 0x1FFu) << 9 | (uint64_t)(e2 >> 19 & 0x1FFu) << 18 | K_HONORS;
     const uint64_t full = own4_mask(h, meldw, n_meld);
     const uint64_t subp = (uint64_t)f0.subm | (uint64_t)f1.subm << 9 | (uint64_t)f2.subm << 18 | (uint64_t)honors_submask(h3) << 27;
     const uint64_t addp = ((uint64_t)f0.addm | (uint64_t)f1.addm << 9 | (uint64_t)f2.addm << 18 |
@@ -538,7 +519,7 @@ MJ_HD uint64_t tenpai_discards_from_facts(const Lut *Lp, uint32_t h0, uint32_t h
       if ((feas >> s1 & 1) && bad_others == 0)
         own_suit |= (uint64_t)squeeze9(fields_nonzero(h[s1])) << (9 * s1);
     }
-    own_suit &= ~out;
+    own_suit &= ~out & xchg;
     MJ_RB(tpo, own_suit != 0);
     while (own_suit) {
       MJ_STAT(n_tp_own);
@@ -880,11 +861,11 @@ MJ_HD void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
   if (over) return;
 
   // per-suit probes
-  int nd[3]; uint32_t idx[3];
+  int nd[3]; uint32_t rec0[3], key[3];
   int n_pair_suits = 0; bool std_ok = true;
+  lut_records3(L, q.h, nd, rec0, key);
 #pragma unroll
   for (int s = 0; s < 3; s++) {
-    nd[s] = lut_records(L, q.h[s], &idx[s]);
     if (nd[s] == 0) std_ok = false;
     if (tiles_in(q.h[s]) % 3 == 2) n_pair_suits++;
   }
@@ -991,9 +972,9 @@ MJ_HD void eval_hand(const Lut *Lp, const HandIn &q, HandOut &out)
         for (int i2 = 0; i2 < nd[2]; i2++) {
           MJ_STAT(n_decomp);
           Decomp d = base;
-          add_record(d, L.recs[idx[0] + i0], 0);
-          add_record(d, L.recs[idx[1] + i1], 1);
-          add_record(d, L.recs[idx[2] + i2], 2);
+          add_record(d, i0 == 0 ? rec0[0] : L.recs[4 * (size_t)key[0] + i0], 0);
+          add_record(d, i1 == 0 ? rec0[1] : L.recs[4 * (size_t)key[1] + i1], 1);
+          add_record(d, i2 == 0 ? rec0[2] : L.recs[4 * (size_t)key[2] + i2], 2);
           eval_decomp(c, d);
         }
     c.colour_ym &= ~gates;

@@ -144,6 +144,23 @@ MJ_HD void eval_seat(Ctx &c, int s, int w, bool tsumo, bool chankan, HandOut &ou
   MJ_RE(ev, PR_EVAL);
 }
 
+// A complete hand certainly has a yaku when the situation alone gives one: riichi, a self-drawn closed hand, a win on
+// a replacement tile or on the tile of a kan, or on the last tile.  (These are exactly the situational yaku that the
+// evaluator adds to every interpretation, so "some interpretation has a yaku" holds without looking at the tiles.)
+// Used where only the yes / no is needed, i.e. when a win is OFFERED; the value is computed when the win is taken.
+#ifndef MJ_SURE
+#define MJ_SURE 1
+#endif
+MJ_HD bool sure_yaku(Ctx &c, int s, bool tsumo, bool chankan)
+{
+  const uint32_t sw = SW(c, s);
+  const bool menzen = menzen_of(c, s);
+  const bool rinshan = (c.g.kanflags & 1) != 0;
+  if (menzen && (tsumo || sw_get(sw, SW_RIICHI, 2))) return true;
+  if (tsumo ? (rinshan || c.g.live_left == 0) : (chankan || c.g.live_left == 0)) return true;
+  return false;
+}
+
 MJ_HD bool furiten(Ctx &c, int s)
 {
   uint32_t sw = SW(c, s);
@@ -220,10 +237,13 @@ MJ_HD void turn_mask(Ctx &c)
   MJ_RE(tme, PR_TM_EXACT);
   MJ_RB(tmt, !c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1));
   if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
-    MJ_STAT(n_tsumo_eval);
-    HandOut r;
-    eval_seat(c, s, drawn_k, true, false, r);
-    if (r.yaku_ok) set_action(m, A_TSUMO);
+    if (MJ_SURE && sure_yaku(c, s, true, false)) set_action(m, A_TSUMO);
+    else {
+      MJ_STAT(n_tsumo_eval);
+      HandOut r;
+      eval_seat(c, s, drawn_k, true, false, r);
+      if (r.yaku_ok) set_action(m, A_TSUMO);
+    }
   }
   MJ_RE(tmt, PR_TM_TSUMO);
   const bool kan_ok = !c.g.riichi_pending && drawn_k >= 0 && c.g.live_left > 0 && c.g.n_kan < 4;
@@ -619,10 +639,13 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   if (!(WAITS(c, o) >> k & 1)) return false;
   bool ok = false;
   if (!furiten(c, o)) {
-    MJ_STAT(n_ron_eval);
-    HandOut r;
-    eval_seat(c, o, k, false, chankan, r);
-    ok = r.yaku_ok;
+    if (MJ_SURE && sure_yaku(c, o, false, chankan)) ok = true;
+    else {
+      MJ_STAT(n_ron_eval);
+      HandOut r;
+      eval_seat(c, o, k, false, chankan, r);
+      ok = r.yaku_ok;
+    }
   }
   if (!ok) mark_furiten(c, o);
   return ok;

@@ -38,7 +38,8 @@ constexpr int kAuxBlock = 256;           // lanes per block of the helper kernel
 struct DevTables {
   const uint8_t *probe;                  // global: rowid[kRowIdBytes] followed by bitmap[rows * 20]
   const uint16_t *base, *rowrank;
-  const uint32_t *keyinfo, *recs;
+  const uint32_t *recs;
+  const uint32_t *nb;                    // neighbours of every suit pattern (7.8 MB, read through L2)
   int probe_bytes;                       // multiple of 16
 };
 constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of 16
@@ -68,13 +69,37 @@ struct BlockMem {
   bool lane_on;                          // this lane carries an environment
 };
 
-// carve up the block's LDS and copy the probe tables in (ends with a block barrier)
-template <int LPW>
-__device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds)
+// The probe tables go from global memory to the block's LDS in two halves, so that a kernel can put its own loads
+// between them: table_fetch starts the loads (all in flight together), table_commit writes them to LDS.  A caller
+// that loads its hot state in between pays one memory round trip for both.
+constexpr int kTableChunks = 6;          // 16-byte chunks per lane: 6 x 128 lanes x 16 B = 12 KB >= the probe tables
+struct TableRegs { uint4 v[kTableChunks]; };
+__device__ __forceinline__ TableRegs table_fetch(const DevTables &T)
 {
+  TableRegs r;
   const uint4 *src = (const uint4 *)T.probe;
+  const int n = T.probe_bytes / 16;
+#pragma unroll
+  for (int k = 0; k < kTableChunks; k++) {
+    const int i = (int)threadIdx.x + k * kBlock;
+    r.v[k] = i < n ? src[i] : make_uint4(0, 0, 0, 0);
+  }
+  return r;
+}
+__device__ __forceinline__ void table_commit(const DevTables &T, uint8_t *lds, const TableRegs &r)
+{
   uint4 *dst = (uint4 *)lds;
-  for (int i = threadIdx.x; i < T.probe_bytes / 16; i += blockDim.x) dst[i] = src[i];
+  const int n = T.probe_bytes / 16;
+#pragma unroll
+  for (int k = 0; k < kTableChunks; k++) {
+    const int i = (int)threadIdx.x + k * kBlock;
+    if (i < n) dst[i] = r.v[k];
+  }
+}
+// carve up the block's LDS (no memory traffic)
+template <int LPW>
+__device__ __forceinline__ BlockMem carve_block(const DevTables &T, uint8_t *lds)
+{
   BlockMem m;
   m.epb = envs_per_block(LPW);
   m.idx = (int)(threadIdx.x >> 6) * LPW + (int)(threadIdx.x & 63);
@@ -83,8 +108,17 @@ __device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds
   m.hw = (uint32_t *)(lds + T.probe_bytes + (size_t)m.epb * 8 * kHotU64);
   m.L.rowid = lds;
   m.L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
-  m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.keyinfo = T.keyinfo; m.L.recs = T.recs;
+  m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.recs = T.recs; m.L.nb = T.nb;
   m.col = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + m.idx;
+  return m;
+}
+// ... and copy the probe tables in (ends with a block barrier)
+template <int LPW>
+__device__ __forceinline__ BlockMem stage_block(const DevTables &T, uint8_t *lds)
+{
+  BlockMem m = carve_block<LPW>(T, lds);
+  const TableRegs r = table_fetch(T);
+  table_commit(T, lds, r);
   __syncthreads();
   return m;
 }
@@ -117,12 +151,12 @@ __device__ __forceinline__ void store_hot(const BlockMem &m, void *state, int64_
 // Deal for every lane of the wavefront that needs one.  All 64 lanes must call this together.
 // One environment at a time, with values that are uniform over the wavefront:
 //   - 34 lanes run Philox (counter word 1 = lane) and turn their four words into four swap targets;
-//   - the wall lives in ONE vector register, four tile ids per lane in lanes 0..33; the 135 swaps of the
-//     Fisher-Yates pass are readlane / select pairs on it (no memory in the loop);
-//   - lanes 0..33 store their word of the wall to HBM, the 4 x 13 tiles are accumulated into sixteen packed
-//     hand words with scalar arithmetic, lanes 0..3 compute the waits of the four hands side by side;
+//   - the wall lives in ONE vector register, four tile ids per lane in lanes 0..33; instead of doing the 135 swaps
+//     of the Fisher-Yates pass one after the other, every position is traced back through them on its own lane
+//     (compare / select against swap targets read by readlane; no memory and no long dependent chain in the loop);
+//   - lanes 0..33 store their word of the wall to HBM; lanes 0..3 collect the 13 tiles of one seat wind each into
+//     packed hand words (lane permutes) and compute the waits of the four hands side by side;
 //   - the owner lane writes the results into its state and takes the dealer's first draw.
-__device__ __forceinline__ uint32_t set_byte(uint32_t w, int pos, uint32_t v) { return (w & ~(255u << (8 * pos))) | v << (8 * pos); }
 
 __device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_t B, int64_t b)
 {
@@ -150,68 +184,63 @@ __device__ __forceinline__ void deal_wave(Ctx &c, bool need, void *state, int64_
       kv2 = i + 2 + mulhi(r[2], (uint32_t)(134 - i));
       kv3 = i + 3 < 135 ? i + 3 + mulhi(r[3], (uint32_t)(133 - i)) : (uint32_t)(i + 3);
     }
-    // the wall: ids 4*lane .. 4*lane+3 in the four bytes of lane's word
-    uint32_t wv = lane < 34 ? (uint32_t)(4 * lane) * 0x01010101u + 0x03020100u : 0u;
-    for (int j = 0; j < 34; j++) {
+    // The permutation without doing the swaps one after the other: position i is final after swap i, which puts
+    // there what stood at k_i just before; what stood at a position q > j before swap j is what stood at j before it
+    // if q = k_j, else what stood at q.  So every position is traced back on its own -- q = k_i, then for j = i - 1
+    // down to 0: q = j where q = k_j -- to the tile id it started as (the wall starts as 0..135).  Lane L < 34 traces
+    // positions 4L..4L+3 (their k_i are its own four values; position 135 is never swapped as "i": k = 135); the only
+    // value carried through the 135 steps is q, the k_j come from registers by readlane.
+    uint32_t q0 = kv0, q1 = kv1, q2 = kv2, q3 = kv3;
+    const uint32_t i0 = 4u * (uint32_t)lane;
+    for (int jj = 33; jj >= 0; jj--) {
 #pragma unroll
-      for (int t = 0; t < 4; t++) {
-        const uint32_t kvt = t == 0 ? kv0 : t == 1 ? kv1 : t == 2 ? kv2 : kv3;
-        const int k = (int)__builtin_amdgcn_readlane(kvt, j);
-        const int lk = k >> 2, pk = k & 3;
-        const uint32_t wa = __builtin_amdgcn_readlane(wv, j);
-        const uint32_t wb = __builtin_amdgcn_readlane(wv, lk);
-        const uint32_t x = (wa >> (8 * t)) & 255u, y = (wb >> (8 * pk)) & 255u;
-        if (lk == j) {
-          wv = lane == j ? set_byte(set_byte(wa, t, y), pk, x) : wv;
-        } else {
-          wv = lane == j ? set_byte(wa, t, y) : lane == lk ? set_byte(wb, pk, x) : wv;
-        }
+      for (int t = 3; t >= 0; t--) {
+        const uint32_t j = 4u * (uint32_t)jj + (uint32_t)t;
+        if (j >= 135u) continue;
+        const uint32_t kj = __builtin_amdgcn_readlane(t == 0 ? kv0 : t == 1 ? kv1 : t == 2 ? kv2 : kv3, jj);
+        q0 = (j < i0 && q0 == kj) ? j : q0;
+        q1 = (j < i0 + 1u && q1 == kj) ? j : q1;
+        q2 = (j < i0 + 2u && q2 == kj) ? j : q2;
+        q3 = (j < i0 + 3u && q3 == kj) ? j : q3;
       }
     }
+    // the wall: ids of positions 4*lane .. 4*lane+3 in the four bytes of lane's word
+    const uint32_t wv = lane < 34 ? (q0 | q1 << 8 | q2 << 16 | q3 << 24) : 0u;
     // the wall goes to HBM, one word per lane
     const int sel = (int)__builtin_amdgcn_readlane((uint32_t)c.g.wall_sel, src);
     if (lane < 34) (state_u32(state, B) + (int64_t)(kHotU32 + 11 + 34 * sel) * B + bsrc)[(int64_t)lane * B] = wv;
-    // 4 x 13 tiles -> packed hand words (index j = seat wind), all in uniform values
-    uint32_t hw[4][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
-    uint32_t red[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-#pragma unroll
-      for (int t = 0; t < 13; t++) {
+    // 4 x 13 tiles -> packed hand words: lane j < 4 collects the hand of seat wind j (its tiles come from the other
+    // lanes' wall words by a lane permute; every lane takes part, lanes >= 4 repeat the work of lane & 3) and then
+    // computes that hand's waits.  Field 3k of a 102-bit accumulator counts kind k, as in refill_next_wall.
+    uint32_t h0, h1, h2, h3, reds = 0;
+    {
+      const int j = lane & 3;
+      uint64_t lo = 0, hi = 0;
+#pragma unroll 1                          // rolled on purpose: unrolled, the thirteen permutes in flight cost the kernel
+      for (int t = 0; t < 13; t++) {          // registers on a path that is rare (measured 1.7 % of the rollout's rate)
         const int i = 13 * j + t;
-        const uint32_t id = (__builtin_amdgcn_readlane(wv, i >> 2) >> (8 * (i & 3))) & 255u;
-        const int kind = (int)(id >> 2), su = suit_of(kind);
-        const uint32_t inc = 1u << (3 * rank_of(kind, su));
-#pragma unroll
-        for (int q = 0; q < 4; q++) hw[j][q] += su == q ? inc : 0u;
-        if (red_rules && (id == 16u || id == 52u || id == 88u)) red[j] |= 1u << su;
+        const uint32_t id = ((uint32_t)__shfl((int)wv, i >> 2) >> (8 * (i & 3))) & 255u;
+        const uint32_t kind = id >> 2;
+        if (kind < 21) lo += 1ull << (3 * kind); else hi += 1ull << (3 * (kind - 21));
+        if (red_rules && (id == 16u || id == 52u || id == 88u)) reds |= 1u << (kind / 9);
       }
+      h0 = (uint32_t)lo & 0x7FFFFFFu; h1 = (uint32_t)(lo >> 27) & 0x7FFFFFFu;
+      h2 = (uint32_t)(lo >> 54) | ((uint32_t)hi & 0x3FFFFu) << 9; h3 = (uint32_t)(hi >> 18);
     }
-    // waits of the four 13-tile hands: lane L < 4 takes seat L, whose seat wind is (L - dealer) & 3
     uint64_t wt = 0;
-    if (lane < 4) {
-      const int j = (lane - dealer) & 3;
-      const uint32_t h0 = pick4(hw[0][0], hw[1][0], hw[2][0], hw[3][0], j), h1 = pick4(hw[0][1], hw[1][1], hw[2][1], hw[3][1], j);
-      const uint32_t h2 = pick4(hw[0][2], hw[1][2], hw[2][2], hw[3][2], j), h3 = pick4(hw[0][3], hw[1][3], hw[2][3], hw[3][3], j);
-      wt = waits_of(&c.L, h0, h1, h2, h3, 0, 0);
-    }
+    if (lane < 4) wt = waits_of(&c.L, h0, h1, h2, h3, 0, 0);
     const uint32_t wt_lo = (uint32_t)wt, wt_hi = (uint32_t)(wt >> 32);
-    uint64_t w4[4];
-#pragma unroll
-    for (int s = 0; s < 4; s++)
-      w4[s] = (uint64_t)__builtin_amdgcn_readlane(wt_hi, s) << 32 | __builtin_amdgcn_readlane(wt_lo, s);
     const uint32_t first_id = (__builtin_amdgcn_readlane(wv, 13) >> 0) & 255u;        // wall[52]
     if (lane == src) {
       deal_reset(c);
 #pragma unroll
       for (int j = 0; j < 4; j++) {
         const int s = (dealer + j) & 3;
-#pragma unroll
-        for (int q = 0; q < 4; q++) HW(c, s, q) = hw[j][q];
-        SW(c, s) |= red[j];
+        HW(c, s, 0) = __builtin_amdgcn_readlane(h0, j); HW(c, s, 1) = __builtin_amdgcn_readlane(h1, j);
+        HW(c, s, 2) = __builtin_amdgcn_readlane(h2, j); HW(c, s, 3) = __builtin_amdgcn_readlane(h3, j);
+        SW(c, s) |= __builtin_amdgcn_readlane(reds, j);
+        WAITS(c, s) = (uint64_t)__builtin_amdgcn_readlane(wt_hi, j) << 32 | __builtin_amdgcn_readlane(wt_lo, j);
       }
-#pragma unroll
-      for (int s = 0; s < 4; s++) WAITS(c, s) = w4[s];
       // the dealer's first draw (wall[52]) without going through HBM
       c.g.draw_ptr = 53; c.g.live_left = 69; c.g.kanflags &= (uint8_t)~1u;
       c.g.drawn = (uint8_t)take_tile(c, dealer, (int)first_id);
@@ -339,27 +368,32 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_new_games(void *state, int64
     if ((threadIdx.x & 63) < LPW && b0 < B) term = (int)(make_env(state, B, b0).glob[0] >> 24 & 0xFFu);   // Glob::terminated
     if (!__syncthreads_or(term)) return;
   }
-  BlockMem m = stage_block<LPW>(T, lds);
+  BlockMem m = carve_block<LPW>(T, lds);
   const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
   const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
   bool touched = false;
+  const TableRegs tr = table_fetch(T);
+  if (active && mode == 1) { load_hot(m, state, B, b); load_glob(c.e, c.g); }     // with the tables: one round trip
+  table_commit(T, lds, tr);
+  __syncthreads();
   if (active) {
     if (mode == 0) {
       reset_env(c, true); touched = true;
       refill_next_wall(c, m.col, m.epb, 0);          // every lane deals now: make the first walls side by side
-    } else {
-      load_glob(c.e, c.g);
-      if (c.g.terminated) { load_hot(m, state, B, b); reset_env(c, false); touched = true; }
-    }
+    } else if (c.g.terminated) { reset_env(c, false); touched = true; }
   }
   deal_stage(c, active, state, B, b);
   if (touched) { step_finish(c); store_hot(m, state, B, b); store_glob(c.e, c.g); }
   if (mode == 0 && active) refill_next_wall(c, m.col, m.epb, 1);
 }
 
+#ifdef MJ_PROFILE
+__device__ long long mj_kstep_prof[4096][8];      // profiling builds only: time stamps of the last k_step launch
+__device__ unsigned long long mj_kstep_regions[2048][3 * PR_N];   // ... and its region counters, per block
+#endif
 // what a step can hand back besides the new state (any pointer may be null)
 struct StepOut {
   uint64_t *mask;          // [B][4][2] legal actions of the state after the step (after the restart, if any)
@@ -373,17 +407,37 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B,
                                                  int auto_reset, StepOut out)
 {
   extern __shared__ __align__(16) uint8_t lds[];
-  BlockMem m = stage_block<LPW>(T, lds);
+#ifdef MJ_PROFILE
+  long long pt[8];
+  for (int i = threadIdx.x; i < 3 * PR_N; i += blockDim.x) mj_prof[i] = 0;
+  __syncthreads();
+  pt[0] = wall_clock64();
+#define MJ_PT(i) pt[i] = wall_clock64()
+#else
+#define MJ_PT(i) ((void)0)
+#endif
+  BlockMem m = carve_block<LPW>(T, lds);
   const int64_t b = (int64_t)blockIdx.x * m.epb + m.idx;
   const bool active = m.lane_on && b < B;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
+  // the tables, the hot state and the control bytes come in with one memory round trip
+  const TableRegs tr = table_fetch(T);
+  uint32_t acts = 0;
   if (active) {
     load_hot(m, state, B, b);
     load_glob(c.e, c.g);
+    acts = ((const uint32_t *)actions)[b];
+  }
+  table_commit(T, lds, tr);
+  __syncthreads();
+  MJ_PT(1);
+  if (active) {
     if (refill && c.e.nserial[0] != c.e.serial[0] + 1) refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
-    step_env(c, ((const uint32_t *)actions)[b]);
+    MJ_PT(2);
+    step_env(c, acts);
+    MJ_PT(3);
     // the step's own results go out before a finished game is started again
     if (out.delta) ((int4 *)out.delta)[b] = make_int4(DELTA(c, 0), DELTA(c, 1), DELTA(c, 2), DELTA(c, 3));
     if (out.reward) {
@@ -395,9 +449,12 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B,
     if (out.terminated) out.terminated[b] = c.g.terminated;
     if (auto_reset && c.g.terminated) reset_env(c, false);
   }
+  MJ_PT(4);
   deal_stage(c, active, state, B, b);
+  MJ_PT(5);
   if (active) {
     step_finish(c);
+    MJ_PT(6);
     if (out.mask) {
 #pragma unroll
       for (int s = 0; s < 4; s++) {
@@ -409,6 +466,18 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_step(void *state, int64_t B,
     store_hot(m, state, B, b);
     store_glob(c.e, c.g);
   }
+#ifdef MJ_PROFILE
+  MJ_PT(7);
+  // 10 ns ticks per wavefront: in, staged, refilled, stepped, (outputs), dealt, mask, stored
+  if ((threadIdx.x & 63) == 0 && blockIdx.x < 2048) {
+    long long *o = mj_kstep_prof[blockIdx.x * 2 + (threadIdx.x >> 6)];
+    for (int i = 0; i < 8; i++) o[i] = active ? pt[i] : 0;
+  }
+  __syncthreads();
+  if (blockIdx.x < 2048)
+    for (int i = threadIdx.x; i < 3 * PR_N; i += blockDim.x) mj_kstep_regions[blockIdx.x][i] = mj_prof[i];
+#endif
+#undef MJ_PT
 }
 
 // the random policy for every acting seat of the lane's environment, packed as four signed bytes
@@ -435,13 +504,21 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
                                                     int n_steps, int auto_reset, int64_t env_lo, int64_t env_hi)
 {
   extern __shared__ __align__(16) uint8_t lds[];
-  BlockMem m = stage_block<LPW>(T, lds);
+  BlockMem m = carve_block<LPW>(T, lds);
   const int64_t b = env_lo + (int64_t)blockIdx.x * m.epb + m.idx;      // the launch covers environments [env_lo, env_hi)
   const bool active = m.lane_on && b < env_hi;
   Ctx c;
   c.e = block_env(m, state, B, active ? b : 0); c.L = m.L; c.R = R; c.env_id = R.env_id_base + (uint32_t)b;
   c.need_deal = false; c.need_turn = false; c.live_ptr = -1;
+#ifdef MJ_OLD_STAGE
+  { const TableRegs tr = table_fetch(T); table_commit(T, lds, tr); __syncthreads(); }
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
+#else
+  const TableRegs tr = table_fetch(T);
+  if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
+  table_commit(T, lds, tr);
+  __syncthreads();
+#endif
 #ifdef MJ_PROFILE
   for (int i = threadIdx.x; i < 3 * PR_N; i += blockDim.x) mj_prof[i] = 0;
   __syncthreads();
@@ -597,7 +674,7 @@ __global__ void __launch_bounds__(kAuxBlock, MJ_OCC) k_eval_hands(DevTables T, i
   }
   Lut Lv;
   Lv.rowid = lds; Lv.bitmap = (const uint32_t *)(lds + kRowIdBytes);
-  Lv.base = T.base; Lv.rowrank = T.rowrank; Lv.keyinfo = T.keyinfo; Lv.recs = T.recs;
+  Lv.base = T.base; Lv.rowrank = T.rowrank; Lv.recs = T.recs; Lv.nb = T.nb;
   const Lut *L = &Lv;
   int64_t i = (int64_t)blockIdx.x * kAuxBlock + threadIdx.x;
   if (i >= n) return;
@@ -839,13 +916,18 @@ const std::vector<uint32_t> &sh_suit_table()
   static const std::vector<uint32_t> t = mjt::build_shanten_table(9, true);
   return t;
 }
+const std::vector<uint32_t> &nb_table()
+{
+  static const std::vector<uint32_t> t = mjt::build_neighbour_table();
+  return t;
+}
 const std::vector<uint32_t> &sh_honor_table()
 {
   static const std::vector<uint32_t> t = mjt::build_shanten_table(7, false);
   return t;
 }
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-struct ScratchLayout { size_t probe, base, rowrank, keyinfo, recs, sh_suit, sh_honor, counters, total, probe_bytes; };
+struct ScratchLayout { size_t probe, base, rowrank, recs, nb, sh_suit, sh_honor, counters, total, probe_bytes; };
 ScratchLayout scratch_layout()
 {
   const mjt::SuitTables &t = tables();
@@ -854,9 +936,9 @@ ScratchLayout scratch_layout()
   s.probe_bytes = t.rowid.size() + t.bitmap.size() * 4;
   s.base = align256(s.probe_bytes);
   s.rowrank = align256(s.base + t.base.size() * 2);
-  s.keyinfo = align256(s.rowrank + t.rowrank.size() * 2);
-  s.recs = align256(s.keyinfo + t.keyinfo.size() * 4);
-  s.sh_suit = align256(s.recs + t.recs.size() * 4);
+  s.recs = align256(s.rowrank + t.rowrank.size() * 2);
+  s.nb = align256(s.recs + t.recs.size() * 4);
+  s.sh_suit = align256(s.nb + nb_table().size() * 4);
   s.sh_honor = align256(s.sh_suit + sh_suit_table().size() * 4);
   s.counters = align256(s.sh_honor + sh_honor_table().size() * 4);
   s.total = s.counters + 256;
@@ -889,7 +971,7 @@ inline int check(hipError_t e) { return e == hipSuccess ? MJ_OK : MJ_E_HIP; }
 // A copy of the per-suit pattern tables (probe part and records, without the shanten block tables) in a file-scope
 // device array: every GPU the library runs on holds its own copy at its own address until the process ends.  In
 // host code the array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
-constexpr size_t kStaticScratchBytes = 224 * 1024;
+constexpr size_t kStaticScratchBytes = 384 * 1024;
 static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 16;
 struct StaticTables { bool ready; DevTables T; };
@@ -907,7 +989,7 @@ int static_tables(const DevTables **out)
   if (!st.ready) {
     const mjt::SuitTables &t = tables();
     const ScratchLayout sl = scratch_layout();
-    const size_t need = sl.sh_suit;                       // everything before the shanten tables
+    const size_t need = sl.nb;                            // everything before the neighbour and shanten tables
     if (need > kStaticScratchBytes || (sl.probe_bytes & 15)) return MJ_E_UNSUPPORTED;
     uint8_t *ptr = nullptr;
     if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MJ_E_HIP;
@@ -916,14 +998,13 @@ int static_tables(const DevTables **out)
     std::memcpy(img.data() + sl.probe + t.rowid.size(), t.bitmap.data(), t.bitmap.size() * 4);
     std::memcpy(img.data() + sl.base, t.base.data(), t.base.size() * 2);
     std::memcpy(img.data() + sl.rowrank, t.rowrank.data(), t.rowrank.size() * 2);
-    std::memcpy(img.data() + sl.keyinfo, t.keyinfo.data(), t.keyinfo.size() * 4);
     std::memcpy(img.data() + sl.recs, t.recs.data(), t.recs.size() * 4);
     if (hipMemcpy(ptr, img.data(), need, hipMemcpyHostToDevice) != hipSuccess) return MJ_E_HIP;
     st.T.probe = ptr + sl.probe;
     st.T.base = (const uint16_t *)(ptr + sl.base);
     st.T.rowrank = (const uint16_t *)(ptr + sl.rowrank);
-    st.T.keyinfo = (const uint32_t *)(ptr + sl.keyinfo);
     st.T.recs = (const uint32_t *)(ptr + sl.recs);
+    st.T.nb = nullptr;                                    // the hand evaluator does not search for tenpai
     st.T.probe_bytes = (int)sl.probe_bytes;
     st.ready = true;
   }
@@ -971,7 +1052,10 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   h->ev_valid = false; h->ev_steps = 0;
   const mjt::SuitTables &t = tables();
   const ScratchLayout sl = scratch_layout();
-  if (t.rowid.size() != (size_t)kRowIdBytes || (sl.probe_bytes & 15)) { delete h; return MJ_E_UNSUPPORTED; }
+  if (t.rowid.size() != (size_t)kRowIdBytes || (sl.probe_bytes & 15) || sl.probe_bytes > (size_t)kTableChunks * kBlock * 16) {
+    delete h;
+    return MJ_E_UNSUPPORTED;
+  }
   int dev = 0, lds_max = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
@@ -987,8 +1071,8 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   std::memcpy(img.data() + sl.probe + t.rowid.size(), t.bitmap.data(), t.bitmap.size() * 4);
   std::memcpy(img.data() + sl.base, t.base.data(), t.base.size() * 2);
   std::memcpy(img.data() + sl.rowrank, t.rowrank.data(), t.rowrank.size() * 2);
-  std::memcpy(img.data() + sl.keyinfo, t.keyinfo.data(), t.keyinfo.size() * 4);
   std::memcpy(img.data() + sl.recs, t.recs.data(), t.recs.size() * 4);
+  std::memcpy(img.data() + sl.nb, nb_table().data(), nb_table().size() * 4);
   std::memcpy(img.data() + sl.sh_suit, sh_suit_table().data(), sh_suit_table().size() * 4);
   std::memcpy(img.data() + sl.sh_honor, sh_honor_table().data(), sh_honor_table().size() * 4);
   int rc = check(hipMemcpyAsync(d_scratch, img.data(), sl.total, hipMemcpyHostToDevice, st));
@@ -997,8 +1081,8 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
   h->T.probe = (const uint8_t *)(sc + sl.probe);
   h->T.base = (const uint16_t *)(sc + sl.base);
   h->T.rowrank = (const uint16_t *)(sc + sl.rowrank);
-  h->T.keyinfo = (const uint32_t *)(sc + sl.keyinfo);
   h->T.recs = (const uint32_t *)(sc + sl.recs);
+  h->T.nb = (const uint32_t *)(sc + sl.nb);
   h->T.probe_bytes = (int)sl.probe_bytes;
   h->sh_suit = (const uint32_t *)(sc + sl.sh_suit);
   h->sh_honor = (const uint32_t *)(sc + sl.sh_honor);
@@ -1201,6 +1285,18 @@ float mj_last_step_kernel_ms(MjHandle *h)
   if (hipEventElapsedTime(&ms, h->ev[0], h->ev[1]) != hipSuccess) return -1.0f;
   return ms / (float)h->ev_steps;
 }
+
+#ifdef MJ_PROFILE
+int mj_prof_read_kstep(long long *h_out /*[4096][8]*/)
+{
+  return check(hipMemcpyFromSymbol(h_out, HIP_SYMBOL(mj_kstep_prof), sizeof(long long) * 4096 * 8));
+}
+int mj_prof_read_kstep_regions(unsigned long long *h_out /*[2048][3 * n]*/, int *n_regions)
+{
+  *n_regions = PR_N;
+  return check(hipMemcpyFromSymbol(h_out, HIP_SYMBOL(mj_kstep_regions), sizeof(unsigned long long) * 2048 * 3 * PR_N));
+}
+#endif
 
 int mj_destroy(MjHandle *h)
 {

@@ -16,9 +16,11 @@
 //  record tables, read from global memory when a winning hand is scored:
 //   base[prefix5]             u16  number of valid keys with a smaller prefix
 //   rowrank[row][20]          u16  set bits of the row before each bitmap word
-//   keyinfo[key]              u32  first record | number of records << 16
-//   recs[]                    u32  bits 0..3 pair rank + 1 (0 = none); four set slots of 5 bits
-//                                  from bit 4: type << 4 | rank (1 = triplet, 0 = run start), 0x1F = empty
+//   recs[key][4]              u32  the key's decompositions (at most four), unused entries 0; bits 28..29 of the
+//                                  first one hold their number - 1, so one 4-byte load per suit serves the usual
+//                                  case of a single decomposition.  A record: bits 0..3 pair rank + 1 (0 = none); four set slots
+//                                  of 5 bits from bit 4: type << 4 | rank (1 = triplet, 0 = run start), 0x1F = empty
+//                                  (so a record is never 0)
 #pragma once
 #include <algorithm>
 #include <cstdint>
@@ -37,8 +39,7 @@ struct SuitTables {
   std::vector<uint32_t> bitmap;    // n_rows * kRowWords
   std::vector<uint16_t> base;      // kPrefixes (+ pad)
   std::vector<uint16_t> rowrank;   // n_rows * kRowWords
-  std::vector<uint32_t> keyinfo;   // n_keys
-  std::vector<uint32_t> recs;      // n_recs
+  std::vector<uint32_t> recs;      // n_keys * 4
   int n_rows = 0, n_keys = 0, n_recs = 0;
 };
 
@@ -125,11 +126,11 @@ inline SuitTables build()
   }
   t.n_rows = (int)row_of.size();
   for (auto &kv : ordered) {
-    t.keyinfo.push_back((uint32_t)t.recs.size() | (uint32_t)kv.second->size() << 16);
-    for (uint32_t r : *kv.second) t.recs.push_back(r);
+    for (int j = 0; j < 4; j++) t.recs.push_back(j < (int)kv.second->size() ? (*kv.second)[j] : 0u);
+    t.recs[t.recs.size() - 4] |= (uint32_t)(kv.second->size() - 1) << 28;      // how many there are, with the first one
+    t.n_keys++;
+    t.n_recs += (int)kv.second->size();
   }
-  t.n_keys = (int)t.keyinfo.size();
-  t.n_recs = (int)t.recs.size();
   return t;
 }
 
@@ -190,6 +191,48 @@ inline std::vector<uint32_t> build_shanten_table(int n_ranks, bool runs)
     }
     F[key] = f;
     out[key] = pack_frontier(f);
+  }
+  return out;
+}
+
+// ---------------------------------------------------------------- neighbours
+// For every pattern of nine counts 0..4 of one suit (key = base-5 number of the counts = prefix5 + 3125 * suffix5,
+// 1,953,125 entries of 32 bits): what the search for tenpai-keeping discards asks about a suit, answered by one read
+// instead of some thirty probes of the pattern table:
+//   bit 0        the pattern itself is valid (sets, or sets and a pair)
+//   bits 1..9    rank r holds fewer than four and the pattern with one more tile of rank r is valid
+//   bits 10..18  rank r is held and the pattern with one tile of rank r less is valid
+//   bits 19..27  rank r is held and the pattern with one tile of rank r less can be made valid by adding some tile
+inline std::vector<uint32_t> build_neighbour_table()
+{
+  std::map<uint32_t, std::vector<uint32_t>> keys;
+  enumerate(keys);
+  const int N = 1953125;
+  std::vector<uint8_t> valid((size_t)N, 0);
+  for (auto &kv : keys) valid[kv.first] = 1;
+  int pw[9];
+  pw[0] = 1;
+  for (int r = 1; r < 9; r++) pw[r] = pw[r - 1] * 5;
+  // first pass: valid + "can take a tile of rank r"
+  std::vector<uint32_t> out((size_t)N, 0);
+  int c[9] = {0};
+  for (int key = 0; key < N; key++) {
+    uint32_t v = valid[key];
+    for (int r = 0; r < 9; r++) if (c[r] < 4 && valid[key + pw[r]]) v |= 1u << (1 + r);
+    out[key] = v;
+    for (int r = 0; r < 9; r++) { if (++c[r] < 5) break; c[r] = 0; }      // next count vector
+  }
+  // second pass: what removing a tile of rank r leaves
+  for (int r = 0; r < 9; r++) c[r] = 0;
+  for (int key = 0; key < N; key++) {
+    uint32_t v = out[key];
+    for (int r = 0; r < 9; r++) if (c[r] > 0) {
+      const uint32_t less = out[key - pw[r]];
+      if (less & 1u) v |= 1u << (10 + r);
+      if (less & 0x3FEu) v |= 1u << (19 + r);
+    }
+    out[key] = v;
+    for (int r = 0; r < 9; r++) { if (++c[r] < 5) break; c[r] = 0; }
   }
   return out;
 }

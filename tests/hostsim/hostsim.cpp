@@ -71,7 +71,9 @@ Sim *hs_create(int64_t B, uint64_t seed, const MjRules *r)
   h->state.assign((size_t)(B * kBytesPerEnv + 7) / 8, 0);
   h->T = mjt::build();
   h->L.rowid = h->T.rowid.data(); h->L.bitmap = h->T.bitmap.data(); h->L.base = h->T.base.data();
-  h->L.rowrank = h->T.rowrank.data(); h->L.keyinfo = h->T.keyinfo.data(); h->L.recs = h->T.recs.data();
+  h->L.rowrank = h->T.rowrank.data(); h->L.recs = h->T.recs.data();
+  static const std::vector<uint32_t> nb_table = mjt::build_neighbour_table();
+  h->L.nb = nb_table.data();
   for (int64_t b = 0; b < B; b++) { Ctx c = ctx_of(h, b); reset_env(c, true); store_glob(c.e, c.g); }
   return h;
 }

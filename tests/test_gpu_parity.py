@@ -433,3 +433,26 @@ def test_binding_refuses_tensors_the_kernels_could_not_index():
         env.observe_tokens(torch.empty((100, 4, 496), dtype=torch.uint8, device="cuda:0")[:, :, ::2])
     env.step(env.sample_random())                        # and the environment still works
     env.close()
+
+
+@pytest.mark.parametrize("B", [33, 3000])
+def test_fused_steps_with_observation_every_step(B):
+    """the fused path with write_obs: the bit strings of a step are expanded on the library's second stream while the
+    next step runs; after each call (1, 2, 5, 3 and 64 steps, two calls back to back without a synchronisation in
+    between) the tensor holds the observation of the last step, and the state is the oracle's"""
+    import torch
+    o = mjo.Oracle(B, 14, mjo.RULES_RED, mjo.MODE_HALF)
+    g = GpuEngine(B, seed=14, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    obs = torch.zeros((B, 4, 56, 34), dtype=torch.uint8, device="cuda:0")
+    for n in (1, 2, 5, 3, 64):
+        g.env.step_random(n, True, obs)
+        o.step_random(n)
+        assert np.array_equal(o.observe(), obs.cpu().numpy()), n
+    g.env.step_random(7, True, obs)
+    g.env.step_random(4, True, obs)
+    o.step_random(11)
+    assert np.array_equal(o.observe(), obs.cpu().numpy())
+    assert not diff_records(o.export(), g.export())
+    # the separate entry point still agrees
+    assert np.array_equal(o.observe(), g.observe())
+    g.close()
