@@ -53,7 +53,7 @@ MJ_HD void export_env(const Env &e, MjEnvCanon &o)
   o.end_type = g.end_type; o.winners = g.winners; o.loser = g.loser; o.tenpai_mask = g.tenpai_mask;
   o.dora_pending = g.kanflags >> 1 & 1; o.n_hist = g.hist_len;
   for (int i = 0; i < 128; i++)
-    o.hist[i] = i < g.hist_len ? e.hist[(int64_t)i * n] : (uint16_t)0;
+    o.hist[i] = i < g.hist_len ? e.hist[i] : (uint16_t)0;
 }
 
 MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
@@ -102,7 +102,7 @@ MJ_HD void import_env(const Env &e, const MjEnvCanon &o)
   g.end_type = o.end_type; g.winners = o.winners; g.loser = o.loser; g.tenpai_mask = o.tenpai_mask;
   g.wall_sel = 0;                      // the imported wall goes to buffer 0
   g.hist_len = o.n_hist > 128 ? 128 : o.n_hist;
-  for (int i = 0; i < 128; i++) e.hist[(int64_t)i * n] = o.hist[i];
+  for (int i = 0; i < 128; i++) e.hist[i] = o.hist[i];
   store_glob(e, g);
 }
 
@@ -299,7 +299,7 @@ MJ_HD void token_obs(const Env &e, const Glob &g, int me, uint32_t rule_flags, c
   o.n_hist = g.hist_len;
   for (int i = 0; i < 15; i++) o.zero_[i] = 0;
   for (int i = 0; i < 128; i++)
-    o.hist[i] = i < g.hist_len ? hist_token(e.hist[(int64_t)i * e.n], me) : (uint16_t)0xFFFF;
+    o.hist[i] = i < g.hist_len ? hist_token(e.hist[i], me) : (uint16_t)0xFFFF;
 }
 
 }  // namespace mj

@@ -122,7 +122,9 @@ struct Env {
   uint32_t *nexth, *nextred;                          // cold [16] [1]: its four dealt hands by seat wind, red fives
   uint64_t *nextwaits;                                // cold [4]: their waits
   uint8_t *river;                                     // cold [128]
-  uint16_t *hist;                                     // cold [128]: the kyoku's public actions in order, action | seat << 8
+  uint16_t *hist;                                     // this environment's row of 128 entries: the kyoku's public actions
+                                                      // in order, action | seat << 8
+
 };
 
 // control bytes kept in registers during a step (7 words in HBM)
@@ -160,6 +162,14 @@ MJ_HD int cnt3(uint32_t w, int r) { return (int)((w >> (3 * r)) & 7u); }
 MJ_HD uint64_t kbit(int k) { return 1ull << k; }
 MJ_HD int code_kind(int c) { return c & 63; }
 MJ_HD int code_red(int c) { return (c >> 6) & 1; }
+
+// a 32-bit word of a byte row (rows of river bytes and history entries start at multiples of four bytes)
+MJ_HD uint32_t row_word(const void *row, int i)
+{
+  uint32_t w;
+  __builtin_memcpy(&w, __builtin_assume_aligned((const uint8_t *)row + 4 * i, 4), 4);      // one 4-byte load
+  return w;
+}
 
 MJ_HD int m_type(uint32_t m) { return (int)(m & 7); }
 MJ_HD int m_kind(uint32_t m) { return (int)((m >> 3) & 63); }

@@ -838,7 +838,7 @@ MJ_HD void mark_passed_ron(Ctx &c, int ron_offered)
 MJ_HD void hist_push(Ctx &c, int s, int a)
 {
   const int i = c.g.hist_len;
-  if (i < 128) { c.e.hist[(int64_t)i * c.e.n] = (uint16_t)(a | s << 8); c.g.hist_len = (uint8_t)(i + 1); }
+  if (i < 128) { c.e.hist[i] = (uint16_t)(a | s << 8); c.g.hist_len = (uint8_t)(i + 1); }
 }
 
 // One step of one environment, as a fixed sequence of stages that every lane walks through in the same order

@@ -838,16 +838,16 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe_tokens(void *state, int64
     load_glob(e, g);
     tok_own(e, s, sh_suit, sh_honor, o);
     tok_env(e, g, s, rule_flags, o);
-    // entries 32 s .. 32 s + 31 of the history: 2-byte loads, consecutive games on consecutive addresses
+    // entries 32 s .. 32 s + 31 of the history: sixteen words of the environment's row, two entries each
     const int nh = g.hist_len;
     if (s == 0) p_nhist[el] = (uint32_t)nh;
-    uint16_t hv[32];
+    uint32_t hv[16];
 #pragma unroll
-    for (int j = 0; j < 32; j++) hv[j] = e.hist[(int64_t)(32 * s + j) * B];      // all 32 loads in flight together
+    for (int j = 0; j < 16; j++) hv[j] = row_word(e.hist + 32 * s, j);              // all sixteen loads in flight together
 #pragma unroll
     for (int j = 0; j < 16; j++) {
       const int i0 = 32 * s + 2 * j;
-      const uint32_t lo = i0 < nh ? (uint32_t)hv[2 * j] : 0xFFFFu, hi = i0 + 1 < nh ? (uint32_t)hv[2 * j + 1] : 0xFFFFu;
+      const uint32_t lo = i0 < nh ? hv[j] & 0xFFFFu : 0xFFFFu, hi = i0 + 1 < nh ? hv[j] >> 16 : 0xFFFFu;
       p_hist[el][16 * s + j] = lo | hi << 16;
     }
     tok_seats(sw, sc, ml, s, o);
