@@ -172,13 +172,18 @@ MJ_HD uint64_t obs_seat_masks(const Env &e, int s, uint64_t out[OB_SEAT_WORDS])
   return redvis;
 }
 
-MJ_HD void obs_env_masks(const Env &e, const Glob &g, uint32_t rule_flags, uint64_t seat_red, uint64_t out[OG_WORDS])
+// the two words of the current wall that hold the dora indicators (wall positions 124..131; the indicators are 126..130)
+MJ_HD void dora_words(const Env &e, int wall_sel, uint32_t dw[2])
 {
-  const int64_t n = e.n;
+  dw[0] = e.wallw[(int64_t)(wall_sel * 34 + 31) * e.n];
+  dw[1] = e.wallw[(int64_t)(wall_sel * 34 + 32) * e.n];
+}
+MJ_HD void obs_env_masks(const Glob &g, uint32_t rule_flags, uint64_t seat_red, const uint32_t dw[2], uint64_t out[OG_WORDS])
+{
   uint32_t ind[4] = {0, 0, 0, 0};
   uint64_t redvis = seat_red;
   for (int i = 0; i < g.n_dora; i++) {
-    int id = wall_at(e, g.wall_sel, 126 + i);
+    int id = (int)(dw[(i + 2) >> 2] >> (8 * ((i + 2) & 3)) & 255u);
     bump(ind, id >> 2, 1);
     if ((rule_flags & F_RED) && (id == 16 || id == 52 || id == 88)) redvis |= kbit(id >> 2);
   }

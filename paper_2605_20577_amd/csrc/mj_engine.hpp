@@ -148,9 +148,6 @@ MJ_HD void eval_seat(Ctx &c, int s, int w, bool tsumo, bool chankan, HandOut &ou
 // a replacement tile or on the tile of a kan, or on the last tile.  (These are exactly the situational yaku that the
 // evaluator adds to every interpretation, so "some interpretation has a yaku" holds without looking at the tiles.)
 // Used where only the yes / no is needed, i.e. when a win is OFFERED; the value is computed when the win is taken.
-#ifndef MJ_SURE
-#define MJ_SURE 1
-#endif
 MJ_HD bool sure_yaku(Ctx &c, int s, bool tsumo, bool chankan)
 {
   const uint32_t sw = SW(c, s);
@@ -237,7 +234,7 @@ MJ_HD void turn_mask(Ctx &c)
   MJ_RE(tme, PR_TM_EXACT);
   MJ_RB(tmt, !c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1));
   if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
-    if (MJ_SURE && sure_yaku(c, s, true, false)) set_action(m, A_TSUMO);
+    if (sure_yaku(c, s, true, false)) set_action(m, A_TSUMO);
     else {
       MJ_STAT(n_tsumo_eval);
       HandOut r;
@@ -639,7 +636,7 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   if (!(WAITS(c, o) >> k & 1)) return false;
   bool ok = false;
   if (!furiten(c, o)) {
-    if (MJ_SURE && sure_yaku(c, o, false, chankan)) ok = true;
+    if (sure_yaku(c, o, false, chankan)) ok = true;
     else {
       MJ_STAT(n_ron_eval);
       HandOut r;
@@ -1083,14 +1080,12 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   MJ_RE(kdr, PR_KANDRAW);
 }
 
-// uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)
-MJ_HD int sample_action(uint64_t m0, uint64_t m1, uint32_t seed, uint32_t env_id, uint64_t step, int seat)
+// the mulhi(r, n)-th set bit of a mask of n legal actions (-1 for an empty mask)
+MJ_HD int pick_action(uint64_t m0, uint64_t m1, uint32_t r)
 {
   int n = popc64(m0) + popc64(m1);
   if (n == 0) return -1;
-  uint32_t r[4];
-  philox((uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seat, 1, seed, env_id, r);
-  int pick = (int)mulhi(r[0], (uint32_t)n);
+  int pick = (int)mulhi(r, (uint32_t)n);
   int n0 = popc64(m0);
   uint64_t m = m0; int base = 0;
   if (pick >= n0) { pick -= n0; m = m1; base = 64; }
@@ -1104,6 +1099,14 @@ MJ_HD int sample_action(uint64_t m0, uint64_t m1, uint32_t seed, uint32_t env_id
     if (pick >= c) { pick -= c; w >>= half; base += half; }
   }
   return base;
+}
+// uniform choice among the set bits of a mask: key (seed, env_id), counter (step_lo, step_hi, seat, 1)
+MJ_HD int sample_action(uint64_t m0, uint64_t m1, uint32_t seed, uint32_t env_id, uint64_t step, int seat)
+{
+  if ((m0 | m1) == 0) return -1;
+  uint32_t r[4];
+  philox((uint32_t)step, (uint32_t)(step >> 32), (uint32_t)seat, 1, seed, env_id, r);
+  return pick_action(m0, m1, r[0]);
 }
 
 }  // namespace mj

@@ -151,7 +151,9 @@ void hs_observe(Sim *h, uint8_t *obs)
     load_glob(e, g);
     uint64_t S[4][OB_SEAT_WORDS], G[OG_WORDS], red = 0;
     for (int s = 0; s < 4; s++) red |= obs_seat_masks(e, s, S[s]);
-    obs_env_masks(e, g, h->R.flags, red, G);
+    uint32_t dw[2];
+    dora_words(e, g.wall_sel, dw);
+    obs_env_masks(g, h->R.flags, red, dw, G);
     for (int me = 0; me < 4; me++)
       for (int p = 0; p < 56; p++) {
         uint64_t v = obs_plane(p, me, &S[0][0], e.seatw[me * h->B] & 7u, G) & K_ALL;
