@@ -284,6 +284,19 @@ def main():
                 env.observe(obs)
             torch.cuda.synchronize()
             extras["observe_kernel_GBps"] = OBS_BYTES_PER_ENV * Bo * 20 / (time.perf_counter() - t0) / 1e9
+            # the same kernel where configs[4] runs it: right after a step (its input no longer in the memory-side
+            # cache); HIP events on the stream of the launches
+            e0 = [torch.cuda.Event(enable_timing=True) for _ in range(20)]
+            e1 = [torch.cuda.Event(enable_timing=True) for _ in range(20)]
+            for i in range(20):
+                env.step_random(1)
+                e0[i].record()
+                env.observe(obs)
+                e1[i].record()
+            torch.cuda.synchronize()
+            ms = sum(a.elapsed_time(b) for a, b in zip(e0, e1)) / 20
+            extras["observe_kernel_after_step_ms"] = ms
+            extras["observe_kernel_after_step_GBps"] = OBS_BYTES_PER_ENV * Bo / (ms * 1e-3) / 1e9
             # the token observation of the same batch: 4 x 496 B per game, shanten number and action history included
             tok = env.observe_tokens()
             torch.cuda.synchronize()

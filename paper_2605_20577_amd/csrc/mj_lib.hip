@@ -802,16 +802,19 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
   static_assert(sizeof(ObsRaw) <= sizeof(uint32_t) * kObsEnvs * 4 * kObsWords, "the raw copy fits under the bit strings");
   const int tid = threadIdx.x;
   const int64_t n_groups = (B + kObsEnvs - 1) / kObsEnvs;
+  // The counter's value g stands for environments (n_groups - 1 - g) * 32 ..: from the end of the batch down, so that a
+  // launch that follows a step starts with the environments that the step wrote last (what the memory-side cache
+  // still holds): 1.60 -> 1.57 ms at B = 2^20.
   if (tid == 0) next_group = atomicAdd(&ctr[0], 1u);
   __syncthreads();
   int64_t grp = next_group;
   ObsFetch f;
   if (grp < n_groups) {
-    const int64_t base = grp * kObsEnvs;
+    const int64_t base = (n_groups - 1 - grp) * kObsEnvs;
     obs_fetch(state, B, base, (int)((B - base) < kObsEnvs ? (B - base) : kObsEnvs), tid, f);
   }
   while (grp < n_groups) {
-    const int64_t base = grp * kObsEnvs;
+    const int64_t base = (n_groups - 1 - grp) * kObsEnvs;
     const int nenv = (int)((B - base) < kObsEnvs ? (B - base) : kObsEnvs);
     unsigned taken = 0;
     if (tid == 0) taken = atomicAdd(&ctr[0], 1u);      // the group after this one; its answer is needed only below
@@ -855,7 +858,7 @@ __global__ void __launch_bounds__(kAuxBlock) k_observe(void *state, int64_t B, u
     __syncthreads();
     const int64_t nxt = next_group;
     if (nxt < n_groups) {
-      const int64_t nb = nxt * kObsEnvs;
+      const int64_t nb = (n_groups - 1 - nxt) * kObsEnvs;
       obs_fetch(state, B, nb, (int)((B - nb) < kObsEnvs ? (B - nb) : kObsEnvs), tid, f);
     }
     // 7616 bytes per env = 476 stores of 16 bytes; 16 bytes = 16 bits of the string
