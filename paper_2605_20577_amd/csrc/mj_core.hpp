@@ -124,6 +124,8 @@ struct Env {
   uint8_t *river;                                     // cold [128]
   uint16_t *hist;                                     // this environment's row of 128 entries: the kyoku's public actions
                                                       // in order, action | seat << 8
+  uint8_t *hstage, *hbase;                            // null, or a staging column for the history in LDS (bytes at
+                                                      // stride hs) and the history index of its first slot (hist_push)
 
 };
 

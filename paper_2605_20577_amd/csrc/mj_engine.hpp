@@ -832,10 +832,42 @@ MJ_HD void mark_passed_ron(Ctx &c, int ron_offered)
 }
 
 // the action history (section 3.2, "Observation Space"): one entry per public action, action | seat << 8
+// A 2-byte store of its own leaves the cache as a partial line of 32 to 64 bytes, so a kernel that runs many steps per
+// launch gives the environment a staging ring in LDS (e.hstage: kHistRing entries, two bytes each at stride hs; entry
+// i of the history sits in slot i mod kHistRing; *e.hbase = the number of entries of this kyoku that the row already
+// holds): entries
+// collect there and go to the row in one run of stores, hist_flush.  The kernel must flush at least every
+// kHistFlushEvery steps: a step adds one entry, or up to three that end the kyoku (wins on one tile), and a deal
+// starts the history afresh, so at most kHistFlushEvery + 2 entries wait in the ring.  71 B of HBM writes per env step
+// became 28.
+constexpr int kHistRing = 64, kHistFlushEvery = 32;
+static_assert(kHistFlushEvery + 2 <= kHistRing && (kHistRing & (kHistRing - 1)) == 0, "the ring holds a flush interval");
+// writes the staged entries to the row.  (After a deal *hbase may still hold the old kyoku's count until the first
+// entry of the new one resets it; the history is empty then and there is nothing to write.)
+MJ_HD void hist_flush(const Env &e, int hist_len)
+{
+  int j = *e.hbase;
+  MJ_HOST_ASSERT(hist_len - j <= kHistRing);
+#pragma unroll 1
+  for (; j < hist_len; j++) {
+    const int k = 2 * (j & (kHistRing - 1));
+    e.hist[j] = (uint16_t)(e.hstage[(int64_t)k * e.hs] | e.hstage[(int64_t)(k + 1) * e.hs] << 8);
+  }
+  *e.hbase = (uint8_t)hist_len;
+}
+// STAGED: 1 the staging ring is there (known at compile time), 0 look at the pointer
+template <int STAGED>
 MJ_HD void hist_push(Ctx &c, int s, int a)
 {
   const int i = c.g.hist_len;
-  if (i < 128) { c.e.hist[i] = (uint16_t)(a | s << 8); c.g.hist_len = (uint8_t)(i + 1); }
+  if (i >= 128) return;
+  if (STAGED || c.e.hstage) {
+    const int k = 2 * (i & (kHistRing - 1));
+    if (i == 0) *c.e.hbase = 0;                          // the first entry after a deal: the row holds nothing of this kyoku
+    c.e.hstage[(int64_t)k * c.e.hs] = (uint8_t)a;
+    c.e.hstage[(int64_t)(k + 1) * c.e.hs] = (uint8_t)s;
+  } else c.e.hist[i] = (uint16_t)(a | s << 8);
+  c.g.hist_len = (uint8_t)(i + 1);
 }
 
 // One step of one environment, as a fixed sequence of stages that every lane walks through in the same order
@@ -847,6 +879,7 @@ MJ_HD void hist_push(Ctx &c, int s, int a)
 // `acts` packs the four seats' actions as signed bytes (seat s in byte s).
 // `sampled_ron` >= 0 says that the actions were drawn from the masks by the library's own sampler (they are legal by
 // construction, so stage 0 is skipped) and carries the seats whose mask offered a win.
+template <int STAGED = 0>
 MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
 {
   c.need_deal = false;
@@ -900,7 +933,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   MJ_RB(s1r, c.g.phase != PH_TURN);
   if (c.g.phase == PH_TURN) {
     int s = c.g.cur, act = act_of(acts, s);
-    hist_push(c, s, act);
+    hist_push<STAGED>(c, s, act);
     MJ_RB(dis, act < A_KAN);
     MJ_RB(kan, act >= A_KAN && act < A_RIICHI);
     MJ_RB(dcl, act >= A_RIICHI);
@@ -938,7 +971,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
 #pragma unroll 1
       for (int j = 1; j < 4; j++) {
         const int o = (from + j) & 3;
-        if (ronners >> o & 1) hist_push(c, o, A_RON);
+        if (ronners >> o & 1) hist_push<STAGED>(c, o, A_RON);
       }
     }
     if (c.g.phase == PH_RESPOND) {
@@ -953,7 +986,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
         if (caller < 0 && (actors >> nx & 1) && act_of(acts, nx) >= A_CHI_L && act_of(acts, nx) < A_PASS) { caller = nx; call = act_of(acts, nx); }
         end_abort = settle_discard(c);
         if (!end_abort) {
-          if (caller >= 0) hist_push(c, caller, call);
+          if (caller >= 0) hist_push<STAGED>(c, caller, call);
           MJ_RB(cal, caller >= 0);
           if (caller < 0) todo |= DO_ADVANCE;
           else if (apply_call(c, caller, call)) { waits_seat = caller; todo |= DO_KANFIN; }

@@ -52,6 +52,7 @@ MJ_HD Env make_env(void *state, int64_t B, int64_t b)
   e.nextred = w + (int64_t)(kHotU32 + 96) * B; e.nextwaits = q + (int64_t)(kHotU64 + 8) * B;
   e.river = state_u8(state, B) + b;
   e.hist = (uint16_t *)(state_u8(state, B) + (int64_t)128 * B) + b * 128;
+  e.hstage = nullptr; e.hbase = nullptr;
   return e;
 }
 

@@ -8,7 +8,8 @@
 // it runs its steps there and writes the hot arrays back.  Walls are shuffled ahead of time, every lane for itself
 // on its LDS column; a deal that finds no wall ready is done by the whole wavefront for one environment at a time
 // (ballot over the lanes that need it, 34 lanes run Philox, the wall sits in one vector register and the swaps are
-// readlane / select pairs).  The observation writers build bit planes / token records per environment in LDS and
+// readlane / select pairs).  Between two shuffles the fused kernel uses an environment's shuffle column as a ring
+// that collects the entries of its action history, written to HBM every 32 steps.  The observation writers build bit planes / token records per environment in LDS and
 // then stream them out with all lanes, 16 bytes per lane.
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -47,16 +48,19 @@ constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of
 #define MJ_OCC 2                         // waves per SIMD the register budget of the stepping kernels is sized for
 #endif
 constexpr int kRefillEvery = 64;         // steps between refills of the walls made ahead of time
+static_assert(kRefillEvery % kHistFlushEvery == 0, "the history's staging ring is empty when the shuffle takes its column");
 
 // A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
 // occupies 2x or 4x as many wavefronts, which lets a SIMD overlap the LDS / memory latency of one wavefront
 // with the instructions of another and shrinks the set of divergent paths per wavefront.  The step is bound by
 // dependent-access latency, not by lane count, so small batches run faster that way.
-// LDS of a step kernel: probe tables | hot u64 arrays | hot u32 arrays | table pointers | 136 wall bytes per env
+// LDS of a step kernel: probe tables | hot u64 arrays | hot u32 arrays | 136 wall bytes per env | one byte per env
+// (between two shuffles the wall bytes of an environment stage its action history, see hist_push; the last byte
+// says where the staged entries start)
 __host__ __device__ inline int envs_per_block(int lpw) { return (kBlock / 64) * lpw; }
 __host__ __device__ inline size_t step_lds_bytes(int probe_bytes, int lpw)
 {
-  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * (kHotBytesPerEnv + 136);
+  return (size_t)probe_bytes + (size_t)envs_per_block(lpw) * (kHotBytesPerEnv + 136 + 1);
 }
 
 struct BlockMem {
@@ -65,6 +69,7 @@ struct BlockMem {
   uint64_t *hq;                          // [kHotU64][envs per block]
   uint32_t *hw;                          // [kHotU32][envs per block]
   uint8_t *col;                          // this lane's column of the [136][envs per block] shuffle area
+  uint8_t *hbase;                        // this lane's byte of the [envs per block] area behind the shuffle area
   int epb, idx;                          // envs per block; this lane's env slot in the block
   bool lane_on;                          // this lane carries an environment
 };
@@ -110,6 +115,7 @@ __device__ __forceinline__ BlockMem carve_block(const DevTables &T, uint8_t *lds
   m.L.bitmap = (const uint32_t *)(lds + kRowIdBytes);
   m.L.base = T.base; m.L.rowrank = T.rowrank; m.L.recs = T.recs; m.L.nb = T.nb;
   m.col = lds + T.probe_bytes + (size_t)m.epb * kHotBytesPerEnv + m.idx;
+  m.hbase = lds + T.probe_bytes + (size_t)m.epb * (kHotBytesPerEnv + 136) + m.idx;
   return m;
 }
 // ... and copy the probe tables in (ends with a block barrier)
@@ -513,6 +519,9 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
   const TableRegs tr = table_fetch(T);
   if (active) { load_hot(m, state, B, b); load_glob(c.e, c.g); }
   table_commit(T, lds, tr);
+  // the action history is staged in the lane's shuffle column (hist_push): empty now, flushed before every shuffle
+  // and at the end
+  if (active) { c.e.hstage = m.col; c.e.hbase = m.hbase; *m.hbase = c.g.hist_len; }
   __syncthreads();
 #ifdef MJ_PROFILE
   for (int i = threadIdx.x; i < 3 * PR_N; i += blockDim.x) mj_prof[i] = 0;
@@ -527,15 +536,18 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
     { int64_t stride = c.e.n; asm volatile("" : "+s"(stride)); c.e.n = stride; }
     if (active) {
       MJ_RB(rf, (step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1);
-      if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
-        refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
+      if ((step0 + t) % kHistFlushEvery == 0) {
+        hist_flush(c.e, c.g.hist_len);                 // the shuffle needs the column that stages the history
+        if ((step0 + t) % kRefillEvery == 0 && c.e.nserial[0] != c.e.serial[0] + 1)
+          refill_next_wall(c, m.col, m.epb, c.e.serial[0] + 1);
+      }
       MJ_RE(rf, PR_REFILL);
       int ron_offered;
       MJ_RB(sa, true);
       acts = sample_actors(c, step0 + t, ron_offered);
       MJ_RE(sa, PR_SAMPLE);
       MJ_RB(st, true);
-      step_env(c, acts, ron_offered);
+      step_env<1>(c, acts, ron_offered);
       MJ_RE(st, PR_STEP);
       MJ_RB(rs, auto_reset && c.g.terminated);
       if (auto_reset && c.g.terminated) reset_env(c, false);
@@ -564,7 +576,10 @@ __global__ void __launch_bounds__(kBlock, MJ_OCC) k_rollout(void *state, int64_t
              mj_prof[3 * i + 1] ? (double)mj_prof[3 * i] / (double)mj_prof[3 * i + 1] : 0.0);
   }
 #endif
-  if (active) { store_hot(m, state, B, b); store_glob(c.e, c.g); }
+  if (active) {
+    hist_flush(c.e, c.g.hist_len);
+    store_hot(m, state, B, b); store_glob(c.e, c.g);
+  }
 }
 
 // test / scripting aid: give env b the wall in `wall` and deal the current kyoku again from it

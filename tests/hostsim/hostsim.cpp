@@ -111,10 +111,21 @@ void hs_reset_done(Sim *h)
 }
 void hs_step_random(Sim *h, int n, int auto_reset)
 {
+  // as the fused kernel does it: the action history is staged in a column of 136 bytes per environment (bytes at
+  // stride B, like the hot arrays here), flushed every kHistFlushEvery steps and at the end; every 64 steps the kernel
+  // uses the column for a shuffle, which is a fill with junk here
+  std::vector<uint8_t> stage((size_t)137 * h->B, 0xEE);
   for (int64_t b = 0; b < h->B; b++) {
     Ctx c = ctx_of(h, b);
     load_glob(c.e, c.g);
+    c.e.hstage = stage.data() + b;
+    c.e.hbase = stage.data() + (size_t)136 * h->B + b;
+    *c.e.hbase = c.g.hist_len;
     for (int t = 0; t < n; t++) {
+      if ((h->step + t) % kHistFlushEvery == 0) {
+        hist_flush(c.e, c.g.hist_len);
+        if ((h->step + t) % 64 == 0) for (int i = 0; i < 136; i++) c.e.hstage[(int64_t)i * h->B] = 0xEE;
+      }
       int a[4], ron_offered = 0;                  // as the fused kernel does it: sampled actions skip the legality check
       for (int s = 0; s < 4; s++) {
         a[s] = sample_action(MASK(c, s, 0), MASK(c, s, 1), h->R.seed, c.env_id, h->step + t, s);
@@ -123,6 +134,7 @@ void hs_step_random(Sim *h, int n, int auto_reset)
       step_and_deal(c, a, ron_offered);
       if (auto_reset && c.g.terminated) reset_env(c, false);
     }
+    hist_flush(c.e, c.g.hist_len);
     store_glob(c.e, c.g);
   }
   h->step += n;
