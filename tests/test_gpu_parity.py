@@ -456,3 +456,33 @@ def test_fused_steps_with_observation_every_step(B):
     # the separate entry point still agrees
     assert np.array_equal(o.observe(), g.observe())
     g.close()
+
+
+@pytest.mark.parametrize("mode,auto_reset", [(mjo.MODE_HALF, True), (mjo.MODE_SINGLE, False)])
+def test_action_history_across_launches(mode, auto_reset):
+    """The fused kernel collects a game's action history in LDS and writes it out every 32 steps, before a shuffle
+    takes the column, and at the end of a launch; the one-step kernels store entry by entry.  Launches of every length
+    around those intervals, mixed with step-at-a-time calls, restarts inside a launch and games that stay finished:
+    the history of the record and of the token observation against the oracle after each."""
+    B = 700
+    o = mjo.Oracle(B, 23, mjo.RULES_RED, mode)
+    g = GpuEngine(B, seed=23, flags=mjo.RULES_RED, mode=mode)
+    def check(tag):
+        a, b = o.export(), g.export()
+        assert np.array_equal(a["n_hist"], b["n_hist"]), tag
+        assert np.array_equal(a["hist"], b["hist"]), tag
+        d = diff_records(a, b)
+        assert not d, (tag, d[:4])
+        want = o.observe_tokens()
+        got = g.env.observe_tokens().cpu().numpy().reshape(B, 4, -1).view(mjo.TOKEN_DTYPE).reshape(B, 4)
+        assert np.array_equal(want["n_hist"], got["n_hist"]) and np.array_equal(want["hist"], got["hist"]), tag
+    for n in (1, 2, 29, 1, 31, 32, 33, 1, 63, 64, 65, 7, 130, 1, 1, 250):
+        o.step_random(n, auto_reset); g.env.step_random(n, auto_reset)
+        check(("fused", n))
+        for _ in range(3):                                        # step-at-a-time calls in between
+            a = o.sample_random()
+            o.step(a); g.step(a)
+            if auto_reset:
+                o.reset_done(); g.reset_done()
+        check(("stepwise after", n))
+    assert o.export()["n_hist"].max() > 40
