@@ -253,9 +253,10 @@ int mj_sample_random(const MjHandle *h, int8_t *d_actions /*[B][4]*/, void *stre
  * write d_obs if write_obs }.  Equivalent to the unfused calls, state by
  * state.  d_obs may be NULL when write_obs is 0.  Without observations up to
  * MJ_ROLLOUT_CHUNK steps run inside one kernel launch (environments never
- * interact); with observations every step is one step launch plus one
- * observation launch. */
-#define MJ_ROLLOUT_CHUNK 1024
+ * interact; fewer for batches above 131,072 games, so that a launch stays
+ * below about 0.1 s); with observations every step is one step launch plus
+ * one observation launch. */
+#define MJ_ROLLOUT_CHUNK 4096
 int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, uint8_t *d_obs, void *stream);
 
 /* canonical records of envs [env_lo, env_lo + n) to / from DEVICE memory */

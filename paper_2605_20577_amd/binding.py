@@ -12,7 +12,7 @@ RULES_NORED = F_KUITAN | F_MULTIRON
 RULES_RED = F_RED | F_ABORT | F_KUITAN | F_MULTIRON
 MODE_SINGLE, MODE_EAST, MODE_HALF = 0, 1, 2
 NUM_ACTIONS = 85
-ROLLOUT_CHUNK = 1024          # MJ_ROLLOUT_CHUNK of include/mj.h: steps per launch of the fused path
+ROLLOUT_CHUNK = 4096          # MJ_ROLLOUT_CHUNK of include/mj.h: steps per launch of the fused path
 
 # numpy views of the records of include/mj.h
 ENV_DTYPE = np.dtype([

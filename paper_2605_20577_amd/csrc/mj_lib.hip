@@ -1292,9 +1292,11 @@ int mj_step_random(MjHandle *h, int32_t n_steps, int auto_reset, int write_obs, 
     // environments never interact, so many steps run inside one launch; chunked to bound a launch's duration.
     // Long launches matter at B = 65,536: all 2,048 wavefronts are resident at once, a launch ends with its
     // slowest wavefront, and the spread of per-wavefront work shrinks with the number of steps (measured:
-    // 128 / 256 / 512 / 1024 / 2048 steps per launch = 6.26 / 6.44 / 6.58 / 6.67 / 6.69 G env steps/s).
-    // MJ_CHUNK overrides the length for experiments.
+    // 128 / 256 / 512 / 1024 / 2048 steps per launch = 6.26 / 6.44 / 6.58 / 6.67 / 6.69 G env steps/s on an earlier
+    // build, 1024 / 2048 / 4096 = 7.13 / 7.19 / 7.23 G on this one).  4,096 steps of 65,536 games take 37 ms; larger
+    // batches get proportionally shorter launches.  MJ_CHUNK overrides the length for experiments.
     int chunk = MJ_ROLLOUT_CHUNK;
+    while (chunk > 256 && (int64_t)chunk * h->B > (int64_t)MJ_ROLLOUT_CHUNK * 131072) chunk /= 2;
     if (const char *cv = std::getenv("MJ_CHUNK")) { int v = std::atoi(cv); if (v > 0) chunk = v; }
     // A batch of up to six times what the machine holds at once (4 blocks per compute unit) can go out in slices of
     // that size (the last one smaller), one launch each.  Measured in units of one full slice's time: a single launch
