@@ -51,3 +51,15 @@ def test_binding_constants_mirror_the_header():
     import paper_2605_20577_amd as mj
     text = open(os.path.join(os.path.dirname(__file__), "..", "include", "mj.h")).read()
     assert int(re.search(r"#define\s+MJ_ROLLOUT_CHUNK\s+(\d+)", text).group(1)) == mj.ROLLOUT_CHUNK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """this build runs on one GPU: bench.py --gpus N with N > 1 says so and exits without touching a device"""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2", "--steps", "1", "--warmup", "0"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
