@@ -48,6 +48,10 @@ constexpr int kRowIdBytes = 3136;        // 3125 row ids padded to a multiple of
 #define MJ_OCC 2                         // waves per SIMD the register budget of the stepping kernels is sized for
 #endif
 constexpr int kRefillEvery = 64;         // steps between refills of the walls made ahead of time
+#ifndef MJ_STEP_REFILL
+#define MJ_STEP_REFILL 32
+#endif
+constexpr int kStepRefillEvery = MJ_STEP_REFILL;   // the same for the one-step kernels
 static_assert(kRefillEvery % kHistFlushEvery == 0, "the history's staging ring is empty when the shuffle takes its column");
 
 // A step kernel may leave lanes of each wavefront idle: with LPW (lanes per wave) of 32 or 16 the same batch
@@ -1205,7 +1209,7 @@ int mj_init(MjHandle **out, void *d_state, void *d_scratch, int64_t B, uint64_t 
 int mj_step(MjHandle *h, const int8_t *d_actions, void *stream)
 {
   if (!h || !d_actions || ((uintptr_t)d_actions & 3)) return MJ_E_ARG;
-  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kRefillEvery == 0), 0,
+  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kStepRefillEvery == 0), 0,
                  StepOut{nullptr, nullptr, nullptr, nullptr});
   h->step++;
   return check(hipGetLastError());
@@ -1217,7 +1221,7 @@ int mj_step_full(MjHandle *h, const int8_t *d_actions, int auto_reset, uint64_t 
   if (!h || !d_actions || ((uintptr_t)d_actions & 3) || ((uintptr_t)d_mask & 15) || ((uintptr_t)d_delta & 15) ||
       ((uintptr_t)d_reward & 15))
     return MJ_E_ARG;
-  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kRefillEvery == 0),
+  MJ_LAUNCH_STEP(k_step, h, (hipStream_t)stream, h->d_state, h->B, h->R, h->T, d_actions, (int)(h->step % kStepRefillEvery == 0),
                  auto_reset ? 1 : 0, StepOut{d_mask, d_delta, d_reward, d_terminated});
   h->step++;
   return check(hipGetLastError());
