@@ -233,7 +233,7 @@ MJ_HD void turn_mask(Ctx &c)
   TD(c) = (exact || riichi ? td | TD_VALID : 0) | (uint64_t)facts << FACTS_SHIFT | TD_FACTS;
   MJ_RE(tme, PR_TM_EXACT);
   MJ_RB(tmt, !c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1));
-  if (!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1)) {
+  if (MJ_RARE(!c.g.riichi_pending && drawn_k >= 0 && (waits >> drawn_k & 1))) {
     if (sure_yaku(c, s, true, false)) set_action(m, A_TSUMO);
     else {
       MJ_STAT(n_tsumo_eval);
@@ -636,7 +636,7 @@ MJ_HD bool ron_option(Ctx &c, int o, int k, bool chankan)
   if (!(WAITS(c, o) >> k & 1)) return false;
   bool ok = false;
   if (!furiten(c, o)) {
-    if (sure_yaku(c, o, false, chankan)) ok = true;
+    if (MJ_USUAL(sure_yaku(c, o, false, chankan))) ok = true;
     else {
       MJ_STAT(n_ron_eval);
       HandOut r;
@@ -1097,7 +1097,7 @@ MJ_HD void step_env(Ctx &c, uint32_t acts, int sampled_ron = -1)
   MJ_RB(win, win_mask != 0);
   MJ_RB(abo, !win_mask && end_abort);
   MJ_RB(exh, !win_mask && !end_abort && exhaust);
-  if (win_mask) win(c, win_mask, (todo & WIN_TSUMO) != 0, win_loser, win_tile, (todo & WIN_ROB) != 0);
+  if (MJ_RARE(win_mask != 0)) win(c, win_mask, (todo & WIN_TSUMO) != 0, win_loser, win_tile, (todo & WIN_ROB) != 0);
   else if (end_abort) abortive_draw(c, end_abort);
   else if (exhaust) exhaustive_draw(c);
   MJ_RE(win, PR_WIN);
