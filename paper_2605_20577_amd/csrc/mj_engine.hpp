@@ -605,6 +605,7 @@ MJ_HD void kan_draw(Ctx &c, bool open)
 MJ_HD int settle_discard(Ctx &c)
 {
   int d = c.g.last_discarder;
+  const bool riichi_now = c.g.riichi_pending != 0;
   if (c.g.riichi_pending) {
     credit(c, d, -1000);
     c.g.kyotaku++;
@@ -617,14 +618,18 @@ MJ_HD int settle_discard(Ctx &c)
   }
   if (c.R.flags & F_ABORT) {
     if (c.g.same_wind_cnt == 4) return 5;
-    bool all_riichi = true, one_seat = false;
-    for (int s = 0; s < 4; s++) {
-      uint32_t sw = SW(c, s);
-      if (!sw_get(sw, SW_RIICHI, 2)) all_riichi = false;
-      if (sw_get(sw, SW_KANBY, 3) == 4) one_seat = true;
+    // four riichi can only become true with the riichi that this discard establishes, four kans only with four kans
+    // on the table: the seats' words are looked at in those two cases only
+    if (MJ_RARE(riichi_now || c.g.n_kan == 4)) {
+      bool all_riichi = true, one_seat = false;
+      for (int s = 0; s < 4; s++) {
+        uint32_t sw = SW(c, s);
+        if (!sw_get(sw, SW_RIICHI, 2)) all_riichi = false;
+        if (sw_get(sw, SW_KANBY, 3) == 4) one_seat = true;
+      }
+      if (all_riichi) return 6;
+      if (c.g.n_kan == 4 && !one_seat) return 7;
     }
-    if (all_riichi) return 6;
-    if (c.g.n_kan == 4 && !one_seat) return 7;
   }
   return 0;
 }
