@@ -212,6 +212,59 @@ def test_abortive_draws(engine):
     assert A_KYUUSHU not in bits(o.export()[0]["mask"][0])
 
 
+def test_four_riichi_and_four_kans(engine):
+    """the two abortive draws that depend on all four seats: four riichi (ends the kyoku when the fourth declaration's
+    discard has gone unclaimed, its stick paid) and four kans by more than one seat (ends it after the discard that
+    follows the fourth kan)"""
+    flags = mjo.RULES_NORED | mjo.F_ABORT
+    o = engine(flags=flags, mode=mjo.MODE_HALF)
+    hands = [TENPAI, TENPAI2, "567m 34p 789p 44s 234s", "123m 789m 123s 99s 56s"]
+    o.deal_from_wall(0, build_wall(hands, draws="1z 2z 3z 4z 5z"))
+    e = None
+    for s, t in enumerate(("1z", "2z", "3z", "4z")):
+        e = act(o, 0, {s: A_RIICHI})
+        e = act(o, 0, {s: kind(t)})
+        if s < 3:
+            assert e["end_type"] == 0 and e["kyotaku"] == s + 1 and e["cur"] == s + 1 and e["kyoku_serial"] == 0
+    # every seat has paid its stick; nobody gets them back; the dealer stays, one counter more, a new deal
+    assert e["end_type"] == 6 and e["honba"] == 1 and e["kyoku"] == 0 and e["kyoku_serial"] == 1 and e["kyotaku"] == 4
+    assert e["score"].tolist() == [24000] * 4 and e["delta"].tolist() == [0, 0, 0, -1000] and e["terminated"] == 0
+    # three riichi and an ordinary discard by the fourth seat: the kyoku goes on
+    o = engine(flags=flags, mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, build_wall(hands, draws="1z 2z 3z 4z 5z"))
+    for s, t in enumerate(("1z", "2z", "3z")):
+        act(o, 0, {s: A_RIICHI})
+        act(o, 0, {s: kind(t)})
+    e = act(o, 0, {3: kind("4z")})
+    assert e["end_type"] == 0 and e["kyoku_serial"] == 0 and e["cur"] == 0 and e["kyotaku"] == 3
+
+    # two concealed kans each by seats 0 and 1: the discard after the fourth kan ends the kyoku
+    o = engine(flags=flags, mode=mjo.MODE_HALF)
+    o.deal_from_wall(0, build_wall(["1111m 4444m 345p 78p", "3333s 6666s 77m 789p", J2, J3], draws="1z 2z",
+                                   rinshan="5z 6z 7z 3z"))
+    e = act(o, 0, {0: A_KAN + kind("1m")})
+    e = act(o, 0, {0: A_KAN + kind("4m")})
+    e = act(o, 0, {0: kind("1z")})
+    assert e["end_type"] == 0 and e["n_kan"] == 2 and e["cur"] == 1
+    e = act(o, 0, {1: A_KAN + kind("3s")})
+    e = act(o, 0, {1: A_KAN + kind("6s")})
+    assert e["n_kan"] == 4 and e["end_type"] == 0 and A_KAN + kind("5z") not in bits(e["mask"][1])
+    e = act(o, 0, {1: kind("2z")})
+    assert e["end_type"] == 7 and e["honba"] == 1 and e["kyoku"] == 0 and e["kyoku_serial"] == 1
+    assert (e["delta"] == 0).all() and e["score"].tolist() == [25000] * 4
+    # all four kans by one seat: no abortive draw
+    o = engine(flags=flags, mode=mjo.MODE_HALF)
+    others = ["456789p 1234567s", "456789m 123p 89s 77z", "456m 789m 456p 789p 1s"]
+    o.deal_from_wall(0, build_wall(["1111m 2222m 3333m 4z"] + others, draws="4z 2z", rinshan="4z 4z 5z 6z"))
+    e = act(o, 0, {0: A_KAN + kind("1m")})
+    e = act(o, 0, {0: A_KAN + kind("2m")})
+    e = act(o, 0, {0: A_KAN + kind("3m")})
+    e = act(o, 0, {0: A_KAN + kind("4z")})
+    assert e["n_kan"] == 4
+    e = act(o, 0, {0: kind("5z")})
+    assert e["end_type"] == 0 and e["kyoku_serial"] == 0 and e["cur"] == 1
+
+
 def test_bust_ends_the_game(engine):
     o = engine(mode=mjo.MODE_HALF)
     o.deal_from_wall(0, build_wall(["5p " + J1[1:], TENPAI, J2, J3], draws="1m", dora="1z"))
