@@ -486,3 +486,26 @@ def test_action_history_across_launches(mode, auto_reset):
                 o.reset_done(); g.reset_done()
         check(("stepwise after", n))
     assert o.export()["n_hist"].max() > 40
+
+
+@pytest.mark.skipif(not __import__("os").environ.get("MJ_TEST_HUGE"),
+                    reason="4.5 minutes of host time: set MJ_TEST_HUGE=1 to run it")
+def test_largest_batch_every_game():
+    """every one of 2^20 games (red rules, hanchan) after 600 fused steps, in launches of 512 steps as the library
+    chooses for this batch size, field by field against the oracle (128 shards of 8,192 games on 16 host threads)"""
+    from concurrent.futures import ThreadPoolExecutor
+    B, steps, shard = 1 << 20, 600, 8192
+    g = GpuEngine(B, seed=5, flags=mjo.RULES_RED, mode=mjo.MODE_HALF)
+    g.step_random(steps)
+    got = g.export()
+
+    def run(i):
+        lo, hi = i * shard, (i + 1) * shard
+        o = mjo.Oracle(hi - lo, 5, mjo.RULES_RED, mjo.MODE_HALF, env_id_base=lo)
+        o.step_random(steps)
+        d = diff_records(o.export(), got[lo:hi])
+        o.close()
+        return i, d
+    with ThreadPoolExecutor(16) as ex:
+        for i, d in ex.map(run, range(B // shard)):
+            assert not d, (i, d[:4])
