@@ -509,3 +509,5 @@ def test_largest_batch_every_game():
     with ThreadPoolExecutor(16) as ex:
         for i, d in ex.map(run, range(B // shard)):
             assert not d, (i, d[:4])
+            if i % 16 == 15:
+                print("largest batch: %d of %d shards identical" % (i + 1, B // shard), flush=True)   # seen with -s
